@@ -1,0 +1,243 @@
+/*
+ * pipemax.h -- C ABI of the MI355X (gfx950) stage-decode library.
+ *
+ * One `pipemax_stage_t` is one pipeline stage: a contiguous slice of Llama-style
+ * decoder layers that runs the decode step of ONE active micro-batch at a time
+ * (PipeMax Sec. 2.3.2: under pipeline parallelism each GPU executes one decode
+ * batch at a time and the KV cache of the other batches sits idle), while the KV
+ * caches of the inactive micro-batches live in pinned host memory and are
+ * prefetched / written back on side HIP streams (Sec. 3, Sec. 3.3.2 Eq. 3,
+ * Sec. 3.4.2).
+ *
+ * Conventions
+ *  - Every call returns a pipemax_status_t (0 = OK, negative = error) and never
+ *    throws.  `pipemax_last_error()` gives a thread-local text for the last
+ *    failing call.  Argument and state errors are detected on the host before
+ *    anything is enqueued and leave the stage unchanged.
+ *  - "host" pointers are ordinary host memory owned by the caller and are read or
+ *    written before the call returns.  "device" pointers are HIP device memory
+ *    owned by the caller (e.g. PyTorch tensors) on the stage's device; the work on
+ *    them is enqueued on the stream given to the call.
+ *  - The stage owns its weights, the GPU page pool, the pinned host page pool, the
+ *    staging buffers, two side streams (host->device and device->host) and all
+ *    events.  prefetch / decode_step / evict enqueue work and return; ordering
+ *    between them is the library's job (events), not the caller's.
+ *  - One caller thread per stage.
+ *  - Canonical tensor layouts are row-major, in the stage's element type
+ *    (float for PIPEMAX_F32, bfloat16 bit patterns for PIPEMAX_BF16).  The
+ *    physical layout inside a KV page is internal (it is chosen so that the
+ *    attention kernel's loads land directly in matrix-core operand order).
+ */
+#ifndef PIPEMAX_H
+#define PIPEMAX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pipemax_stage pipemax_stage_t;   /* opaque */
+typedef struct pipemax_pool  pipemax_pool_t;    /* opaque, host-only page allocator (tests) */
+
+typedef enum {
+  PIPEMAX_OK                 =  0,
+  PIPEMAX_ERR_ARG            = -1,  /* bad argument / shape / index                       */
+  PIPEMAX_ERR_OOM_DEVICE     = -2,  /* hipMalloc failed                                   */
+  PIPEMAX_ERR_OOM_HOST       = -3,  /* pinned host allocation failed                      */
+  PIPEMAX_ERR_NOT_RESIDENT   = -4,  /* decode_step on a sequence that is host-resident    */
+  PIPEMAX_ERR_POOL_EXHAUSTED = -5,  /* not enough free pages (GPU or host pool)           */
+  PIPEMAX_ERR_HIP            = -6,  /* a HIP runtime call failed                          */
+  PIPEMAX_ERR_STATE          = -7   /* call not valid in this state (e.g. max_ctx reached) */
+} pipemax_status_t;
+
+enum { PIPEMAX_F32 = 0, PIPEMAX_BF16 = 1 };
+
+/* which = argument of pipemax_set_weight; canonical shapes ("y = x @ W"):        */
+enum {
+  PIPEMAX_W_QKV  = 0,  /* [hidden][(Hq + 2 Hkv) * d]  columns: q heads, k heads, v heads */
+  PIPEMAX_W_O    = 1,  /* [Hq * d][hidden]                                               */
+  PIPEMAX_W_GU   = 2,  /* [hidden][2 * ffn]           columns: gate, then up             */
+  PIPEMAX_W_D    = 3,  /* [ffn][hidden]                                                  */
+  PIPEMAX_G_ATTN = 4,  /* [hidden]  RMSNorm gain before attention                        */
+  PIPEMAX_G_FFN  = 5   /* [hidden]  RMSNorm gain before the FFN                          */
+};
+
+/* flags of pipemax_config_t */
+enum {
+  PIPEMAX_FLAG_FORCE_GENERIC  = 1,  /* use the shape-generic kernels even where the matrix-core
+                                       kernels apply (diagnostics)                               */
+  PIPEMAX_FLAG_CAPTURE_LAYERS = 2,  /* keep the residual stream after every layer of the last
+                                       decode_step (see pipemax_get_layer_outputs)               */
+  PIPEMAX_FLAG_TIME_KERNELS   = 4,  /* bracket every kernel class and every transfer with HIP
+                                       events and accumulate their durations in the stats        */
+  PIPEMAX_FLAG_NO_WRITEBACK   = 8   /* do not write new K,V through to the host replica
+                                       (compute-only timing runs; evict then loses new tokens)   */
+};
+
+typedef struct {
+  int32_t  n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+  float    rope_base, rms_eps;
+  int32_t  dtype;            /* PIPEMAX_F32 | PIPEMAX_BF16                                   */
+  int32_t  page_tokens;      /* tokens per KV page; must be 16 (Sec. 4.4 uses the same size) */
+  int32_t  n_microbatches;   /* n of Eq. 3                                                   */
+  int32_t  max_seqs_per_mb;  /* upper bound on b                                             */
+  int32_t  max_ctx;          /* upper bound on a sequence's tokens, prompt + generated       */
+  uint64_t gpu_kv_bytes;     /* size of the GPU page pool (rounded down to whole pages)      */
+  uint64_t host_kv_bytes;    /* size of the pinned host page pool                            */
+  int32_t  device;           /* HIP device ordinal                                           */
+  uint32_t flags;            /* PIPEMAX_FLAG_*                                               */
+} pipemax_config_t;
+
+/* kernel classes of the per-class timers (PIPEMAX_FLAG_TIME_KERNELS) */
+enum {
+  PIPEMAX_K_NORM = 0,     /* residual add + RMSNorm                        (steps a1, a7)  */
+  PIPEMAX_K_GEMM_QKV,     /* QKV projection                                (a2)            */
+  PIPEMAX_K_ROPE_APPEND,  /* RoPE + KV append + write-back staging         (a3, a4)        */
+  PIPEMAX_K_ATTN,         /* GQA paged decode attention, split-K pass      (a5)            */
+  PIPEMAX_K_ATTN_MERGE,   /* merge of the split-K partials                 (a5)            */
+  PIPEMAX_K_GEMM_O,       /* output projection                             (a6)            */
+  PIPEMAX_K_GEMM_GU,      /* gate/up projection                            (a8)            */
+  PIPEMAX_K_SWIGLU,       /* SiLU(gate) * up                               (a8)            */
+  PIPEMAX_K_GEMM_D,       /* down projection                               (a9)            */
+  PIPEMAX_K_MISC,         /* hidden load/store, RoPE table, length advance                 */
+  PIPEMAX_N_KCLASS
+};
+
+typedef struct {
+  uint64_t steps;                 /* decode_step calls completed (enqueued)                  */
+  uint64_t tokens;                /* sum of b over those steps                               */
+  uint64_t h2d_bytes, h2d_copies; /* KV prefetch traffic (page copies)                       */
+  uint64_t d2h_bytes, d2h_copies; /* KV write-back traffic (per-layer staging copies)        */
+  uint64_t table_uploads;         /* block-table uploads                                     */
+  uint64_t relayout_jobs;         /* per-layer host re-layout jobs finished by the worker    */
+  double   host_enqueue_s;        /* host time spent inside decode_step                      */
+  double   host_wait_s;           /* host time blocked on the write-back worker              */
+  double   h2d_ms;                /* busy time of prefetch copies   (FLAG_TIME_KERNELS)      */
+  double   d2h_ms;                /* busy time of write-back copies (FLAG_TIME_KERNELS)      */
+  double   kernel_ms[PIPEMAX_N_KCLASS];        /* summed kernel durations per class          */
+  uint64_t kernel_launches[PIPEMAX_N_KCLASS];
+  int32_t  engine;                /* 0 = shape-generic kernels, 1 = matrix-core (bf16) kernels */
+  int32_t  gpu_pages_total, gpu_pages_free, host_pages_total, host_pages_free;
+  uint64_t page_bytes;
+} pipemax_stats_t;
+
+/* ---- life cycle ----------------------------------------------------------------------- */
+
+/* Validates cfg (host pointer), allocates weights, pools, staging, streams and events on
+ * cfg->device and returns the handle in *out.  Errors: ERR_ARG (shape/dtype/page size),
+ * ERR_OOM_DEVICE, ERR_OOM_HOST, ERR_HIP.  Nothing is left allocated on error.            */
+int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out);
+
+/* Drains all work, stops the write-back worker, frees everything.                         */
+int pipemax_stage_destroy(pipemax_stage_t* st);
+
+/* Copies one weight tensor (host pointer, canonical layout above, stage element type,
+ * `bytes` must equal the tensor's size) into the stage; the library re-tiles it into its
+ * internal layout.  Synchronous.                                                          */
+int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* host, size_t bytes);
+
+/* ---- micro-batches and their host-resident KV (Sec. 3.3.2: decode batches D_0..D_{n-1}) - */
+
+/* Defines micro-batch `mb` (0 <= mb < n_microbatches, not yet defined) with n_seqs sequences
+ * whose prompts have ctx_lens[i] cached tokens (host pointer; 0 <= len <= max_ctx).
+ * Allocates ceil(len/16) host pages per sequence, consecutively, lowest index first.
+ * All sequences start HOST-resident.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED.                */
+int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ctx_lens);
+
+/* Writes / reads tokens [tok0, tok0+ntok) of one layer of one sequence in the HOST replica.
+ * K and V are host pointers, canonical layout [ntok][Hkv][d].  Both calls first wait until
+ * all pending write-back of that micro-batch has landed.  Range must lie within the
+ * sequence's current length.  kv_host_write does not touch GPU pages: call it while the
+ * sequence is HOST-resident (ERR_STATE otherwise).                                         */
+int pipemax_kv_host_write(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok,
+                          const void* K, const void* V);
+int pipemax_kv_host_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok,
+                         void* K, void* V);
+/* Same read from the GPU pages (debug / parity).  Synchronises the stage first.
+ * ERR_NOT_RESIDENT if the sequence has no GPU pages.                                      */
+int pipemax_kv_dev_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok,
+                        void* K, void* V);
+
+/* ---- the hot path ---------------------------------------------------------------------- */
+
+/* Prefetch (Sec. 3.3.2, "prefetching KV cache from CPU memory to update D_j"; Sec. 3.4.2,
+ * block-first layout): for every named sequence of `mb` that is HOST-resident, allocates GPU
+ * pages (lowest free index first) and enqueues host->device copies of its pages on the
+ * library's prefetch stream, adjacent (host, GPU) page pairs merged into single copies.
+ * seq_ids: host pointer to n sequence indices, or NULL for all sequences of mb.  Sequences that
+ * already have GPU pages are skipped.  Waits on the host for pending write-back of `mb`
+ * (so that the host replica is complete) and, on the stream, for the last reader of any page
+ * it re-uses.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED (nothing applied), ERR_HIP.             */
+int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n);
+
+/* One decode step of the stage on micro-batch `mb` (the op list of the benchmark spec; cost
+ * structure alpha*b + beta*L + delta of Sec. 3.3.1): for every layer RMSNorm, QKV projection,
+ * RoPE at position L_i, append of the new K,V to page table[i][L_i/16] slot L_i%16, GQA
+ * attention over L_i+1 tokens, output projection + residual, RMSNorm, SwiGLU FFN + residual.
+ * hidden_in / hidden_out: device pointers, [b][hidden] row-major in the stage's element type
+ * (may alias).  hip_stream: the hipStream_t to run on (NULL = the library's own compute
+ * stream).  Each layer's new K,V are also written to a contiguous staging buffer that the
+ * write-back stream copies to pinned host memory, where a worker thread places them into the
+ * host pages (Sec. 3.4.2, asynchronous CPU-assisted offloading).  Afterwards every L_i of mb is
+ * one larger.  New pages (GPU and host) are taken when L_i % 16 == 0.
+ * Errors: ERR_ARG, ERR_NOT_RESIDENT (some sequence of mb has no GPU pages and no prefetch in
+ * flight), ERR_STATE (max_ctx reached), ERR_POOL_EXHAUSTED, ERR_HIP.                       */
+int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
+                        void* hip_stream);
+
+/* Evict (Sec. 3.3.2, "overwriting KV cache blocks associated with the inactive batch D_k"):
+ * releases the GPU pages of the named sequences (NULL = all of mb).  No bulk copy is made: the
+ * host replica is kept current by the per-layer write-back.  Later prefetches into the freed
+ * pages are ordered after the last decode step that read them.  Returns without blocking.  */
+int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n);
+
+/* Blocks until all three streams are idle and the write-back worker has placed every
+ * pending token into the host replica.                                                    */
+int pipemax_sync(pipemax_stage_t* st);
+
+/* ---- introspection ---------------------------------------------------------------------- */
+
+int pipemax_get_stats(pipemax_stage_t* st, pipemax_stats_t* out);   /* synchronises if timing */
+int pipemax_reset_stats(pipemax_stage_t* st);
+
+/* out: host pointer to n_seqs int32 (current context lengths).                             */
+int pipemax_get_ctx_lens(pipemax_stage_t* st, int mb, int32_t* out);
+/* out: host pointer to n_seqs int32: 0 = HOST, 1 = prefetch in flight, 2 = GPU.            */
+int pipemax_get_residency(pipemax_stage_t* st, int mb, int32_t* out);
+/* gpu_pages / host_pages: host pointers with room for *n entries (either may be NULL); on
+ * return *n = number of pages of the sequence; gpu_pages entries are -1 when HOST-resident. */
+int pipemax_get_block_table(pipemax_stage_t* st, int mb, int seq, int32_t* gpu_pages,
+                            int32_t* host_pages, int* n);
+/* Residual stream after every layer of the last decode_step (needs FLAG_CAPTURE_LAYERS):
+ * out = host pointer to [n_layers][b][hidden] float.  Synchronises.                        */
+int pipemax_get_layer_outputs(pipemax_stage_t* st, float* out, size_t bytes);
+
+const char* pipemax_last_error(void);
+const char* pipemax_version(void);
+
+/* ---- host-side planning helpers (pure host code; also used by the CPU tests) ------------- */
+
+/* Element offset, inside one KV page, of element `dd` of token slot `tok` (0..15) of head
+ * `head` of K (kv = 0) or V (kv = 1) of layer `layer`.  Returns -1 on bad arguments.       */
+int64_t pipemax_page_elem_offset(int n_layers, int n_kv_heads, int head_dim,
+                                 int layer, int kv, int head, int tok, int dd);
+
+/* Merges n (src_page, dst_page) pairs, in the given order, into runs of consecutive pages,
+ * each at most max_run_pages long.  Writes (src_first, dst_first, count) triples to runs
+ * (room for 3*n int32) and returns the number of runs, or a negative status.               */
+int pipemax_plan_copy_runs(const int32_t* src_pages, const int32_t* dst_pages, int n,
+                           int max_run_pages, int32_t* runs);
+
+/* Lowest-index-first page allocator (the one the stage uses for both pools).               */
+int pipemax_pool_create(int n_pages, pipemax_pool_t** out);
+int pipemax_pool_destroy(pipemax_pool_t* p);
+int pipemax_pool_alloc(pipemax_pool_t* p, int n, int32_t* out_pages);  /* all or nothing */
+int pipemax_pool_free(pipemax_pool_t* p, const int32_t* pages, int n);
+int pipemax_pool_free_count(pipemax_pool_t* p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEMAX_H */

@@ -1,0 +1,278 @@
+"""ctypes binding of libpipemax.so: the same names as include/pipemax.h, argument marshalling only.
+
+Importing this module loads the library and raises if it has not been built
+(`python -m paper_2605_02189_amd.build`): there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipemax.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_02189_amd.build`")
+_lib = C.CDLL(LIB_PATH)
+
+OK, ERR_ARG, ERR_OOM_DEVICE, ERR_OOM_HOST = 0, -1, -2, -3
+ERR_NOT_RESIDENT, ERR_POOL_EXHAUSTED, ERR_HIP, ERR_STATE = -4, -5, -6, -7
+F32, BF16 = 0, 1
+W_QKV, W_O, W_GU, W_D, G_ATTN, G_FFN = range(6)
+FLAG_FORCE_GENERIC, FLAG_CAPTURE_LAYERS, FLAG_TIME_KERNELS, FLAG_NO_WRITEBACK = 1, 2, 4, 8
+K_CLASSES = ["norm", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gu", "swiglu",
+             "gemm_d", "misc"]
+N_KCLASS = len(K_CLASSES)
+HOST, INFLIGHT, GPU = 0, 1, 2
+
+# every symbol include/pipemax.h declares
+SYMBOLS = [
+    "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
+    "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
+    "pipemax_decode_step", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
+    "pipemax_reset_stats", "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
+    "pipemax_get_layer_outputs", "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
+    "pipemax_plan_copy_runs", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
+    "pipemax_pool_free", "pipemax_pool_free_count",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
+                ("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
+                ("page_tokens", C.c_int32), ("n_microbatches", C.c_int32),
+                ("max_seqs_per_mb", C.c_int32), ("max_ctx", C.c_int32),
+                ("gpu_kv_bytes", C.c_uint64), ("host_kv_bytes", C.c_uint64),
+                ("device", C.c_int32), ("flags", C.c_uint32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("steps", C.c_uint64), ("tokens", C.c_uint64),
+                ("h2d_bytes", C.c_uint64), ("h2d_copies", C.c_uint64),
+                ("d2h_bytes", C.c_uint64), ("d2h_copies", C.c_uint64),
+                ("table_uploads", C.c_uint64), ("relayout_jobs", C.c_uint64),
+                ("host_enqueue_s", C.c_double), ("host_wait_s", C.c_double),
+                ("h2d_ms", C.c_double), ("d2h_ms", C.c_double),
+                ("kernel_ms", C.c_double * N_KCLASS), ("kernel_launches", C.c_uint64 * N_KCLASS),
+                ("engine", C.c_int32), ("gpu_pages_total", C.c_int32), ("gpu_pages_free", C.c_int32),
+                ("host_pages_total", C.c_int32), ("host_pages_free", C.c_int32),
+                ("page_bytes", C.c_uint64)]
+
+    def as_dict(self):
+        d = {n: getattr(self, n) for n, _ in self._fields_ if n not in ("kernel_ms", "kernel_launches")}
+        d["kernel_ms"] = {k: self.kernel_ms[i] for i, k in enumerate(K_CLASSES)}
+        d["kernel_launches"] = {k: self.kernel_launches[i] for i, k in enumerate(K_CLASSES)}
+        return d
+
+
+_vp, _i32p = C.c_void_p, C.POINTER(C.c_int32)
+_sig = {
+    "pipemax_stage_create": (C.c_int, [C.POINTER(Config), C.POINTER(_vp)]),
+    "pipemax_stage_destroy": (C.c_int, [_vp]),
+    "pipemax_set_weight": (C.c_int, [_vp, C.c_int, C.c_int, _vp, C.c_size_t]),
+    "pipemax_mb_define": (C.c_int, [_vp, C.c_int, C.c_int, _i32p]),
+    "pipemax_kv_host_write": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
+    "pipemax_kv_host_read": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
+    "pipemax_kv_dev_read": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
+    "pipemax_prefetch_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
+    "pipemax_decode_step": (C.c_int, [_vp, C.c_int, _vp, _vp, _vp]),
+    "pipemax_evict_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
+    "pipemax_sync": (C.c_int, [_vp]),
+    "pipemax_get_stats": (C.c_int, [_vp, C.POINTER(Stats)]),
+    "pipemax_reset_stats": (C.c_int, [_vp]),
+    "pipemax_get_ctx_lens": (C.c_int, [_vp, C.c_int, _i32p]),
+    "pipemax_get_residency": (C.c_int, [_vp, C.c_int, _i32p]),
+    "pipemax_get_block_table": (C.c_int, [_vp, C.c_int, C.c_int, _i32p, _i32p, C.POINTER(C.c_int)]),
+    "pipemax_get_layer_outputs": (C.c_int, [_vp, _vp, C.c_size_t]),
+    "pipemax_last_error": (C.c_char_p, []),
+    "pipemax_version": (C.c_char_p, []),
+    "pipemax_page_elem_offset": (C.c_int64, [C.c_int] * 8),
+    "pipemax_plan_copy_runs": (C.c_int, [_i32p, _i32p, C.c_int, C.c_int, _i32p]),
+    "pipemax_pool_create": (C.c_int, [C.c_int, C.POINTER(_vp)]),
+    "pipemax_pool_destroy": (C.c_int, [_vp]),
+    "pipemax_pool_alloc": (C.c_int, [_vp, C.c_int, _i32p]),
+    "pipemax_pool_free": (C.c_int, [_vp, _i32p, C.c_int]),
+    "pipemax_pool_free_count": (C.c_int, [_vp]),
+}
+for _name, (_res, _args) in _sig.items():
+    _f = getattr(_lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+class PipemaxError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"pipemax status {code}: {msg}")
+        self.code = code
+
+
+def last_error() -> str:
+    return _lib.pipemax_last_error().decode()
+
+
+def version() -> str:
+    return _lib.pipemax_version().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise PipemaxError(rc, last_error())
+
+
+def _ids(seq_ids):
+    if seq_ids is None:
+        return None, 0
+    a = np.ascontiguousarray(seq_ids, dtype=np.int32)
+    return a.ctypes.data_as(_i32p), int(a.size)
+
+
+def _ptr(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+class Stage:
+    """Thin owner of a pipemax_stage_t; method names follow the C entry points."""
+
+    def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps,
+                 dtype, n_microbatches, max_seqs_per_mb, max_ctx, gpu_kv_bytes, host_kv_bytes,
+                 device=0, flags=0, page_tokens=16):
+        self.cfg = Config(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps,
+                          dtype, page_tokens, n_microbatches, max_seqs_per_mb, max_ctx,
+                          int(gpu_kv_bytes), int(host_kv_bytes), device, flags)
+        self._h = _vp()
+        _check(_lib.pipemax_stage_create(C.byref(self.cfg), C.byref(self._h)))
+        self.np_dtype = np.float32 if dtype == F32 else np.uint16
+        self._nseq = {}
+
+    def destroy(self):
+        if self._h:
+            _check(_lib.pipemax_stage_destroy(self._h))
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # -- set-up ---------------------------------------------------------------------------
+    def set_weight(self, layer: int, which: int, arr: np.ndarray):
+        a = np.ascontiguousarray(arr, dtype=self.np_dtype)
+        _check(_lib.pipemax_set_weight(self._h, layer, which, _ptr(a), a.nbytes))
+
+    def mb_define(self, mb: int, ctx_lens):
+        a = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        _check(_lib.pipemax_mb_define(self._h, mb, int(a.size), a.ctypes.data_as(_i32p)))
+        self._nseq[mb] = int(a.size)
+
+    def kv_host_write(self, mb, seq, layer, tok0, K: np.ndarray, V: np.ndarray):
+        K = np.ascontiguousarray(K, dtype=self.np_dtype)
+        V = np.ascontiguousarray(V, dtype=self.np_dtype)
+        assert K.shape == V.shape
+        _check(_lib.pipemax_kv_host_write(self._h, mb, seq, layer, tok0, K.shape[0], _ptr(K), _ptr(V)))
+
+    def _kv_read(self, fn, mb, seq, layer, tok0, ntok):
+        shp = (ntok, self.cfg.n_kv_heads, self.cfg.head_dim)
+        K = np.empty(shp, dtype=self.np_dtype)
+        V = np.empty(shp, dtype=self.np_dtype)
+        _check(fn(self._h, mb, seq, layer, tok0, ntok, _ptr(K), _ptr(V)))
+        return K, V
+
+    def kv_host_read(self, mb, seq, layer, tok0, ntok):
+        return self._kv_read(_lib.pipemax_kv_host_read, mb, seq, layer, tok0, ntok)
+
+    def kv_dev_read(self, mb, seq, layer, tok0, ntok):
+        return self._kv_read(_lib.pipemax_kv_dev_read, mb, seq, layer, tok0, ntok)
+
+    # -- hot path -------------------------------------------------------------------------
+    def prefetch_kv(self, mb, seq_ids=None):
+        p, n = _ids(seq_ids)
+        _check(_lib.pipemax_prefetch_kv(self._h, mb, p, n))
+
+    def decode_step(self, mb, hidden_in_ptr: int, hidden_out_ptr: int, stream_ptr: int = 0):
+        """Device pointers as integers (e.g. tensor.data_ptr(), torch stream .cuda_stream)."""
+        _check(_lib.pipemax_decode_step(self._h, mb, _vp(hidden_in_ptr), _vp(hidden_out_ptr),
+                                        _vp(stream_ptr) if stream_ptr else None))
+
+    def evict_kv(self, mb, seq_ids=None):
+        p, n = _ids(seq_ids)
+        _check(_lib.pipemax_evict_kv(self._h, mb, p, n))
+
+    def sync(self):
+        _check(_lib.pipemax_sync(self._h))
+
+    # -- introspection --------------------------------------------------------------------
+    def get_stats(self) -> dict:
+        s = Stats()
+        _check(_lib.pipemax_get_stats(self._h, C.byref(s)))
+        return s.as_dict()
+
+    def reset_stats(self):
+        _check(_lib.pipemax_reset_stats(self._h))
+
+    def get_ctx_lens(self, mb) -> np.ndarray:
+        out = np.empty(self._nseq[mb], dtype=np.int32)
+        _check(_lib.pipemax_get_ctx_lens(self._h, mb, out.ctypes.data_as(_i32p)))
+        return out
+
+    def get_residency(self, mb) -> np.ndarray:
+        out = np.empty(self._nseq[mb], dtype=np.int32)
+        _check(_lib.pipemax_get_residency(self._h, mb, out.ctypes.data_as(_i32p)))
+        return out
+
+    def get_block_table(self, mb, seq):
+        n = C.c_int(0)
+        _check(_lib.pipemax_get_block_table(self._h, mb, seq, None, None, C.byref(n)))
+        g = np.empty(max(n.value, 1), dtype=np.int32)
+        h = np.empty(max(n.value, 1), dtype=np.int32)
+        m = C.c_int(n.value)
+        _check(_lib.pipemax_get_block_table(self._h, mb, seq, g.ctypes.data_as(_i32p),
+                                            h.ctypes.data_as(_i32p), C.byref(m)))
+        return g[: m.value], h[: m.value]
+
+    def get_layer_outputs(self, b: int) -> np.ndarray:
+        out = np.empty((self.cfg.n_layers, b, self.cfg.hidden), dtype=np.float32)
+        _check(_lib.pipemax_get_layer_outputs(self._h, _ptr(out), out.nbytes))
+        return out
+
+
+# -- host-side planning helpers ---------------------------------------------------------------
+def page_elem_offset(n_layers, n_kv_heads, head_dim, layer, kv, head, tok, dd) -> int:
+    return int(_lib.pipemax_page_elem_offset(n_layers, n_kv_heads, head_dim, layer, kv, head, tok, dd))
+
+
+def plan_copy_runs(src_pages, dst_pages, max_run_pages: int):
+    s = np.ascontiguousarray(src_pages, dtype=np.int32)
+    d = np.ascontiguousarray(dst_pages, dtype=np.int32)
+    assert s.size == d.size
+    runs = np.empty(3 * max(int(s.size), 1), dtype=np.int32)
+    n = _lib.pipemax_plan_copy_runs(s.ctypes.data_as(_i32p), d.ctypes.data_as(_i32p), int(s.size),
+                                    max_run_pages, runs.ctypes.data_as(_i32p))
+    if n < 0:
+        raise PipemaxError(n, last_error())
+    return runs[: 3 * n].reshape(n, 3)
+
+
+class Pool:
+    def __init__(self, n_pages: int):
+        self._h = _vp()
+        _check(_lib.pipemax_pool_create(n_pages, C.byref(self._h)))
+
+    def alloc(self, n: int) -> np.ndarray:
+        out = np.empty(max(n, 1), dtype=np.int32)
+        _check(_lib.pipemax_pool_alloc(self._h, n, out.ctypes.data_as(_i32p)))
+        return out[:n]
+
+    def free(self, pages):
+        a = np.ascontiguousarray(pages, dtype=np.int32)
+        _check(_lib.pipemax_pool_free(self._h, a.ctypes.data_as(_i32p), int(a.size)))
+
+    def free_count(self) -> int:
+        return int(_lib.pipemax_pool_free_count(self._h))
+
+    def __del__(self):
+        if self._h:
+            _lib.pipemax_pool_destroy(self._h)
+            self._h = _vp()

@@ -1,0 +1,71 @@
+// Launchers of the device kernels.  Every launcher checks nothing: the stage object validates
+// shapes once at create time and passes only buffers it sized itself.
+#pragma once
+
+#include "common.hpp"
+
+namespace pmx {
+
+struct Dims {
+  int n_layers, h, Hq, Hkv, d, F, Nqkv, G;
+  float rope_base, eps;
+  int max_pages;        // block-table row length
+  int max_ctx_pad;      // row length of the generic attention's score scratch
+  int64_t page_elems;   // elements per page
+};
+
+// ---- shared small kernels ----------------------------------------------------------------------
+// cs[i][j] = (cos, sin)(ctx[i] * base^(-2j/d)), angle formed in double precision.
+void launch_rope_table(hipStream_t s, const int* ctx, float2* cs, int b, int d, float base);
+void launch_advance_ctx(hipStream_t s, int* ctx, int b);
+
+// ---- shape-generic engine (T = float or bf16 bit patterns as uint16_t) ---------------------------
+template <typename T>
+struct Generic {
+  static void load_hidden(hipStream_t s, const T* in, float* x, int64_t n);
+  static void store_hidden(hipStream_t s, const float* x, T* out, int64_t n);
+  static void rmsnorm(hipStream_t s, const float* x, const T* gain, float* xn, int b, int h, float eps);
+  // C[M][N] (+)= A[M][K] @ W[K][N]
+  static void gemm(hipStream_t s, const float* A, const T* W, float* C, int M, int K, int N,
+                   int accumulate);
+  static void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* qkv,
+                          const float2* cs, const int* ctx, const int* table, T* pool, T* staging,
+                          float* q_out);
+  static void attention(hipStream_t s, const Dims& D, int layer, int b, const float* q, const T* pool,
+                        const int* table, const int* ctx, float* scores, float* out);
+};
+void launch_swiglu_generic(hipStream_t s, const float* gu, float* act, int b, int F);
+
+// ---- matrix-core engine (bf16, head_dim 128) -------------------------------------------------------
+namespace mfma {
+
+// x (+)= sum_s part[s] ;  optional bf16 input row (hin) replaces x first ;
+// optional RMSNorm -> A-tiled bf16 (xn_t, KT = h/16) ; optional bf16 row-major output (hout).
+void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, const float* part,
+                int n_split, int64_t split_stride, float* x, const uint16_t* gain, uint16_t* xn_t,
+                uint16_t* hout);
+
+// part[s][m][n] = X[m][k-range s] @ W[k-range s][n]   (X A-tiled, W B-tiled, fp32 partials)
+// Mpad = 32*MT rows are computed, rows < M are stored.  N % (32*wn) == 0, wn in {4, 8}.
+void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
+          int n_split, int wn);
+
+void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
+                 int64_t split_stride, const float2* cs, const int* ctx, const int* table,
+                 uint16_t* pool, uint16_t* staging, uint16_t* q_out);
+
+// Split-K paged GQA decode attention + merge.  chunk_pages = target pages per work-group,
+// max_chunks = grid extent along the context axis (>= ceil(max pages / chunk_pages)).
+void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q,
+               const uint16_t* pool, const int* table, const int* ctx, float* part_o, float* part_ml,
+               int chunk_pages, int max_chunks);
+void attention_merge(hipStream_t s, const Dims& D, int b, const int* ctx, const float* part_o,
+                     const float* part_ml, int chunk_pages, int max_chunks, uint16_t* out_t);
+
+// act_t (A-tiled, KT = F/16) = silu(sum_s gate) * sum_s up ; partial columns are in the
+// gate/up-interleaved order of the tiled W_gu (32 gate columns, then the 32 up columns).
+void swiglu(hipStream_t s, int b, int F, const float* part, int n_split, int64_t split_stride,
+            uint16_t* act_t);
+
+}  // namespace mfma
+}  // namespace pmx

@@ -1,0 +1,499 @@
+// Matrix-core (MFMA) kernels of the stage decode step for gfx950: bf16 storage, fp32 accumulation,
+// head_dim 128, 64-wide wavefronts.
+//
+// Data reaches the matrix instructions without any shuffle: KV pages, weights and activations are
+// stored in operand-fragment order (see common.hpp), so every global load is a lane-linear 16-byte
+// load (1 KiB contiguous per wave instruction) that lands directly in an MFMA operand register.
+#include "kernels.hpp"
+
+namespace pmx {
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+// streaming 16-byte load: data read exactly once should not displace what is re-used
+__device__ inline uint4 ld_stream(const uint4* p) {
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)p));
+}
+
+__device__ inline float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ inline uint16_t f2bf(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ inline uint32_t pack2(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
+__device__ inline uint4 pack8(const float* v) {
+  return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+}
+__device__ inline void unpack8(uint4 u, float* v) {
+  v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+  v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+  v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+  v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+
+__device__ inline float block_sum256(float v, float* sh) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
+
+// =================================================================================================
+// residual add (+ split-K reduction of the producing GEMM) + RMSNorm -> A-tiled bf16
+// =================================================================================================
+__global__ __launch_bounds__(256) void k_resid_norm(int h, float eps, const uint16_t* hin,
+                                                    const float* part, int n_split,
+                                                    int64_t split_stride, float* x,
+                                                    const uint16_t* gain, uint16_t* xn_t,
+                                                    uint16_t* hout) {
+  __shared__ float sh[4];
+  const int i = blockIdx.x;
+  float* xr = x + (int64_t)i * h;
+  float ss = 0.f;
+  for (int j0 = threadIdx.x * 8; j0 < h; j0 += 256 * 8) {
+    float v[8];
+    if (hin) {
+      unpack8(*(const uint4*)(hin + (int64_t)i * h + j0), v);
+    } else {
+      float4 a = *(const float4*)(xr + j0), b = *(const float4*)(xr + j0 + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    if (part) {
+      const float* p = part + (int64_t)i * h + j0;
+      for (int s = 0; s < n_split; ++s) {
+        float4 a = *(const float4*)(p + s * split_stride), b = *(const float4*)(p + s * split_stride + 4);
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+      }
+    }
+    *(float4*)(xr + j0) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(xr + j0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+    if (hout) *(uint4*)(hout + (int64_t)i * h + j0) = pack8(v);
+  }
+  if (!xn_t) return;
+  ss = block_sum256(ss, sh);     // its barriers also order the x stores above before the re-read
+  const float r = 1.0f / sqrtf(ss / (float)h + eps);
+  const int KT = h >> 4;
+  for (int j0 = threadIdx.x * 8; j0 < h; j0 += 256 * 8) {
+    float4 a = *(const float4*)(xr + j0), b = *(const float4*)(xr + j0 + 4);
+    float gv[8];
+    unpack8(*(const uint4*)(gain + j0), gv);
+    float v[8] = {a.x * r * gv[0], a.y * r * gv[1], a.z * r * gv[2], a.w * r * gv[3],
+                  b.x * r * gv[4], b.y * r * gv[5], b.z * r * gv[6], b.w * r * gv[7]};
+    *(uint4*)(xn_t + a_tiled_idx(KT, i, j0)) = pack8(v);
+  }
+}
+
+// =================================================================================================
+// skinny GEMM: part[s][m][n] = X[m][k in split s] . W[k][n]
+//   work-group = WN waves; wave w owns the 32 columns of n-tile blockIdx.x*WN + w and all MT m-tiles;
+//   blockIdx.y = split of the K range.  The X fragments of a chunk of KC k-steps are staged once in
+//   LDS and shared by the WN waves; every wave streams its own weight fragments straight from HBM.
+// =================================================================================================
+template <int MT, int WN>
+__global__ __launch_bounds__(WN * 64) void k_gemm(const uint4* __restrict__ Xt,
+                                                  const uint4* __restrict__ Wt,
+                                                  float* __restrict__ part, int M, int N, int KT,
+                                                  int ksp, int64_t split_stride) {
+  constexpr int KC = 4;
+  constexpr int NF = MT * KC;                       // X fragments per chunk
+  constexpr int XPT = (NF + WN - 1) / WN;           // X fragments loaded per wave
+  __shared__ uint4 xs[2][NF * 64];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt = blockIdx.x * WN + w;
+  const int k0 = blockIdx.y * ksp;
+  const int k1 = min(KT, k0 + ksp);
+  const int nchunks = (k1 - k0 + KC - 1) / KC;
+  const uint4* wp = Wt + (int64_t)nt * KT * 64 + lane;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+
+  uint4 xr[XPT], wcur[KC], wnext[KC];
+  auto load_x = [&](int kc0) {
+#pragma unroll
+    for (int t = 0; t < XPT; ++t) {
+      int f = w + t * WN;
+      int mt = f / KC, kk = f - mt * KC;
+      xr[t] = (f < NF && kc0 + kk < k1) ? Xt[((int64_t)mt * KT + kc0 + kk) * 64 + lane] : zero4;
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int t = 0; t < XPT; ++t) {
+      int f = w + t * WN;
+      if (f < NF) xs[buf][f * 64 + lane] = xr[t];
+    }
+  };
+  auto load_w = [&](int kc0, uint4* dst) {
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk)
+      dst[kk] = (kc0 + kk < k1) ? ld_stream(wp + (int64_t)(kc0 + kk) * 64) : zero4;
+  };
+
+  if (nchunks > 0) {
+    load_x(k0);
+    load_w(k0, wcur);
+    store_x(0);
+  }
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const int buf = c & 1;
+    const bool more = (c + 1 < nchunks);
+    if (more) {
+      load_x(k0 + (c + 1) * KC);
+      load_w(k0 + (c + 1) * KC, wnext);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      bf16x8 B = __builtin_bit_cast(bf16x8, wcur[kk]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        bf16x8 A = __builtin_bit_cast(bf16x8, xs[buf][(mt * KC + kk) * 64 + lane]);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[mt], 0, 0, 0);
+      }
+    }
+    if (more) {
+      store_x(buf ^ 1);
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk) wcur[kk] = wnext[kk];
+    }
+    __syncthreads();
+  }
+
+  float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt * 32 + (lane & 31);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (m < M) out[(int64_t)m * N] = acc[mt][r];
+    }
+}
+
+// =================================================================================================
+// RoPE + KV append + write-back staging; also reduces the split-K partials of the QKV GEMM
+//   grid (b, Hq + 2 Hkv), block 64: thread j rotates the pair (j, j + 64)
+// =================================================================================================
+__global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const float* part, int n_split,
+                                                    int64_t split_stride, const float2* cs,
+                                                    const int* ctx, const int* table, uint16_t* pool,
+                                                    uint16_t* staging, uint16_t* q_out) {
+  const int i = blockIdx.x, hd = blockIdx.y, j = threadIdx.x;
+  const float* row = part + (int64_t)i * D.Nqkv + (int64_t)hd * 128;
+  float lo = 0.f, hi = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    lo += row[s * split_stride + j];
+    hi += row[s * split_stride + j + 64];
+  }
+  const int pos = ctx[i];
+  if (hd < D.Hq) {
+    float2 c = cs[i * 64 + j];
+    uint16_t* q = q_out + ((int64_t)i * D.Hq + hd) * 128;
+    q[j] = f2bf(lo * c.x - hi * c.y);
+    q[j + 64] = f2bf(hi * c.x + lo * c.y);
+    return;
+  }
+  const int kv = (hd < D.Hq + D.Hkv) ? 0 : 1;
+  const int head = hd - D.Hq - kv * D.Hkv;
+  if (kv == 0) {
+    float2 c = cs[i * 64 + j];
+    float a = lo * c.x - hi * c.y, b2 = hi * c.x + lo * c.y;
+    lo = a;
+    hi = b2;
+  }
+  const int phys = table[(int64_t)i * D.max_pages + (pos >> 4)];
+  const int slot = pos & 15;
+  uint16_t* sub = pool + (int64_t)phys * D.page_elems + sub_block_off(D.Hkv, 128, layer, head, kv);
+  if (slot == 0) {     // first token of a fresh page: clear the 4 KiB sub-block first
+    uint4* z = (uint4*)sub;
+    for (int e = j; e < 256; e += 64) z[e] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+  }
+  const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
+  if (kv == 0) {
+    sub[k_sub_idx(slot, j)] = blo;
+    sub[k_sub_idx(slot, j + 64)] = bhi;
+  } else {
+    sub[v_sub_idx(slot, j)] = blo;
+    sub[v_sub_idx(slot, j + 64)] = bhi;
+  }
+  uint16_t* st = staging + (((int64_t)i * 2 + kv) * D.Hkv + head) * 128;   // [b][2][Hkv][128]
+  st[j] = blo;
+  st[j + 64] = bhi;
+}
+
+// =================================================================================================
+// GQA paged decode attention, split-K over the context
+//   grid (chunk, kv head, sequence), block = 4 waves.  A block owns a run of pages of one (sequence,
+//   kv head); its waves take the pages round-robin, each keeping an online-softmax state for the G
+//   query heads of the group (padded to the 16 columns of the MFMA tile), and merge through LDS.
+//   S^T[tok][head] = K[tok][:] . Q[head][:]      mfma_f32_16x16x32_bf16   (A = K page, B = Q)
+//   O^T[d][head]  += V^T[d][tok] . P^T[tok][head] mfma_f32_16x16x16_bf16   (A = V page, B = P)
+//   The S^T accumulator layout (lane: column = head, 4 consecutive tokens) is exactly the B-operand
+//   layout of the second product, so P never leaves its registers.
+// =================================================================================================
+__device__ inline void chunk_range(int n_tok, int CP, int chunk, int& nch, int& p0, int& p1) {
+  const int npages = (n_tok + 15) >> 4;
+  const int nch0 = (npages + CP - 1) / CP;
+  const int per = (npages + nch0 - 1) / nch0;
+  nch = (npages + per - 1) / per;
+  p0 = chunk * per;
+  p1 = min(npages, p0 + per);
+}
+
+constexpr int kORow = 132;   // padded LDS row of the cross-wave merge
+
+__global__ __launch_bounds__(256) void k_attn(Dims D, int layer, const uint16_t* __restrict__ q,
+                                              const uint16_t* __restrict__ pool,
+                                              const int* __restrict__ table,
+                                              const int* __restrict__ ctx, float* __restrict__ part_o,
+                                              float* __restrict__ part_ml, int CP, int NCH) {
+  extern __shared__ float so[];                 // [4][G][kORow]
+  __shared__ float sm[4][16], sl[4][16];
+  const int chunk = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  const int G = D.G;
+  const int n_tok = ctx[i] + 1;
+  int nch, p0, p1;
+  chunk_range(n_tok, CP, chunk, nch, p0, p1);
+  if (chunk >= nch) return;
+
+  // Q fragments: B operand, lane (n, g) holds Q[head n][kk*32 + 8g .. +8]
+  bf16x8 qf[4];
+  {
+    const uint16_t* qrow = q + ((int64_t)i * D.Hq + c * G + (n < G ? n : 0)) * 128 + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 v = (n < G) ? *(const uint4*)(qrow + kk * 32) : make_uint4(0, 0, 0, 0);
+      qf[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  // this wave's pages: p0 + w, p0 + w + 4, ...
+  const int span = p1 - p0;
+  const int npw = (span > w) ? ((span - w + 3) >> 2) : 0;
+  int my_page = 0;
+  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + w + 4 * lane];
+  const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
+  const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 oacc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 kf[4], vf[4];
+  auto load_page = [&](int t, uint4* kd, uint4* vd) {
+    const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
+    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
+  };
+  if (npw > 0) load_page(0, kf, vf);
+
+  for (int t = 0; t < npw; ++t) {
+    uint4 kn[4], vn[4];
+    if (t + 1 < npw) load_page(t + 1, kn, vn);
+
+    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[kk]), qf[kk], sacc,
+                                                     0, 0, 0);
+    const int tok0 = ((p0 + w + 4 * t) << 4) + 4 * g;
+    float s[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s[r] = (tok0 + r < n_tok) ? sacc[r] * scale_log2 : -INFINITY;
+    float mloc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+    const float m_new = fmaxf(m_run, mloc);
+    const float alpha = exp2f(m_run - m_new);
+    float p[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) p[r] = exp2f(s[r] - m_new);
+    float lsum = (p[0] + p[1]) + (p[2] + p[3]);
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    l_run = l_run * alpha + lsum;
+    m_run = m_new;
+    const uint2 pp = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+    const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[jj].x, vf[jj].y));
+      const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[jj].z, vf[jj].w));
+      oacc[2 * jj] = oacc[2 * jj] * alpha;
+      oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
+      oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
+      oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+    }
+    if (t + 1 < npw) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { kf[e] = kn[e]; vf[e] = vn[e]; }
+    }
+  }
+
+  // ---- merge the 4 waves' partial states through LDS -------------------------------------------
+  if (g == 0) { sm[w][n] = m_run; sl[w][n] = l_run; }
+  __syncthreads();
+  float m_tot = fmaxf(fmaxf(sm[0][n], sm[1][n]), fmaxf(sm[2][n], sm[3][n]));
+  float l_tot = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < 4; ++ww) l_tot += sl[ww][n] * exp2f(sm[ww][n] - m_tot);
+  const float f = exp2f(m_run - m_tot);
+  if (n < G) {
+    float* dst = so + ((int64_t)w * G + n) * kORow + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      f32x4 v = oacc[dt] * f;
+      *(float4*)(dst + dt * 16) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < G * 128; e += 256) {
+    const int nn = e >> 7, dd = e & 127;
+    float o = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) o += so[((int64_t)ww * G + nn) * kORow + dd];
+    part_o[(((int64_t)i * D.Hq + c * G + nn) * NCH + chunk) * 128 + dd] = o;
+  }
+  if (w == 0 && g == 0 && n < G) {
+    float* ml = part_ml + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 2;
+    ml[0] = m_tot;
+    ml[1] = l_tot;
+  }
+}
+
+// grid (b, Hq), block 128 (one thread per output dimension); writes the A-tiled bf16 input of the
+// output projection
+__global__ __launch_bounds__(128) void k_attn_merge(Dims D, const int* ctx, const float* part_o,
+                                                    const float* part_ml, int CP, int NCH,
+                                                    uint16_t* out_t) {
+  const int i = blockIdx.x, u = blockIdx.y, dd = threadIdx.x;
+  int nch, p0, p1;
+  chunk_range(ctx[i] + 1, CP, 0, nch, p0, p1);
+  const float* ml = part_ml + ((int64_t)i * D.Hq + u) * NCH * 2;
+  const float* po = part_o + ((int64_t)i * D.Hq + u) * NCH * 128 + dd;
+  float m_tot = -INFINITY;
+  for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ml[2 * j]);
+  float l = 0.f, o = 0.f;
+  for (int j = 0; j < nch; ++j) {
+    const float fj = exp2f(ml[2 * j] - m_tot);
+    l += ml[2 * j + 1] * fj;
+    o += po[(int64_t)j * 128] * fj;
+  }
+  out_t[a_tiled_idx(D.Hq * 128 / 16, i, u * 128 + dd)] = f2bf(o / l);
+}
+
+// =================================================================================================
+// SwiGLU over the split-K partials of the gate/up GEMM -> A-tiled bf16 input of the down GEMM
+// =================================================================================================
+__global__ __launch_bounds__(256) void k_swiglu(int b, int F, const float* part, int n_split,
+                                                int64_t split_stride, uint16_t* act_t) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int F8 = F >> 3;
+  if (idx >= (int64_t)b * F8) return;
+  const int i = (int)(idx / F8), f0 = (int)(idx - (int64_t)i * F8) * 8;
+  const int col = (f0 >> 5) * 64 + (f0 & 31);          // gate columns; the up columns follow at +32
+  const float* p = part + (int64_t)i * 2 * F + col;
+  float gt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, up[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int s = 0; s < n_split; ++s) {
+    const float* ps = p + s * split_stride;
+    float4 a = *(const float4*)ps, b2 = *(const float4*)(ps + 4);
+    float4 c = *(const float4*)(ps + 32), d2 = *(const float4*)(ps + 36);
+    gt[0] += a.x; gt[1] += a.y; gt[2] += a.z; gt[3] += a.w;
+    gt[4] += b2.x; gt[5] += b2.y; gt[6] += b2.z; gt[7] += b2.w;
+    up[0] += c.x; up[1] += c.y; up[2] += c.z; up[3] += c.w;
+    up[4] += d2.x; up[5] += d2.y; up[6] += d2.z; up[7] += d2.w;
+  }
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = gt[e] / (1.0f + expf(-gt[e])) * up[e];
+  *(uint4*)(act_t + a_tiled_idx(F >> 4, i, f0)) = pack8(v);
+}
+
+}  // namespace
+
+// ---- launchers -------------------------------------------------------------------------------------
+void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, const float* part,
+                int n_split, int64_t split_stride, float* x, const uint16_t* gain, uint16_t* xn_t,
+                uint16_t* hout) {
+  hipLaunchKernelGGL(k_resid_norm, dim3(b), dim3(256), 0, s, h, eps, hin, part, n_split, split_stride,
+                     x, gain, xn_t, hout);
+}
+
+template <int WN>
+static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K,
+                    int N, int n_split) {
+  const int KT = K / 16;
+  const int ksp = (KT + n_split - 1) / n_split;
+  const int MT = (M + 31) / 32;
+  const int64_t stride = (int64_t)MT * 32 * N;
+  dim3 grid(N / (32 * WN), n_split), block(WN * 64);
+  const uint4* X4 = (const uint4*)Xt;
+  const uint4* W4 = (const uint4*)Wt;
+#define PMX_GEMM_CASE(mt)                                                                         \
+  hipLaunchKernelGGL((k_gemm<mt, WN>), grid, block, 0, s, X4, W4, part, M, N, KT, ksp, stride)
+  if (MT <= 1) PMX_GEMM_CASE(1);
+  else if (MT <= 2) PMX_GEMM_CASE(2);
+  else if (MT <= 4) PMX_GEMM_CASE(4);
+  else PMX_GEMM_CASE(8);
+#undef PMX_GEMM_CASE
+}
+
+void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
+          int n_split, int wn) {
+  if (wn == 8) gemm_wn<8>(s, Xt, Wt, part, M, K, N, n_split);
+  else gemm_wn<4>(s, Xt, Wt, part, M, K, N, n_split);
+}
+
+void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
+                 int64_t split_stride, const float2* cs, const int* ctx, const int* table,
+                 uint16_t* pool, uint16_t* staging, uint16_t* q_out) {
+  hipLaunchKernelGGL(k_rope_append, dim3(b, D.Hq + 2 * D.Hkv), dim3(64), 0, s, D, layer, part, n_split,
+                     split_stride, cs, ctx, table, pool, staging, q_out);
+}
+
+void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
+               const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
+               int max_chunks) {
+  const size_t lds = (size_t)4 * D.G * kORow * sizeof(float);
+  hipLaunchKernelGGL(k_attn, dim3(max_chunks, D.Hkv, b), dim3(256), lds, s, D, layer, q, pool, table,
+                     ctx, part_o, part_ml, chunk_pages, max_chunks);
+}
+
+void attention_merge(hipStream_t s, const Dims& D, int b, const int* ctx, const float* part_o,
+                     const float* part_ml, int chunk_pages, int max_chunks, uint16_t* out_t) {
+  hipLaunchKernelGGL(k_attn_merge, dim3(b, D.Hq), dim3(128), 0, s, D, ctx, part_o, part_ml,
+                     chunk_pages, max_chunks, out_t);
+}
+
+void swiglu(hipStream_t s, int b, int F, const float* part, int n_split, int64_t split_stride,
+            uint16_t* act_t) {
+  hipLaunchKernelGGL(k_swiglu, dim3(cdiv((int64_t)b * (F / 8), 256)), dim3(256), 0, s, b, F, part,
+                     n_split, split_stride, act_t);
+}
+
+}  // namespace mfma
+}  // namespace pmx

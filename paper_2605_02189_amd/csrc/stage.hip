@@ -1,0 +1,1244 @@
+// The stage object behind the C ABI: KV page pools and block tables, the three-stream step
+// executor, the prefetch / evict paths and the write-back worker.
+//
+// Streams.  compute = the caller's stream (or the stage's own); h2d = KV prefetch; d2h = KV
+// write-back.  All at default priority.
+//   decode_step(mb): compute waits for mb's prefetch event; per layer, after the kernel that appends
+//     the new K,V, an event releases the d2h copy of that layer's contiguous staging to pinned host
+//     memory; the worker thread waits for that copy and scatters the rows into the host pages.
+//   prefetch(mb):   host waits until mb's pending write-back has landed in the host replica, then
+//     page runs are copied on h2d, which is ordered (see evict) after the last reader of any page
+//     it overwrites.
+//   evict(mb):      h2d waits for mb's last step event; the GPU pages go back to the free list.
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <memory>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "kernels.hpp"
+#include "kv_pool.hpp"
+
+namespace pmx {
+
+static thread_local char g_err[512] = "";
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+constexpr int kSlots = 4;        // depth of the write-back staging ring
+constexpr int kTableRing = 8;    // depth of the block-table upload ring
+constexpr int kMaxRunPages = 128;  // longest single prefetch copy, in pages (64 MiB at 512 KiB pages)
+enum { ST_HOST = 0, ST_INFLIGHT = 1, ST_GPU = 2 };
+enum { TC_H2D = PIPEMAX_N_KCLASS, TC_D2H = PIPEMAX_N_KCLASS + 1 };
+
+double now_s() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+struct SeqState {
+  int len = 0;
+  int state = ST_HOST;
+  std::vector<int32_t> gpu, host;
+};
+
+struct MicroBatch {
+  bool defined = false;
+  int b = 0;
+  std::vector<SeqState> seq;
+  int* d_ctx = nullptr;
+  int* d_table = nullptr;
+  bool table_dirty = true;
+  hipEvent_t ev_prefetch = nullptr;
+  bool prefetch_pending = false;
+  hipEvent_t ev_step = nullptr;
+  bool stepped = false;
+  int wb_pending = 0;   // guarded by Stage::mu
+};
+
+struct WbJob {
+  hipEvent_t ev = nullptr;
+  int mb = 0, layer = 0, slot = 0, b = 0;
+  std::shared_ptr<std::vector<std::pair<int32_t, int>>> where;   // per sequence: host page, slot
+  bool stop = false;
+};
+
+struct Timed {
+  int cls;
+  hipEvent_t a, b;
+};
+
+struct LayerW {
+  void *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr, *g1 = nullptr, *g2 = nullptr;
+};
+
+struct GemmPlan {
+  int split = 1, wn = 8;
+};
+
+}  // namespace
+}  // namespace pmx
+
+using namespace pmx;
+
+struct pipemax_pool {
+  PagePool pool;
+  explicit pipemax_pool(int n) : pool(n) {}
+};
+
+struct pipemax_stage {
+  pipemax_config_t cfg{};
+  Dims D{};
+  int engine = 0;
+  size_t esz = 4;
+  size_t page_bytes = 0;
+  int dev = 0;
+  hipStream_t s_own = nullptr, s_h2d = nullptr, s_d2h = nullptr, s_last = nullptr;
+  void* gpu_pool = nullptr;
+  void* host_pool = nullptr;
+  std::unique_ptr<PagePool> gpu_pages, host_pages;
+  std::vector<MicroBatch> mbs;
+  std::vector<LayerW> w;
+  std::vector<void*> dev_allocs;    // everything hipMalloc'ed except the pool
+  std::vector<void*> host_allocs;   // everything hipHostMalloc'ed except the pool
+  // activations
+  float* x = nullptr;
+  float2* rope_cs = nullptr;
+  float *g_xn = nullptr, *g_qkv = nullptr, *g_q = nullptr, *g_attn = nullptr, *g_gu = nullptr,
+        *g_act = nullptr, *g_scores = nullptr;
+  uint16_t *m_xn_t = nullptr, *m_q = nullptr, *m_attn_t = nullptr, *m_act_t = nullptr;
+  float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr;
+  GemmPlan p_qkv, p_o, p_gu, p_d;
+  int nch_alloc = 1;
+  float* layer_out = nullptr;
+  int last_b = 0;
+  // write-back ring
+  void* d_stage[kSlots] = {};
+  void* h_stage[kSlots] = {};
+  std::vector<hipEvent_t> ev_ready[kSlots], ev_copied[kSlots];
+  int slot_pending[kSlots] = {};   // guarded by mu
+  uint64_t step_no = 0;
+  // table upload ring
+  int32_t* h_table[kTableRing] = {};
+  hipEvent_t ev_table[kTableRing] = {};
+  bool table_used[kTableRing] = {};
+  int table_pos = 0;
+  // ordering of growth pages against cancelled prefetches
+  hipEvent_t ev_h2d_fence = nullptr;
+  bool h2d_fence_pending = false;
+  // worker
+  std::thread worker;
+  std::mutex mu;
+  std::condition_variable cv_job, cv_done;
+  std::deque<WbJob> jobs;
+  bool worker_started = false;
+  // stats / timing
+  pipemax_stats_t st{};
+  std::vector<Timed> timed;
+  std::vector<hipEvent_t> ev_free;
+
+  // ---- helpers ---------------------------------------------------------------------------------
+  bool timing() const { return cfg.flags & PIPEMAX_FLAG_TIME_KERNELS; }
+  hipEvent_t get_event() {
+    if (!ev_free.empty()) {
+      hipEvent_t e = ev_free.back();
+      ev_free.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  void tbegin(int cls, hipStream_t s) {
+    if (!timing()) return;
+    if (timed.size() >= 4096) resolve_timers(true);
+    Timed t{cls, get_event(), get_event()};
+    if (!t.a || !t.b) return;
+    (void)hipEventRecord(t.a, s);
+    timed.push_back(t);
+  }
+  void tend(hipStream_t s) {
+    if (!timing() || timed.empty()) return;
+    (void)hipEventRecord(timed.back().b, s);
+  }
+  // only_ready: keep the pairs whose second event has not completed yet
+  void resolve_timers(bool only_ready = false) {
+    std::vector<Timed> keep;
+    for (auto& t : timed) {
+      float ms = 0.f;
+      if (only_ready && hipEventQuery(t.b) != hipSuccess) {
+        keep.push_back(t);
+        continue;
+      }
+      if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) {
+        if (t.cls < PIPEMAX_N_KCLASS) {
+          st.kernel_ms[t.cls] += ms;
+          st.kernel_launches[t.cls] += 1;
+        } else if (t.cls == TC_H2D) {
+          st.h2d_ms += ms;
+        } else {
+          st.d2h_ms += ms;
+        }
+      }
+      ev_free.push_back(t.a);
+      ev_free.push_back(t.b);
+    }
+    timed.swap(keep);
+  }
+  char* host_page_ptr(int32_t page) const { return (char*)host_pool + (size_t)page * page_bytes; }
+  char* gpu_page_ptr(int32_t page) const { return (char*)gpu_pool + (size_t)page * page_bytes; }
+  void wait_mb_writeback(int mb) {
+    std::unique_lock<std::mutex> lk(mu);
+    if (mbs[mb].wb_pending == 0) return;
+    double t0 = now_s();
+    cv_done.wait(lk, [&] { return mbs[mb].wb_pending == 0; });
+    st.host_wait_s += now_s() - t0;
+  }
+  void wait_slot(int slot) {
+    std::unique_lock<std::mutex> lk(mu);
+    if (slot_pending[slot] == 0) return;
+    double t0 = now_s();
+    cv_done.wait(lk, [&] { return slot_pending[slot] == 0; });
+    st.host_wait_s += now_s() - t0;
+  }
+  void wait_all_writeback() {
+    std::unique_lock<std::mutex> lk(mu);
+    cv_done.wait(lk, [&] {
+      if (!jobs.empty()) return false;
+      for (int s = 0; s < kSlots; ++s)
+        if (slot_pending[s]) return false;
+      return true;
+    });
+  }
+};
+
+namespace {
+
+// ---- element scatter between the canonical [tok][Hkv][d] layout and a page -----------------------
+template <typename T>
+void scatter_token(const pipemax_stage* st, T* page, int layer, int slot, const T* k_row, const T* v_row) {
+  const int Hkv = st->D.Hkv, d = st->D.d;
+  for (int head = 0; head < Hkv; ++head) {
+    T* ks = page + sub_block_off(Hkv, d, layer, head, 0);
+    T* vs = page + sub_block_off(Hkv, d, layer, head, 1);
+    if (k_row) {
+      const T* kr = k_row + (size_t)head * d;
+      for (int dd = 0; dd < d; dd += 8) memcpy(ks + k_sub_idx(slot, dd), kr + dd, 8 * sizeof(T));
+    }
+    if (v_row) {
+      const T* vr = v_row + (size_t)head * d;
+      for (int dd = 0; dd < d; ++dd) vs[v_sub_idx(slot, dd)] = vr[dd];
+    }
+  }
+}
+template <typename T>
+void gather_token(const pipemax_stage* st, const T* page, int layer, int slot, T* k_row, T* v_row) {
+  const int Hkv = st->D.Hkv, d = st->D.d;
+  for (int head = 0; head < Hkv; ++head) {
+    const T* ks = page + sub_block_off(Hkv, d, layer, head, 0);
+    const T* vs = page + sub_block_off(Hkv, d, layer, head, 1);
+    if (k_row)
+      for (int dd = 0; dd < d; dd += 8) memcpy(k_row + (size_t)head * d + dd, ks + k_sub_idx(slot, dd), 8 * sizeof(T));
+    if (v_row)
+      for (int dd = 0; dd < d; ++dd) v_row[(size_t)head * d + dd] = vs[v_sub_idx(slot, dd)];
+  }
+}
+
+void worker_main(pipemax_stage* st) {
+  (void)hipSetDevice(st->dev);
+  for (;;) {
+    WbJob job;
+    {
+      std::unique_lock<std::mutex> lk(st->mu);
+      st->cv_job.wait(lk, [&] { return !st->jobs.empty(); });
+      job = st->jobs.front();
+      st->jobs.pop_front();
+    }
+    if (job.stop) return;
+    (void)hipEventSynchronize(job.ev);
+    const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
+    const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
+    const char* src = (const char*)st->h_stage[job.slot] + (size_t)job.layer * layer_elems * st->esz;
+    for (int i = 0; i < job.b; ++i) {
+      const auto& wh = (*job.where)[i];
+      char* page = st->host_page_ptr(wh.first);
+      const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
+      const char* vr = src + ((size_t)i * 2 + 1) * row * st->esz;
+      if (st->esz == 4)
+        scatter_token<float>(st, (float*)page, job.layer, wh.second, (const float*)kr, (const float*)vr);
+      else
+        scatter_token<uint16_t>(st, (uint16_t*)page, job.layer, wh.second, (const uint16_t*)kr,
+                                (const uint16_t*)vr);
+    }
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      st->mbs[job.mb].wb_pending -= 1;
+      st->slot_pending[job.slot] -= 1;
+      st->st.relayout_jobs += 1;
+    }
+    st->cv_done.notify_all();
+  }
+}
+
+template <typename T>
+int dev_alloc(pipemax_stage* st, T** p, size_t count) {
+  void* q = nullptr;
+  if (count == 0) count = 1;
+  hipError_t e = hipMalloc(&q, count * sizeof(T));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    PMX_FAIL(PIPEMAX_ERR_OOM_DEVICE, "hipMalloc of %zu bytes failed: %s", count * sizeof(T),
+             hipGetErrorString(e));
+  }
+  st->dev_allocs.push_back(q);
+  *p = (T*)q;
+  return PIPEMAX_OK;
+}
+template <typename T>
+int host_alloc(pipemax_stage* st, T** p, size_t count) {
+  void* q = nullptr;
+  if (count == 0) count = 1;
+  hipError_t e = hipHostMalloc(&q, count * sizeof(T), hipHostMallocDefault);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    PMX_FAIL(PIPEMAX_ERR_OOM_HOST, "hipHostMalloc of %zu bytes failed: %s", count * sizeof(T),
+             hipGetErrorString(e));
+  }
+  st->host_allocs.push_back(q);
+  *p = (T*)q;
+  return PIPEMAX_OK;
+}
+
+GemmPlan plan_gemm(int N, int K) {
+  GemmPlan p;
+  p.wn = (N % 256 == 0) ? 8 : 4;
+  const int groups = N / (32 * p.wn);
+  const int KT = K / 16;
+  int S = (512 + groups - 1) / groups;
+  S = std::max(1, std::min(S, std::max(1, KT / 16)));
+  const int ksp = (KT + S - 1) / S;
+  p.split = (KT + ksp - 1) / ksp;
+  return p;
+}
+
+bool mfma_shape_ok(const pipemax_config_t& c) {
+  const int nq = c.n_q_heads * c.head_dim;
+  return c.dtype == PIPEMAX_BF16 && c.head_dim == 128 && c.hidden % 128 == 0 && c.ffn % 64 == 0 &&
+         nq % 16 == 0 && c.max_seqs_per_mb <= 256 && c.n_q_heads / c.n_kv_heads <= 16;
+}
+
+void destroy_impl(pipemax_stage* st) {
+  if (!st) return;
+  (void)hipSetDevice(st->dev);
+  if (st->worker_started) {
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      WbJob stop;
+      stop.stop = true;
+      st->jobs.push_back(stop);
+    }
+    st->cv_job.notify_all();
+    st->worker.join();
+  }
+  (void)hipDeviceSynchronize();
+  st->timed.clear();
+  for (auto e : st->ev_free) (void)hipEventDestroy(e);
+  for (auto& mb : st->mbs) {
+    if (mb.ev_prefetch) (void)hipEventDestroy(mb.ev_prefetch);
+    if (mb.ev_step) (void)hipEventDestroy(mb.ev_step);
+  }
+  for (int s = 0; s < kSlots; ++s) {
+    for (auto e : st->ev_ready[s]) (void)hipEventDestroy(e);
+    for (auto e : st->ev_copied[s]) (void)hipEventDestroy(e);
+  }
+  for (int r = 0; r < kTableRing; ++r)
+    if (st->ev_table[r]) (void)hipEventDestroy(st->ev_table[r]);
+  if (st->ev_h2d_fence) (void)hipEventDestroy(st->ev_h2d_fence);
+  for (void* p : st->dev_allocs) (void)hipFree(p);
+  for (void* p : st->host_allocs) (void)hipHostFree(p);
+  if (st->gpu_pool) (void)hipFree(st->gpu_pool);
+  if (st->host_pool) (void)hipHostFree(st->host_pool);
+  if (st->s_own) (void)hipStreamDestroy(st->s_own);
+  if (st->s_h2d) (void)hipStreamDestroy(st->s_h2d);
+  if (st->s_d2h) (void)hipStreamDestroy(st->s_d2h);
+  delete st;
+}
+
+int check_mb(pipemax_stage* st, int mb, bool must_be_defined) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  if (mb < 0 || mb >= st->cfg.n_microbatches) PMX_FAIL(PIPEMAX_ERR_ARG, "micro-batch %d out of range", mb);
+  if (must_be_defined && !st->mbs[mb].defined) PMX_FAIL(PIPEMAX_ERR_ARG, "micro-batch %d is not defined", mb);
+  return PIPEMAX_OK;
+}
+
+// resolves a (seq_ids, n) argument into a list of distinct valid sequence indices
+int seq_list(pipemax_stage* st, int mb, const int32_t* ids, int n, std::vector<int>& out) {
+  MicroBatch& M = st->mbs[mb];
+  out.clear();
+  if (!ids) {
+    for (int i = 0; i < M.b; ++i) out.push_back(i);
+    return PIPEMAX_OK;
+  }
+  if (n < 0) PMX_FAIL(PIPEMAX_ERR_ARG, "negative sequence count");
+  std::vector<char> seen(M.b, 0);
+  for (int k = 0; k < n; ++k) {
+    if (ids[k] < 0 || ids[k] >= M.b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", ids[k]);
+    if (!seen[ids[k]]) {
+      seen[ids[k]] = 1;
+      out.push_back(ids[k]);
+    }
+  }
+  return PIPEMAX_OK;
+}
+
+int kv_rw_check(pipemax_stage* st, int mb, int seq, int layer, int tok0, int ntok) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  if (seq < 0 || seq >= M.b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", seq);
+  if (layer < 0 || layer >= st->cfg.n_layers) PMX_FAIL(PIPEMAX_ERR_ARG, "layer %d out of range", layer);
+  if (tok0 < 0 || ntok < 0 || tok0 + ntok > M.seq[seq].len)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "token range [%d, %d) outside the sequence's %d tokens", tok0, tok0 + ntok,
+             M.seq[seq].len);
+  return PIPEMAX_OK;
+}
+
+}  // namespace
+
+// =================================================================================================
+// C ABI
+// =================================================================================================
+extern "C" {
+
+const char* pipemax_last_error(void) { return g_err; }
+const char* pipemax_version(void) { return "pipemax-stage 0.1 (gfx950)"; }
+
+int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
+  if (!cfg || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  *out = nullptr;
+  const pipemax_config_t& c = *cfg;
+  if (c.n_layers < 1 || c.hidden < 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.head_dim < 32 ||
+      c.ffn < 1 || c.n_microbatches < 1 || c.max_seqs_per_mb < 1 || c.max_ctx < 1)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "non-positive shape field");
+  if (c.dtype != PIPEMAX_F32 && c.dtype != PIPEMAX_BF16) PMX_FAIL(PIPEMAX_ERR_ARG, "unknown dtype %d", c.dtype);
+  if (c.page_tokens != kPageTokens) PMX_FAIL(PIPEMAX_ERR_ARG, "page_tokens must be %d", kPageTokens);
+  if (c.n_q_heads % c.n_kv_heads) PMX_FAIL(PIPEMAX_ERR_ARG, "n_q_heads must be a multiple of n_kv_heads");
+  if (c.head_dim % 32 || c.head_dim > 512) PMX_FAIL(PIPEMAX_ERR_ARG, "head_dim must be a multiple of 32, at most 512");
+  if (c.max_seqs_per_mb > 65535) PMX_FAIL(PIPEMAX_ERR_ARG, "max_seqs_per_mb too large");
+  if (!(c.rope_base > 1.0f) || !(c.rms_eps >= 0.0f)) PMX_FAIL(PIPEMAX_ERR_ARG, "bad rope_base / rms_eps");
+  int ndev = 0;
+  PMX_HIP(hipGetDeviceCount(&ndev));
+  if (c.device < 0 || c.device >= ndev) PMX_FAIL(PIPEMAX_ERR_ARG, "device %d not present (%d devices)", c.device, ndev);
+
+  pipemax_stage* st = new (std::nothrow) pipemax_stage();
+  if (!st) PMX_FAIL(PIPEMAX_ERR_OOM_HOST, "out of host memory");
+  st->cfg = c;
+  st->dev = c.device;
+  st->esz = (c.dtype == PIPEMAX_F32) ? 4 : 2;
+  Dims& D = st->D;
+  D.n_layers = c.n_layers; D.h = c.hidden; D.Hq = c.n_q_heads; D.Hkv = c.n_kv_heads; D.d = c.head_dim;
+  D.F = c.ffn; D.Nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; D.G = c.n_q_heads / c.n_kv_heads;
+  D.rope_base = c.rope_base; D.eps = c.rms_eps;
+  D.max_pages = (c.max_ctx + kPageTokens - 1) / kPageTokens;
+  D.max_ctx_pad = D.max_pages * kPageTokens;
+  D.page_elems = page_elems(c.n_layers, c.n_kv_heads, c.head_dim);
+  st->page_bytes = (size_t)D.page_elems * st->esz;
+  st->engine = (mfma_shape_ok(c) && !(c.flags & PIPEMAX_FLAG_FORCE_GENERIC)) ? 1 : 0;
+  const int n_gpu_pages = (int)std::min<uint64_t>(c.gpu_kv_bytes / st->page_bytes, 1u << 30);
+  const int n_host_pages = (int)std::min<uint64_t>(c.host_kv_bytes / st->page_bytes, 1u << 30);
+  if (n_gpu_pages < 1 || n_host_pages < 1) {
+    delete st;
+    PMX_FAIL(PIPEMAX_ERR_ARG, "pools must hold at least one page of %zu bytes", st->page_bytes);
+  }
+
+#define PMX_TRY(expr)           \
+  do {                          \
+    int rc_ = (expr);           \
+    if (rc_ != PIPEMAX_OK) {    \
+      destroy_impl(st);         \
+      return rc_;               \
+    }                           \
+  } while (0)
+#define PMX_TRY_HIP(expr)                                                                       \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) {                                                                     \
+      set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__);     \
+      destroy_impl(st);                                                                         \
+      return PIPEMAX_ERR_HIP;                                                                   \
+    }                                                                                           \
+  } while (0)
+
+  PMX_TRY_HIP(hipSetDevice(st->dev));
+  PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_own, hipStreamNonBlocking));
+  PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_h2d, hipStreamNonBlocking));
+  PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_d2h, hipStreamNonBlocking));
+  st->s_last = st->s_own;
+
+  // pools
+  {
+    hipError_t e = hipMalloc(&st->gpu_pool, (size_t)n_gpu_pages * st->page_bytes);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      set_error("hipMalloc of the GPU page pool (%zu bytes) failed: %s", (size_t)n_gpu_pages * st->page_bytes,
+                hipGetErrorString(e));
+      st->gpu_pool = nullptr;
+      destroy_impl(st);
+      return PIPEMAX_ERR_OOM_DEVICE;
+    }
+    e = hipHostMalloc(&st->host_pool, (size_t)n_host_pages * st->page_bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      set_error("hipHostMalloc of the host page pool (%zu bytes) failed: %s",
+                (size_t)n_host_pages * st->page_bytes, hipGetErrorString(e));
+      st->host_pool = nullptr;
+      destroy_impl(st);
+      return PIPEMAX_ERR_OOM_HOST;
+    }
+    // unused slots of every page must hold finite values (the attention kernel multiplies them by 0)
+    memset(st->host_pool, 0, (size_t)n_host_pages * st->page_bytes);
+    PMX_TRY_HIP(hipMemset(st->gpu_pool, 0, (size_t)n_gpu_pages * st->page_bytes));
+  }
+  st->gpu_pages.reset(new PagePool(n_gpu_pages));
+  st->host_pages.reset(new PagePool(n_host_pages));
+
+  const int maxb = c.max_seqs_per_mb;
+  const int h = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
+  st->mbs.resize(c.n_microbatches);
+  for (auto& M : st->mbs) {
+    PMX_TRY(dev_alloc(st, &M.d_ctx, (size_t)maxb));
+    PMX_TRY(dev_alloc(st, &M.d_table, (size_t)maxb * D.max_pages));
+    PMX_TRY_HIP(hipMemset(M.d_table, 0, (size_t)maxb * D.max_pages * sizeof(int)));
+    PMX_TRY_HIP(hipMemset(M.d_ctx, 0, (size_t)maxb * sizeof(int)));
+    PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_prefetch, hipEventDisableTiming));
+    PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_step, hipEventDisableTiming));
+  }
+  PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_h2d_fence, hipEventDisableTiming));
+
+  // weights (internal layouts have the same sizes as the canonical ones)
+  st->w.resize(c.n_layers);
+  for (auto& L : st->w) {
+    char* p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)h * D.Nqkv * st->esz)); L.wqkv = p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)nq * h * st->esz));     L.wo = p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)h * 2 * F * st->esz));  L.wgu = p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)F * h * st->esz));      L.wd = p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)h * st->esz));          L.g1 = p;
+    PMX_TRY(dev_alloc(st, &p, (size_t)h * st->esz));          L.g2 = p;
+    PMX_TRY_HIP(hipMemset(L.wqkv, 0, (size_t)h * D.Nqkv * st->esz));
+    PMX_TRY_HIP(hipMemset(L.wo, 0, (size_t)nq * h * st->esz));
+    PMX_TRY_HIP(hipMemset(L.wgu, 0, (size_t)h * 2 * F * st->esz));
+    PMX_TRY_HIP(hipMemset(L.wd, 0, (size_t)F * h * st->esz));
+    PMX_TRY_HIP(hipMemset(L.g1, 0, (size_t)h * st->esz));
+    PMX_TRY_HIP(hipMemset(L.g2, 0, (size_t)h * st->esz));
+  }
+
+  // activations
+  const int mpad = ((maxb + 31) / 32) * 32;
+  // the GEMM kernels are instantiated for 1, 2, 4 or 8 row tiles of 32 and read all of them
+  const int mtile = (maxb <= 32) ? 32 : (maxb <= 64) ? 64 : (maxb <= 128) ? 128 : 256;
+  PMX_TRY(dev_alloc(st, &st->x, (size_t)mpad * h));
+  PMX_TRY(dev_alloc(st, &st->rope_cs, (size_t)maxb * (c.head_dim / 2)));
+  if (st->engine == 0) {
+    PMX_TRY(dev_alloc(st, &st->g_xn, (size_t)maxb * h));
+    PMX_TRY(dev_alloc(st, &st->g_qkv, (size_t)maxb * D.Nqkv));
+    PMX_TRY(dev_alloc(st, &st->g_q, (size_t)maxb * nq));
+    PMX_TRY(dev_alloc(st, &st->g_attn, (size_t)maxb * nq));
+    PMX_TRY(dev_alloc(st, &st->g_gu, (size_t)maxb * 2 * F));
+    PMX_TRY(dev_alloc(st, &st->g_act, (size_t)maxb * F));
+    PMX_TRY(dev_alloc(st, &st->g_scores, (size_t)maxb * c.n_q_heads * D.max_ctx_pad));
+  } else {
+    st->p_qkv = plan_gemm(D.Nqkv, h);
+    st->p_o = plan_gemm(h, nq);
+    st->p_gu = plan_gemm(2 * F, h);
+    st->p_d = plan_gemm(h, F);
+    size_t part = 0;
+    part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
+    part = std::max(part, (size_t)st->p_o.split * mpad * h);
+    part = std::max(part, (size_t)st->p_gu.split * mpad * 2 * F);
+    part = std::max(part, (size_t)st->p_d.split * mpad * h);
+    PMX_TRY(dev_alloc(st, &st->m_part, part));
+    PMX_TRY(dev_alloc(st, &st->m_xn_t, (size_t)mtile * h));
+    PMX_TRY(dev_alloc(st, &st->m_q, (size_t)maxb * nq));
+    PMX_TRY(dev_alloc(st, &st->m_attn_t, (size_t)mtile * nq));
+    PMX_TRY(dev_alloc(st, &st->m_act_t, (size_t)mtile * F));
+    PMX_TRY_HIP(hipMemset(st->m_xn_t, 0, (size_t)mtile * h * 2));
+    PMX_TRY_HIP(hipMemset(st->m_attn_t, 0, (size_t)mtile * nq * 2));
+    PMX_TRY_HIP(hipMemset(st->m_act_t, 0, (size_t)mtile * F * 2));
+    st->nch_alloc = (D.max_pages + 7) / 8;
+    PMX_TRY(dev_alloc(st, &st->m_part_o, (size_t)maxb * c.n_q_heads * st->nch_alloc * 128));
+    PMX_TRY(dev_alloc(st, &st->m_part_ml, (size_t)maxb * c.n_q_heads * st->nch_alloc * 2));
+  }
+  if (c.flags & PIPEMAX_FLAG_CAPTURE_LAYERS) PMX_TRY(dev_alloc(st, &st->layer_out, (size_t)c.n_layers * maxb * h));
+
+  // write-back staging ring + table ring
+  const size_t stage_bytes = (size_t)c.n_layers * maxb * 2 * c.n_kv_heads * c.head_dim * st->esz;
+  for (int s = 0; s < kSlots; ++s) {
+    char* p;
+    PMX_TRY(dev_alloc(st, &p, stage_bytes)); st->d_stage[s] = p;
+    PMX_TRY(host_alloc(st, &p, stage_bytes)); st->h_stage[s] = p;
+    st->ev_ready[s].resize(c.n_layers, nullptr);
+    st->ev_copied[s].resize(c.n_layers, nullptr);
+    for (int l = 0; l < c.n_layers; ++l) {
+      PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_ready[s][l], hipEventDisableTiming));
+      PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_copied[s][l], hipEventDisableTiming));
+    }
+  }
+  for (int r = 0; r < kTableRing; ++r) {
+    PMX_TRY(host_alloc(st, &st->h_table[r], (size_t)maxb * D.max_pages));
+    PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_table[r], hipEventDisableTiming));
+  }
+  PMX_TRY_HIP(hipDeviceSynchronize());
+#undef PMX_TRY
+#undef PMX_TRY_HIP
+
+  st->worker = std::thread(worker_main, st);
+  st->worker_started = true;
+  st->st.engine = st->engine;
+  *out = st;
+  return PIPEMAX_OK;
+}
+
+int pipemax_stage_destroy(pipemax_stage_t* st) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  destroy_impl(st);
+  return PIPEMAX_OK;
+}
+
+int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* host, size_t bytes) {
+  if (!st || !host) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  if (layer < 0 || layer >= st->cfg.n_layers) PMX_FAIL(PIPEMAX_ERR_ARG, "layer %d out of range", layer);
+  const Dims& D = st->D;
+  const int nq = D.Hq * D.d;
+  int K = 0, N = 0;
+  void* dst = nullptr;
+  LayerW& L = st->w[layer];
+  switch (which) {
+    case PIPEMAX_W_QKV: K = D.h; N = D.Nqkv; dst = L.wqkv; break;
+    case PIPEMAX_W_O: K = nq; N = D.h; dst = L.wo; break;
+    case PIPEMAX_W_GU: K = D.h; N = 2 * D.F; dst = L.wgu; break;
+    case PIPEMAX_W_D: K = D.F; N = D.h; dst = L.wd; break;
+    case PIPEMAX_G_ATTN: K = 1; N = D.h; dst = L.g1; break;
+    case PIPEMAX_G_FFN: K = 1; N = D.h; dst = L.g2; break;
+    default: PMX_FAIL(PIPEMAX_ERR_ARG, "unknown weight id %d", which);
+  }
+  const size_t want = (size_t)K * N * st->esz;
+  if (bytes != want) PMX_FAIL(PIPEMAX_ERR_ARG, "weight %d needs %zu bytes, got %zu", which, want, bytes);
+  PMX_HIP(hipSetDevice(st->dev));
+  if (st->engine == 0 || which >= PIPEMAX_G_ATTN) {
+    PMX_HIP(hipMemcpy(dst, host, want, hipMemcpyHostToDevice));
+    return PIPEMAX_OK;
+  }
+  // matrix-core engine: re-tile into B-operand fragments.  The gate/up matrix additionally
+  // interleaves 32-column tiles (gate tile j, up tile j) so that one work-group column range
+  // holds both halves of the same FFN columns.
+  std::vector<uint16_t> tiled;
+  try {
+    tiled.resize((size_t)K * N);
+  } catch (...) {
+    PMX_FAIL(PIPEMAX_ERR_OOM_HOST, "out of host memory re-tiling a weight");
+  }
+  const uint16_t* src = (const uint16_t*)host;
+  const int KT = K / 16;
+  const int F = D.F;
+  const int NT = N / 32;
+#pragma omp parallel for schedule(static)
+  for (int nt = 0; nt < NT; ++nt) {
+    int src_col0;
+    if (which == PIPEMAX_W_GU) src_col0 = (nt & 1) ? (F + (nt >> 1) * 32) : ((nt >> 1) * 32);
+    else src_col0 = nt * 32;
+    for (int kt = 0; kt < KT; ++kt) {
+      uint16_t* frag = tiled.data() + ((size_t)nt * KT + kt) * 512;
+      for (int lane = 0; lane < 64; ++lane) {
+        const int n = src_col0 + (lane & 31);
+        const int kb = kt * 16 + (lane >> 5) * 8;
+        for (int e = 0; e < 8; ++e) frag[lane * 8 + e] = src[(size_t)(kb + e) * N + n];
+      }
+    }
+  }
+  PMX_HIP(hipMemcpy(dst, tiled.data(), want, hipMemcpyHostToDevice));
+  return PIPEMAX_OK;
+}
+
+int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ctx_lens) {
+  int rc = check_mb(st, mb, false);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  if (M.defined) PMX_FAIL(PIPEMAX_ERR_ARG, "micro-batch %d is already defined", mb);
+  if (!ctx_lens || n_seqs < 1 || n_seqs > st->cfg.max_seqs_per_mb)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "n_seqs %d outside [1, %d]", n_seqs, st->cfg.max_seqs_per_mb);
+  int64_t need = 0;
+  for (int i = 0; i < n_seqs; ++i) {
+    if (ctx_lens[i] < 0 || ctx_lens[i] > st->cfg.max_ctx)
+      PMX_FAIL(PIPEMAX_ERR_ARG, "context length %d outside [0, %d]", ctx_lens[i], st->cfg.max_ctx);
+    need += (ctx_lens[i] + kPageTokens - 1) / kPageTokens;
+  }
+  if (need > st->host_pages->free_count())
+    PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "host pool has %d free pages, %lld needed", st->host_pages->free_count(),
+             (long long)need);
+  PMX_HIP(hipSetDevice(st->dev));
+  M.seq.assign(n_seqs, SeqState());
+  for (int i = 0; i < n_seqs; ++i) {
+    SeqState& S = M.seq[i];
+    S.len = ctx_lens[i];
+    S.state = ST_HOST;
+    const int np = (S.len + kPageTokens - 1) / kPageTokens;
+    S.host.resize(np);
+    st->host_pages->alloc(np, S.host.data());
+  }
+  PMX_HIP(hipMemcpy(M.d_ctx, ctx_lens, (size_t)n_seqs * sizeof(int), hipMemcpyHostToDevice));
+  M.b = n_seqs;
+  M.defined = true;
+  M.table_dirty = true;
+  return PIPEMAX_OK;
+}
+
+int pipemax_kv_host_write(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok,
+                          const void* K, const void* V) {
+  int rc = kv_rw_check(st, mb, seq, layer, tok0, ntok);
+  if (rc) return rc;
+  if (!K || !V) PMX_FAIL(PIPEMAX_ERR_ARG, "null K/V");
+  SeqState& S = st->mbs[mb].seq[seq];
+  if (S.state != ST_HOST) PMX_FAIL(PIPEMAX_ERR_STATE, "kv_host_write needs a HOST-resident sequence");
+  st->wait_mb_writeback(mb);
+  const size_t row = (size_t)st->D.Hkv * st->D.d;
+  for (int t = 0; t < ntok; ++t) {
+    const int tok = tok0 + t;
+    char* page = st->host_page_ptr(S.host[tok / kPageTokens]);
+    if (st->esz == 4)
+      scatter_token<float>(st, (float*)page, layer, tok % kPageTokens, (const float*)K + t * row,
+                           (const float*)V + t * row);
+    else
+      scatter_token<uint16_t>(st, (uint16_t*)page, layer, tok % kPageTokens, (const uint16_t*)K + t * row,
+                              (const uint16_t*)V + t * row);
+  }
+  return PIPEMAX_OK;
+}
+
+int pipemax_kv_host_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok, void* K,
+                         void* V) {
+  int rc = kv_rw_check(st, mb, seq, layer, tok0, ntok);
+  if (rc) return rc;
+  if (!K || !V) PMX_FAIL(PIPEMAX_ERR_ARG, "null K/V");
+  SeqState& S = st->mbs[mb].seq[seq];
+  st->wait_mb_writeback(mb);
+  const size_t row = (size_t)st->D.Hkv * st->D.d;
+  for (int t = 0; t < ntok; ++t) {
+    const int tok = tok0 + t;
+    const char* page = st->host_page_ptr(S.host[tok / kPageTokens]);
+    if (st->esz == 4)
+      gather_token<float>(st, (const float*)page, layer, tok % kPageTokens, (float*)K + t * row, (float*)V + t * row);
+    else
+      gather_token<uint16_t>(st, (const uint16_t*)page, layer, tok % kPageTokens, (uint16_t*)K + t * row,
+                             (uint16_t*)V + t * row);
+  }
+  return PIPEMAX_OK;
+}
+
+int pipemax_kv_dev_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok, void* K,
+                        void* V) {
+  int rc = kv_rw_check(st, mb, seq, layer, tok0, ntok);
+  if (rc) return rc;
+  if (!K || !V) PMX_FAIL(PIPEMAX_ERR_ARG, "null K/V");
+  SeqState& S = st->mbs[mb].seq[seq];
+  if (S.state == ST_HOST) PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d has no GPU pages", seq, mb);
+  rc = pipemax_sync(st);
+  if (rc) return rc;
+  const int Hkv = st->D.Hkv, d = st->D.d;
+  const size_t row = (size_t)Hkv * d;
+  const size_t layer_bytes = (size_t)Hkv * 2 * kPageTokens * d * st->esz;   // one layer's slice of a page
+  std::vector<char> tmp(st->page_bytes);
+  int cached = -1;
+  for (int t = 0; t < ntok; ++t) {
+    const int tok = tok0 + t, pi = tok / kPageTokens;
+    if (pi != cached) {
+      const size_t off = (size_t)sub_block_off(Hkv, d, layer, 0, 0) * st->esz;
+      PMX_HIP(hipMemcpy(tmp.data() + off, st->gpu_page_ptr(S.gpu[pi]) + off, layer_bytes, hipMemcpyDeviceToHost));
+      cached = pi;
+    }
+    if (st->esz == 4)
+      gather_token<float>(st, (const float*)tmp.data(), layer, tok % kPageTokens, (float*)K + t * row, (float*)V + t * row);
+    else
+      gather_token<uint16_t>(st, (const uint16_t*)tmp.data(), layer, tok % kPageTokens, (uint16_t*)K + t * row,
+                             (uint16_t*)V + t * row);
+  }
+  return PIPEMAX_OK;
+}
+
+// ---- prefetch / evict -----------------------------------------------------------------------------
+int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  std::vector<int> ids;
+  rc = seq_list(st, mb, seq_ids, n, ids);
+  if (rc) return rc;
+  std::vector<int> todo;
+  int64_t need = 0;
+  for (int i : ids)
+    if (M.seq[i].state == ST_HOST) {
+      todo.push_back(i);
+      need += (int64_t)M.seq[i].host.size();
+    }
+  if (todo.empty()) return PIPEMAX_OK;
+  if (need > st->gpu_pages->free_count())
+    PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "GPU pool has %d free pages, %lld needed", st->gpu_pages->free_count(),
+             (long long)need);
+  PMX_HIP(hipSetDevice(st->dev));
+  st->wait_mb_writeback(mb);     // the host replica of mb must be complete before it is read
+  std::vector<int32_t> src, dst;
+  src.reserve(need);
+  dst.reserve(need);
+  for (int i : todo) {
+    SeqState& S = M.seq[i];
+    S.gpu.resize(S.host.size());
+    st->gpu_pages->alloc((int)S.gpu.size(), S.gpu.data());
+    S.state = ST_INFLIGHT;
+    src.insert(src.end(), S.host.begin(), S.host.end());
+    dst.insert(dst.end(), S.gpu.begin(), S.gpu.end());
+  }
+  M.table_dirty = true;
+  std::vector<CopyRun> runs;
+  plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, runs);
+  st->tbegin(TC_H2D, st->s_h2d);
+  for (const CopyRun& r : runs) {
+    PMX_HIP(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
+                           hipMemcpyHostToDevice, st->s_h2d));
+    st->st.h2d_bytes += (uint64_t)r.count * st->page_bytes;
+    st->st.h2d_copies += 1;
+  }
+  st->tend(st->s_h2d);
+  PMX_HIP(hipEventRecord(M.ev_prefetch, st->s_h2d));
+  M.prefetch_pending = true;
+  return PIPEMAX_OK;
+}
+
+int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  std::vector<int> ids;
+  rc = seq_list(st, mb, seq_ids, n, ids);
+  if (rc) return rc;
+  bool any = false, any_inflight = false;
+  for (int i : ids)
+    if (M.seq[i].state != ST_HOST) {
+      any = true;
+      any_inflight |= (M.seq[i].state == ST_INFLIGHT);
+    }
+  if (!any) return PIPEMAX_OK;
+  PMX_HIP(hipSetDevice(st->dev));
+  // later prefetches into these pages must come after the last step that read them
+  if (M.stepped) PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
+  // pages of a cancelled prefetch may be handed to a decode step's growth: fence the compute stream
+  if (any_inflight) {
+    PMX_HIP(hipEventRecord(st->ev_h2d_fence, st->s_h2d));
+    st->h2d_fence_pending = true;
+  }
+  for (int i : ids) {
+    SeqState& S = M.seq[i];
+    if (S.state == ST_HOST) continue;
+    st->gpu_pages->release(S.gpu.data(), (int)S.gpu.size());
+    S.gpu.clear();
+    S.state = ST_HOST;
+  }
+  M.table_dirty = true;
+  return PIPEMAX_OK;
+}
+
+// ---- the decode step ----------------------------------------------------------------------------------
+int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
+                        void* hip_stream) {
+  const double t_enter = now_s();
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
+  MicroBatch& M = st->mbs[mb];
+  const Dims& D = st->D;
+  const int b = M.b, nl = st->cfg.n_layers;
+  int grow = 0, max_len = 0;
+  for (int i = 0; i < b; ++i)
+    if (M.seq[i].state == ST_HOST)
+      PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", i, mb);
+  for (int i = 0; i < b; ++i) {
+    const SeqState& S = M.seq[i];
+    if (S.len + 1 > st->cfg.max_ctx)
+      PMX_FAIL(PIPEMAX_ERR_STATE, "sequence %d of micro-batch %d is at max_ctx %d", i, mb, st->cfg.max_ctx);
+    if (S.len % kPageTokens == 0) ++grow;
+    max_len = std::max(max_len, S.len);
+  }
+  if (grow > st->gpu_pages->free_count() || grow > st->host_pages->free_count())
+    PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", grow,
+             st->gpu_pages->free_count(), st->host_pages->free_count());
+  PMX_HIP(hipSetDevice(st->dev));
+  hipStream_t cs = hip_stream ? (hipStream_t)hip_stream : st->s_own;
+  st->s_last = cs;
+
+  // ---- bookkeeping: growth pages, positions of the new token ----------------------------------------
+  const bool writeback = !(st->cfg.flags & PIPEMAX_FLAG_NO_WRITEBACK);
+  auto where = std::make_shared<std::vector<std::pair<int32_t, int>>>(b);
+  for (int i = 0; i < b; ++i) {
+    SeqState& S = M.seq[i];
+    if (S.len % kPageTokens == 0) {
+      int32_t gp, hp;
+      st->gpu_pages->alloc(1, &gp);
+      st->host_pages->alloc(1, &hp);
+      S.gpu.push_back(gp);
+      S.host.push_back(hp);
+      M.table_dirty = true;
+    }
+    (*where)[i] = {S.host[S.len / kPageTokens], S.len % kPageTokens};
+  }
+
+  // ---- stream dependencies -----------------------------------------------------------------------
+  if (M.prefetch_pending) {
+    PMX_HIP(hipStreamWaitEvent(cs, M.ev_prefetch, 0));
+    M.prefetch_pending = false;
+  }
+  if (st->h2d_fence_pending) {
+    PMX_HIP(hipStreamWaitEvent(cs, st->ev_h2d_fence, 0));
+    st->h2d_fence_pending = false;
+  }
+  for (auto& S : M.seq) S.state = ST_GPU;
+  if (M.table_dirty) {
+    const int r = st->table_pos;
+    st->table_pos = (st->table_pos + 1) % kTableRing;
+    if (st->table_used[r]) PMX_HIP(hipEventSynchronize(st->ev_table[r]));
+    int32_t* ht = st->h_table[r];
+    for (int i = 0; i < b; ++i) {
+      const SeqState& S = M.seq[i];
+      int32_t* rowp = ht + (size_t)i * D.max_pages;
+      std::copy(S.gpu.begin(), S.gpu.end(), rowp);
+      std::fill(rowp + S.gpu.size(), rowp + D.max_pages, 0);
+    }
+    PMX_HIP(hipMemcpyAsync(M.d_table, ht, (size_t)b * D.max_pages * sizeof(int32_t), hipMemcpyHostToDevice, cs));
+    PMX_HIP(hipEventRecord(st->ev_table[r], cs));
+    st->table_used[r] = true;
+    M.table_dirty = false;
+    st->st.table_uploads += 1;
+  }
+  const int slot = (int)(st->step_no % kSlots);
+  if (writeback) st->wait_slot(slot);
+  const size_t row = (size_t)D.Hkv * D.d;
+  const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;
+  const size_t copy_bytes = (size_t)b * 2 * row * st->esz;
+
+  // ---- kernels ---------------------------------------------------------------------------------------
+  st->tbegin(PIPEMAX_K_MISC, cs);
+  launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
+  st->tend(cs);
+
+  auto after_append = [&](int l) -> int {
+    if (!writeback) return PIPEMAX_OK;
+    PMX_HIP(hipEventRecord(st->ev_ready[slot][l], cs));
+    PMX_HIP(hipStreamWaitEvent(st->s_d2h, st->ev_ready[slot][l], 0));
+    st->tbegin(TC_D2H, st->s_d2h);
+    PMX_HIP(hipMemcpyAsync((char*)st->h_stage[slot] + (size_t)l * layer_elems * st->esz,
+                           (char*)st->d_stage[slot] + (size_t)l * layer_elems * st->esz, copy_bytes,
+                           hipMemcpyDeviceToHost, st->s_d2h));
+    st->tend(st->s_d2h);
+    PMX_HIP(hipEventRecord(st->ev_copied[slot][l], st->s_d2h));
+    WbJob job;
+    job.ev = st->ev_copied[slot][l];
+    job.mb = mb; job.layer = l; job.slot = slot; job.b = b; job.where = where;
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      M.wb_pending += 1;
+      st->slot_pending[slot] += 1;
+      st->jobs.push_back(job);
+    }
+    st->cv_job.notify_one();
+    st->st.d2h_bytes += copy_bytes;
+    st->st.d2h_copies += 1;
+    return PIPEMAX_OK;
+  };
+
+  if (st->engine == 0) {
+    auto run = [&](auto tag) -> int {
+      using T = decltype(tag);
+      using Gk = Generic<T>;
+      st->tbegin(PIPEMAX_K_MISC, cs);
+      Gk::load_hidden(cs, (const T*)hidden_in, st->x, (int64_t)b * D.h);
+      st->tend(cs);
+      for (int l = 0; l < nl; ++l) {
+        const LayerW& L = st->w[l];
+        T* stage_l = (T*)st->d_stage[slot] + (size_t)l * layer_elems;
+        st->tbegin(PIPEMAX_K_NORM, cs);
+        Gk::rmsnorm(cs, st->x, (const T*)L.g1, st->g_xn, b, D.h, D.eps);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
+        Gk::gemm(cs, st->g_xn, (const T*)L.wqkv, st->g_qkv, b, D.h, D.Nqkv, 0);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
+        Gk::rope_append(cs, D, l, b, st->g_qkv, st->rope_cs, M.d_ctx, M.d_table, (T*)st->gpu_pool, stage_l, st->g_q);
+        st->tend(cs);
+        int rc2 = after_append(l);
+        if (rc2) return rc2;
+        st->tbegin(PIPEMAX_K_ATTN, cs);
+        Gk::attention(cs, D, l, b, st->g_q, (const T*)st->gpu_pool, M.d_table, M.d_ctx, st->g_scores, st->g_attn);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_O, cs);
+        Gk::gemm(cs, st->g_attn, (const T*)L.wo, st->x, b, D.Hq * D.d, D.h, 1);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_NORM, cs);
+        Gk::rmsnorm(cs, st->x, (const T*)L.g2, st->g_xn, b, D.h, D.eps);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_GU, cs);
+        Gk::gemm(cs, st->g_xn, (const T*)L.wgu, st->g_gu, b, D.h, 2 * D.F, 0);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_SWIGLU, cs);
+        launch_swiglu_generic(cs, st->g_gu, st->g_act, b, D.F);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_D, cs);
+        Gk::gemm(cs, st->g_act, (const T*)L.wd, st->x, b, D.F, D.h, 1);
+        st->tend(cs);
+        if (st->layer_out)
+          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)l * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                                 hipMemcpyDeviceToDevice, cs));
+      }
+      st->tbegin(PIPEMAX_K_MISC, cs);
+      Gk::store_hidden(cs, st->x, (T*)hidden_out, (int64_t)b * D.h);
+      st->tend(cs);
+      return PIPEMAX_OK;
+    };
+    rc = (st->esz == 4) ? run(float()) : run(uint16_t());
+    if (rc) return rc;
+  } else {
+    const int mpad = ((b + 31) / 32) * 32;
+    const int nq = D.Hq * D.d;
+    // attention split: about 2048 work-groups, 8..64 pages each
+    const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
+    const int nch_target = std::max(1, 2048 / (b * D.Hkv));
+    int CP = (npages_max + nch_target - 1) / nch_target;
+    CP = std::max(8, std::min(64, CP));
+    const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
+    const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
+    const float* prev_part = nullptr;     // partials of the previous layer's down projection
+    for (int l = 0; l < nl; ++l) {
+      const LayerW& L = st->w[l];
+      uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
+      st->tbegin(PIPEMAX_K_NORM, cs);
+      mfma::resid_norm(cs, b, D.h, D.eps, l == 0 ? (const uint16_t*)hidden_in : nullptr, prev_part,
+                       st->p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
+      st->tend(cs);
+      if (st->layer_out && l > 0)
+        PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                               hipMemcpyDeviceToDevice, cs));
+      st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
+      mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wqkv, st->m_part, b, D.h, D.Nqkv, st->p_qkv.split, st->p_qkv.wn);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
+      mfma::rope_append(cs, D, l, b, st->m_part, st->p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
+                        (uint16_t*)st->gpu_pool, stage_l, st->m_q);
+      st->tend(cs);
+      int rc2 = after_append(l);
+      if (rc2) return rc2;
+      st->tbegin(PIPEMAX_K_ATTN, cs);
+      mfma::attention(cs, D, l, b, st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, st->m_part_o,
+                      st->m_part_ml, CP, nch);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_ATTN_MERGE, cs);
+      mfma::attention_merge(cs, D, b, M.d_ctx, st->m_part_o, st->m_part_ml, CP, nch, st->m_attn_t);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_GEMM_O, cs);
+      mfma::gemm(cs, st->m_attn_t, (const uint16_t*)L.wo, st->m_part, b, nq, D.h, st->p_o.split, st->p_o.wn);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_NORM, cs);
+      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, st->p_o.split, s_h, st->x, (const uint16_t*)L.g2,
+                       st->m_xn_t, nullptr);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_GEMM_GU, cs);
+      mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wgu, st->m_part, b, D.h, 2 * D.F, st->p_gu.split, st->p_gu.wn);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_SWIGLU, cs);
+      mfma::swiglu(cs, b, D.F, st->m_part, st->p_gu.split, s_gu, st->m_act_t);
+      st->tend(cs);
+      st->tbegin(PIPEMAX_K_GEMM_D, cs);
+      mfma::gemm(cs, st->m_act_t, (const uint16_t*)L.wd, st->m_part, b, D.F, D.h, st->p_d.split, st->p_d.wn);
+      st->tend(cs);
+      prev_part = st->m_part;
+    }
+    st->tbegin(PIPEMAX_K_NORM, cs);
+    mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, st->p_d.split, s_h, st->x, nullptr, nullptr,
+                     (uint16_t*)hidden_out);
+    st->tend(cs);
+    if (st->layer_out)
+      PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(nl - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                             hipMemcpyDeviceToDevice, cs));
+  }
+  st->tbegin(PIPEMAX_K_MISC, cs);
+  launch_advance_ctx(cs, M.d_ctx, b);
+  st->tend(cs);
+  PMX_HIP(hipEventRecord(M.ev_step, cs));
+  PMX_HIP(hipGetLastError());
+  M.stepped = true;
+  for (auto& S : M.seq) S.len += 1;
+  st->last_b = b;
+  st->step_no += 1;
+  st->st.steps += 1;
+  st->st.tokens += (uint64_t)b;
+  st->st.host_enqueue_s += now_s() - t_enter;
+  return PIPEMAX_OK;
+}
+
+int pipemax_sync(pipemax_stage_t* st) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  PMX_HIP(hipSetDevice(st->dev));
+  PMX_HIP(hipStreamSynchronize(st->s_last));
+  if (st->s_last != st->s_own) PMX_HIP(hipStreamSynchronize(st->s_own));
+  PMX_HIP(hipStreamSynchronize(st->s_h2d));
+  PMX_HIP(hipStreamSynchronize(st->s_d2h));
+  st->wait_all_writeback();
+  for (auto& M : st->mbs) {
+    if (!M.defined) continue;
+    M.prefetch_pending = false;
+    for (auto& S : M.seq)
+      if (S.state == ST_INFLIGHT) S.state = ST_GPU;
+  }
+  st->h2d_fence_pending = false;
+  return PIPEMAX_OK;
+}
+
+// ---- introspection ---------------------------------------------------------------------------------------
+int pipemax_get_stats(pipemax_stage_t* st, pipemax_stats_t* out) {
+  if (!st || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  if (st->timing()) {
+    int rc = pipemax_sync(st);
+    if (rc) return rc;
+    st->resolve_timers();
+  }
+  {
+    std::lock_guard<std::mutex> lk(st->mu);
+    *out = st->st;
+  }
+  out->engine = st->engine;
+  out->gpu_pages_total = st->gpu_pages->total();
+  out->gpu_pages_free = st->gpu_pages->free_count();
+  out->host_pages_total = st->host_pages->total();
+  out->host_pages_free = st->host_pages->free_count();
+  out->page_bytes = st->page_bytes;
+  return PIPEMAX_OK;
+}
+
+int pipemax_reset_stats(pipemax_stage_t* st) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  if (st->timing()) {
+    int rc = pipemax_sync(st);
+    if (rc) return rc;
+    st->resolve_timers();
+  }
+  std::lock_guard<std::mutex> lk(st->mu);
+  st->st = pipemax_stats_t{};
+  st->st.engine = st->engine;
+  return PIPEMAX_OK;
+}
+
+int pipemax_get_ctx_lens(pipemax_stage_t* st, int mb, int32_t* out) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!out) PMX_FAIL(PIPEMAX_ERR_ARG, "null output");
+  for (int i = 0; i < st->mbs[mb].b; ++i) out[i] = st->mbs[mb].seq[i].len;
+  return PIPEMAX_OK;
+}
+
+int pipemax_get_residency(pipemax_stage_t* st, int mb, int32_t* out) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!out) PMX_FAIL(PIPEMAX_ERR_ARG, "null output");
+  for (int i = 0; i < st->mbs[mb].b; ++i) out[i] = st->mbs[mb].seq[i].state;
+  return PIPEMAX_OK;
+}
+
+int pipemax_get_block_table(pipemax_stage_t* st, int mb, int seq, int32_t* gpu_pages, int32_t* host_pages,
+                            int* n) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!n) PMX_FAIL(PIPEMAX_ERR_ARG, "null count");
+  MicroBatch& M = st->mbs[mb];
+  if (seq < 0 || seq >= M.b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", seq);
+  const SeqState& S = M.seq[seq];
+  const int np = (int)S.host.size();
+  if ((gpu_pages || host_pages) && *n < np) PMX_FAIL(PIPEMAX_ERR_ARG, "room for %d pages, %d needed", *n, np);
+  for (int p = 0; p < np; ++p) {
+    if (host_pages) host_pages[p] = S.host[p];
+    if (gpu_pages) gpu_pages[p] = (S.state == ST_HOST) ? -1 : S.gpu[p];
+  }
+  *n = np;
+  return PIPEMAX_OK;
+}
+
+int pipemax_get_layer_outputs(pipemax_stage_t* st, float* out, size_t bytes) {
+  if (!st || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  if (!st->layer_out) PMX_FAIL(PIPEMAX_ERR_STATE, "stage was created without PIPEMAX_FLAG_CAPTURE_LAYERS");
+  const size_t want = (size_t)st->cfg.n_layers * st->last_b * st->cfg.hidden * sizeof(float);
+  if (bytes != want) PMX_FAIL(PIPEMAX_ERR_ARG, "layer outputs are %zu bytes, got room for %zu", want, bytes);
+  int rc = pipemax_sync(st);
+  if (rc) return rc;
+  PMX_HIP(hipMemcpy(out, st->layer_out, want, hipMemcpyDeviceToHost));
+  return PIPEMAX_OK;
+}
+
+// ---- host-side planning helpers ------------------------------------------------------------------------------
+int64_t pipemax_page_elem_offset(int n_layers, int n_kv_heads, int head_dim, int layer, int kv, int head,
+                                 int tok, int dd) {
+  if (n_layers < 1 || n_kv_heads < 1 || head_dim < 32 || head_dim % 32 || layer < 0 || layer >= n_layers ||
+      kv < 0 || kv > 1 || head < 0 || head >= n_kv_heads || tok < 0 || tok >= kPageTokens || dd < 0 ||
+      dd >= head_dim)
+    return -1;
+  return sub_block_off(n_kv_heads, head_dim, layer, head, kv) + (kv ? v_sub_idx(tok, dd) : k_sub_idx(tok, dd));
+}
+
+int pipemax_plan_copy_runs(const int32_t* src_pages, const int32_t* dst_pages, int n, int max_run_pages,
+                           int32_t* runs) {
+  if (n < 0 || max_run_pages < 1 || (n > 0 && (!src_pages || !dst_pages || !runs)))
+    PMX_FAIL(PIPEMAX_ERR_ARG, "bad argument");
+  std::vector<CopyRun> out;
+  plan_copy_runs(src_pages, dst_pages, n, max_run_pages, out);
+  for (size_t i = 0; i < out.size(); ++i) {
+    runs[3 * i] = out[i].src;
+    runs[3 * i + 1] = out[i].dst;
+    runs[3 * i + 2] = out[i].count;
+  }
+  return (int)out.size();
+}
+
+int pipemax_pool_create(int n_pages, pipemax_pool_t** out) {
+  if (n_pages < 0 || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "bad argument");
+  *out = new (std::nothrow) pipemax_pool(n_pages);
+  if (!*out) PMX_FAIL(PIPEMAX_ERR_OOM_HOST, "out of host memory");
+  return PIPEMAX_OK;
+}
+int pipemax_pool_destroy(pipemax_pool_t* p) {
+  if (!p) PMX_FAIL(PIPEMAX_ERR_ARG, "null pool");
+  delete p;
+  return PIPEMAX_OK;
+}
+int pipemax_pool_alloc(pipemax_pool_t* p, int n, int32_t* out_pages) {
+  if (!p || n < 0 || (n > 0 && !out_pages)) PMX_FAIL(PIPEMAX_ERR_ARG, "bad argument");
+  if (!p->pool.alloc(n, out_pages)) PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d pages wanted, %d free", n, p->pool.free_count());
+  return PIPEMAX_OK;
+}
+int pipemax_pool_free(pipemax_pool_t* p, const int32_t* pages, int n) {
+  if (!p || n < 0 || (n > 0 && !pages)) PMX_FAIL(PIPEMAX_ERR_ARG, "bad argument");
+  if (!p->pool.release(pages, n)) PMX_FAIL(PIPEMAX_ERR_ARG, "page out of range, duplicated or already free");
+  return PIPEMAX_OK;
+}
+int pipemax_pool_free_count(pipemax_pool_t* p) {
+  if (!p) PMX_FAIL(PIPEMAX_ERR_ARG, "null pool");
+  return p->pool.free_count();
+}
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+"""Driver of the stage library for tests, smoke() and bench.py: builds a stage from a workload
+shape and its synthetic inputs and runs the cyclic schedule of Eq. 3 (execute D_i, prefetch D_j,
+overwrite D_k).  PyTorch is used for the hidden-state device buffers and the compute stream only.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as pm
+from .synth_inputs import StageShape, SynthInputs
+
+
+def pages_for(tokens: int, page_tokens: int = 16) -> int:
+    return -(-int(tokens) // page_tokens)
+
+
+class StageRunner:
+    """One stage + its micro-batches.
+
+    sigma = streamed fraction of every micro-batch: the last round(sigma*b) sequences of each
+    micro-batch are evicted after their step and prefetched before their next one; the others stay
+    GPU-resident (the hybrid resident + prefetched composition of Sec. 3.1.2).
+    """
+
+    def __init__(self, shape: StageShape, syn: SynthInputs, *, sigma: float = 1.0, steps: int | None = None,
+                 flags: int = 0, device: int = 0, n_microbatches: int | None = None,
+                 ctx_lens: dict | None = None):
+        self.shape, self.syn = shape, syn
+        self.n = n_microbatches or shape.n_microbatches
+        self.b = shape.seqs_per_mb
+        self.steps = steps if steps is not None else shape.decode_steps
+        self.device = device
+        self.ctx0 = {mb: np.asarray(ctx_lens[mb] if ctx_lens else syn.ctx_lens(mb), dtype=np.int32)
+                     for mb in range(self.n)}
+        self.b_of = {mb: len(self.ctx0[mb]) for mb in range(self.n)}
+        steps_per_mb = -(-self.steps // self.n)
+        grow = pages_for(steps_per_mb) + 1
+        self.n_stream = {mb: int(round(sigma * self.b_of[mb])) for mb in range(self.n)}
+        self.stream_ids = {mb: np.arange(self.b_of[mb] - self.n_stream[mb], self.b_of[mb], dtype=np.int32)
+                           for mb in range(self.n)}
+        full = {mb: [pages_for(l) + grow for l in self.ctx0[mb]] for mb in range(self.n)}
+        host_pages = sum(sum(v) for v in full.values())
+        resident_pages = sum(sum(full[mb][: self.b_of[mb] - self.n_stream[mb]]) for mb in range(self.n))
+        stream_pages = sorted((sum(full[mb][self.b_of[mb] - self.n_stream[mb]:]) for mb in range(self.n)),
+                              reverse=True)
+        gpu_pages = resident_pages + sum(stream_pages[:2]) + 8          # two arenas for the streamed part
+        max_ctx = int(max(int(c.max()) for c in self.ctx0.values())) + steps_per_mb + 1
+        self.stage = pm.Stage(
+            n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
+            n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+            rope_base=shape.rope_base, rms_eps=shape.rms_eps,
+            dtype=pm.F32 if shape.dtype == "fp32" else pm.BF16, n_microbatches=self.n,
+            max_seqs_per_mb=max(self.b_of.values()), max_ctx=max_ctx,
+            gpu_kv_bytes=gpu_pages * shape.page_bytes, host_kv_bytes=(host_pages + 8) * shape.page_bytes,
+            device=device, flags=flags)
+        self.torch_dtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+        self.t = 0
+
+    # -- set-up ---------------------------------------------------------------------------------
+    def load_weights(self):
+        for l in range(self.shape.n_layers):
+            w = self.syn.weights(l)
+            self.stage.set_weight(l, pm.W_QKV, w["wqkv"])
+            self.stage.set_weight(l, pm.W_O, w["wo"])
+            self.stage.set_weight(l, pm.W_GU, w["wgu"])
+            self.stage.set_weight(l, pm.W_D, w["wd"])
+            self.stage.set_weight(l, pm.G_ATTN, w["g1"])
+            self.stage.set_weight(l, pm.G_FFN, w["g2"])
+
+    def load_kv(self):
+        for mb in range(self.n):
+            self.stage.mb_define(mb, self.ctx0[mb])
+            for s, L in enumerate(self.ctx0[mb]):
+                if L == 0:
+                    continue
+                for l in range(self.shape.n_layers):
+                    K, V = self.syn.kv_prefix(mb, s, l, int(L))
+                    self.stage.kv_host_write(mb, s, l, 0, K, V)
+
+    def load(self):
+        self.load_weights()
+        self.load_kv()
+        return self
+
+    # -- hidden states ----------------------------------------------------------------------------
+    def hidden_tensor(self, step: int, mb: int) -> torch.Tensor:
+        a = self.syn.hidden(step, self.b_of[mb])
+        if self.shape.dtype == "bf16":
+            t = torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(np.array(a, dtype=np.float32))
+        return t.to(f"cuda:{self.device}")
+
+    def to_numpy_f32(self, t: torch.Tensor) -> np.ndarray:
+        return t.float().cpu().numpy()
+
+    # -- schedule ---------------------------------------------------------------------------------
+    def warm_start(self):
+        """Brings the resident parts of all micro-batches and all of D_0 onto the GPU."""
+        for mb in range(self.n):
+            nres = self.b_of[mb] - self.n_stream[mb]
+            if nres:
+                self.stage.prefetch_kv(mb, np.arange(nres, dtype=np.int32))
+        self.stage.prefetch_kv(0)
+
+    def step(self, hidden_in: torch.Tensor, hidden_out: torch.Tensor, stream: torch.cuda.Stream | None = None):
+        """Iteration t of the cyclic schedule: overwrite D_k, prefetch D_j, execute D_i (Eq. 3)."""
+        n, t = self.n, self.t
+        i, j, k = t % n, (t + 1) % n, (t - 1) % n
+        if t > 0 and self.n_stream[k] and k != i and k != j:
+            self.stage.evict_kv(k, self.stream_ids[k])
+        if j != i and self.n_stream[j]:
+            self.stage.prefetch_kv(j, self.stream_ids[j])
+        sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
+        self.t += 1
+        return i

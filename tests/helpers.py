@@ -1,0 +1,43 @@
+"""Shared pieces of the GPU parity tests: an oracle built from the same synthetic inputs."""
+import numpy as np
+
+from oracle.stage_oracle import StageOracle
+
+
+def make_oracle(shape, syn, ctx0: dict, seqs: dict | None = None, dtype=np.float32) -> StageOracle:
+    """ctx0[mb] = prompt lengths; seqs[mb] = which sequences to track (default all)."""
+    orc = StageOracle(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                      shape.ffn, shape.rope_base, shape.rms_eps, dtype=dtype)
+    for l in range(shape.n_layers):
+        w = syn.weights(l)
+        orc.set_layer_weights(l, **{k: syn.as_f32(v) for k, v in w.items()})
+    for mb, lens in ctx0.items():
+        for s in (seqs[mb] if seqs else range(len(lens))):
+            kv = [syn.kv_prefix(mb, s, l, int(lens[s])) for l in range(shape.n_layers)]
+            orc.define_sequence(mb, s, [syn.as_f32(k) for k, _ in kv], [syn.as_f32(v) for _, v in kv])
+    return orc
+
+
+def check_tables(runner, n_gpu_pages_total=None):
+    """Block tables: right length, inside the pool, no page owned twice."""
+    st = runner.stage
+    stats = st.get_stats()
+    gpu_seen, host_seen = set(), set()
+    for mb in range(runner.n):
+        lens = st.get_ctx_lens(mb)
+        res = st.get_residency(mb)
+        for s in range(runner.b_of[mb]):
+            g, h = st.get_block_table(mb, s)
+            assert len(h) == -(-int(lens[s]) // 16), (mb, s, len(h), lens[s])
+            assert len(set(h.tolist())) == len(h)
+            assert not (set(h.tolist()) & host_seen)
+            host_seen |= set(h.tolist())
+            assert all(0 <= p < stats["host_pages_total"] for p in h)
+            if res[s] == 0:
+                assert all(p == -1 for p in g)
+            else:
+                assert all(0 <= p < stats["gpu_pages_total"] for p in g)
+                assert not (set(g.tolist()) & gpu_seen)
+                gpu_seen |= set(g.tolist())
+    assert stats["gpu_pages_free"] == stats["gpu_pages_total"] - len(gpu_seen)
+    assert stats["host_pages_free"] == stats["host_pages_total"] - len(host_seen)

@@ -1,0 +1,134 @@
+"""CPU-only tests of the C-ABI library: it loads, exports what the header declares, and its
+host-side planning code (page allocator, copy-run planner, in-page layout) behaves."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_symbol_of_the_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "pipemax.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(pipemax_[a-z_]+)\s*\(", hdr))
+    assert declared == set(lib.SYMBOLS)
+    for name in declared:
+        assert getattr(lib._lib, name) is not None
+    assert "gfx950" in lib.version()
+
+
+def test_struct_sizes_match_the_header(lib):
+    import ctypes as C
+    # pipemax_config_t: 6 int32, 2 float, 5 int32, (pad) 2 uint64, int32, uint32
+    assert C.sizeof(lib.Config) == 80
+    assert lib.Config.gpu_kv_bytes.offset == 56
+    assert C.sizeof(lib.Stats) == 8 * 8 + 4 * 8 + lib.N_KCLASS * 16 + 5 * 4 + 4 + 8
+
+
+def test_stage_create_fails_loudly_without_a_gpu_or_with_bad_shapes(lib):
+    kw = dict(n_layers=1, hidden=64, n_q_heads=2, n_kv_heads=1, head_dim=32, ffn=64, rope_base=1e4,
+              rms_eps=1e-5, dtype=lib.F32, n_microbatches=1, max_seqs_per_mb=1, max_ctx=32,
+              gpu_kv_bytes=1 << 20, host_kv_bytes=1 << 20)
+    for bad in (dict(page_tokens=8), dict(head_dim=48), dict(n_q_heads=3, n_kv_heads=2), dict(dtype=7),
+                dict(n_layers=0)):
+        with pytest.raises(lib.PipemaxError) as e:
+            lib.Stage(**{**kw, **bad})
+        assert e.value.code == lib.ERR_ARG
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(lib.PipemaxError) as e:
+            lib.Stage(**kw)
+        assert e.value.code == lib.ERR_HIP
+
+
+def test_pool_is_lowest_index_first_and_all_or_nothing(lib):
+    p = lib.Pool(10)
+    assert list(p.alloc(4)) == [0, 1, 2, 3]
+    assert list(p.alloc(2)) == [4, 5]
+    p.free([1, 2, 5])
+    assert p.free_count() == 7
+    assert list(p.alloc(4)) == [1, 2, 5, 6]                      # lowest free indices, across intervals
+    with pytest.raises(lib.PipemaxError) as e:
+        p.alloc(4)                                               # only 3 left
+    assert e.value.code == lib.ERR_POOL_EXHAUSTED
+    assert p.free_count() == 3                                   # nothing taken
+    assert list(p.alloc(3)) == [7, 8, 9]
+    for bad in ([0, 0], [10], [-1]):
+        with pytest.raises(lib.PipemaxError):
+            p.free(bad)
+    p.free([0])
+    with pytest.raises(lib.PipemaxError):
+        p.free([0])                                              # double free
+    assert p.free_count() == 1
+
+
+def test_pool_random_against_a_set_model(lib):
+    rng = np.random.default_rng(0)
+    n = 257
+    p = lib.Pool(n)
+    free, held = set(range(n)), []
+    for _ in range(400):
+        if held and rng.random() < 0.45:
+            k = int(rng.integers(1, len(held) + 1))
+            idx = rng.choice(len(held), size=k, replace=False)
+            pages = [held[i] for i in idx]
+            held = [h for i, h in enumerate(held) if i not in set(idx.tolist())]
+            p.free(pages)
+            free |= set(pages)
+        else:
+            k = int(rng.integers(0, 40))
+            if k > len(free):
+                with pytest.raises(lib.PipemaxError):
+                    p.alloc(k)
+                continue
+            got = list(p.alloc(k))
+            assert got == sorted(free)[:k]
+            free -= set(got)
+            held += got
+        assert p.free_count() == len(free)
+
+
+def test_copy_runs_merge_consecutive_pairs_only(lib):
+    runs = lib.plan_copy_runs([0, 1, 2, 5, 6, 9], [10, 11, 12, 13, 14, 20], 128)
+    assert runs.tolist() == [[0, 10, 3], [5, 13, 2], [9, 20, 1]]
+    runs = lib.plan_copy_runs(np.arange(10), np.arange(10) + 100, 4)
+    assert runs.tolist() == [[0, 100, 4], [4, 104, 4], [8, 108, 2]]
+    runs = lib.plan_copy_runs([3, 4, 5], [7, 9, 10], 128)           # dst not consecutive at first pair
+    assert runs.tolist() == [[3, 7, 1], [4, 9, 2]]
+    assert lib.plan_copy_runs([], [], 8).shape == (0, 3)
+    # the runs cover every pair exactly once, in order
+    rng = np.random.default_rng(1)
+    src = np.sort(rng.choice(1000, 300, replace=False))
+    dst = np.sort(rng.choice(1000, 300, replace=False))
+    runs = lib.plan_copy_runs(src, dst, 16)
+    s = np.concatenate([np.arange(a, a + c) for a, _, c in runs])
+    d = np.concatenate([np.arange(b, b + c) for _, b, c in runs])
+    np.testing.assert_array_equal(s, src)
+    np.testing.assert_array_equal(d, dst)
+    assert runs[:, 2].max() <= 16
+
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_page_layout_is_a_bijection_with_the_documented_order(lib, d):
+    nl, hkv = 3, 2
+    total = nl * hkv * 2 * 16 * d
+    seen = np.zeros(total, dtype=np.int32)
+    for layer in range(nl):
+        for head in range(hkv):
+            for kv in range(2):
+                base = ((layer * hkv + head) * 2 + kv) * 16 * d        # [layer][head][K|V] sub-blocks
+                for tok in range(16):
+                    for dd in range(d):
+                        off = lib.page_elem_offset(nl, hkv, d, layer, kv, head, tok, dd)
+                        if kv == 0:
+                            want = base + ((dd // 8) * 16 + tok) * 8 + dd % 8
+                        else:
+                            want = base + ((((dd // 32) * 4 + tok // 4) * 16 + dd % 16) * 2 + (dd // 16) % 2) * 4 + tok % 4
+                        assert off == want
+                        seen[off] += 1
+    assert np.all(seen == 1)
+    assert lib.page_elem_offset(nl, hkv, d, nl, 0, 0, 0, 0) == -1
+    assert lib.page_elem_offset(nl, hkv, d, 0, 0, 0, 16, 0) == -1
+    assert lib.page_elem_offset(nl, hkv, 48, 0, 0, 0, 0, 0) == -1

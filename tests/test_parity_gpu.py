@@ -1,0 +1,323 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bars: bit-exact for KV paging / indexing / bookkeeping; relative L2 per layer output
+<= 1e-5 for the fp32 stage and <= 1e-2 for bf16 stages (the tolerance the benchmark spec fixes)."""
+import numpy as np
+import pytest
+
+from conftest import rel_l2
+from helpers import check_tables, make_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def _runner(shape, seed=0, **kw):
+    from paper_2605_02189_amd.harness import StageRunner
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    syn = SynthInputs(shape, seed=seed, pool_elems=kw.pop("pool_elems", 1 << 23), gain_jitter=0.1)
+    return StageRunner(shape, syn, **kw), syn
+
+
+def _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer, tol_delta, oracle_seqs=None):
+    """Runs `steps` iterations of the cyclic schedule and compares every step with the oracle."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    orc = make_oracle(shape, syn, runner.ctx0, oracle_seqs)
+    runner.warm_start()
+    worst_layer = worst_delta = 0.0
+    for t in range(steps):
+        mb = t % runner.n
+        b = runner.b_of[mb]
+        hin = runner.hidden_tensor(t, mb)
+        hout = torch.empty_like(hin)
+        print(f"step {t} mb {mb} b {b}", flush=True)
+        assert runner.step(hin, hout) == mb
+        seqs = list(oracle_seqs[mb]) if oracle_seqs else list(range(b))
+        x_in = syn.as_f32(syn.hidden(t, b))[seqs]
+        ref_out, ref_layers = orc.decode_step(mb, x_in, seqs=seqs)
+        got_layers = runner.stage.get_layer_outputs(b)[:, seqs, :]
+        got_out = runner.to_numpy_f32(hout)[seqs]
+        prev_ref, prev_got = x_in, x_in
+        for l in range(shape.n_layers):
+            e = rel_l2(got_layers[l], ref_layers[l])
+            d = rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref)
+            worst_layer, worst_delta = max(worst_layer, e), max(worst_delta, d)
+            assert e <= tol_layer, f"step {t} layer {l}: rel L2 {e:.3e} > {tol_layer}"
+            assert d <= tol_delta, f"step {t} layer {l}: rel L2 of the layer's update {d:.3e} > {tol_delta}"
+            prev_ref, prev_got = ref_layers[l], got_layers[l]
+        # the stage output is the last layer's residual stream in the stage's element type
+        out_tol = tol_layer if shape.dtype == "fp32" else max(tol_layer, 8e-3)
+        assert rel_l2(got_out, ref_out) <= out_tol
+        # bookkeeping after the step
+        lens = runner.stage.get_ctx_lens(mb)
+        assert lens.tolist() == [orc.ctx_len(mb, s) if (not oracle_seqs or s in seqs) else lens[s]
+                                 for s in range(b)]
+        res = runner.stage.get_residency(mb)
+        assert np.all(res == pm.GPU)
+    print(f"worst rel L2: layer output {worst_layer:.3e}, layer update {worst_delta:.3e}", flush=True)
+    return orc
+
+
+def _check_replica(runner, syn, shape, orc, tol_new, seqs=None):
+    """Host replica == device pages byte for byte; prefix bit-identical to what was written;
+    tokens appended on the GPU within tolerance of the oracle's."""
+    st = runner.stage
+    st.sync()
+    for mb in range(runner.n):
+        lens = st.get_ctx_lens(mb)
+        res = st.get_residency(mb)
+        for s in (seqs[mb] if seqs else range(runner.b_of[mb])):
+            L0, L = int(runner.ctx0[mb][s]), int(lens[s])
+            for l in range(shape.n_layers):
+                Kh, Vh = st.kv_host_read(mb, s, l, 0, L)
+                K0, V0 = syn.kv_prefix(mb, s, l, L0)
+                np.testing.assert_array_equal(Kh[:L0], K0)
+                np.testing.assert_array_equal(Vh[:L0], V0)
+                if res[s] != 0:
+                    Kd, Vd = st.kv_dev_read(mb, s, l, 0, L)
+                    np.testing.assert_array_equal(Kd, Kh)
+                    np.testing.assert_array_equal(Vd, Vh)
+                if L > L0:
+                    Ko, Vo = orc.cached_kv(mb, s, l)
+                    assert rel_l2(syn.as_f32(Kh[L0:]), Ko[L0:]) <= tol_new
+                    assert rel_l2(syn.as_f32(Vh[L0:]), Vo[L0:]) <= tol_new
+
+
+# ---------------------------------------------------------------------------------------------
+def test_config1_tiny_fp32_full_schedule():
+    """configs[0] in full: 4 micro-batches x 8 sequences, 128-token prompts, 16 decode steps in cyclic
+    order with 2 GPU arenas (3 of 4 micro-batches host-resident at any time)."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS
+    shape = CONFIGS["C1"]
+    runner, syn = _runner(shape, seed=1, flags=pm.FLAG_CAPTURE_LAYERS)
+    runner.load()
+    assert runner.stage.get_stats()["engine"] == 0
+    orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-5, tol_delta=2e-4)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-5)
+    st = runner.stage.get_stats()
+    assert st["steps"] == 16 and st["tokens"] == 16 * 8
+    assert st["d2h_copies"] == 16 * shape.n_layers and st["relayout_jobs"] == 16 * shape.n_layers
+    # every micro-batch was streamed in once per cycle (4 cycles), whole prompts + grown tokens
+    assert st["h2d_bytes"] >= 16 * 8 * 8 * shape.page_bytes
+    runner.stage.destroy()
+
+
+def _mid_shape(**kw):
+    from paper_2605_02189_amd.synth_inputs import StageShape
+    base = dict(name="mid", n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2816,
+                dtype="bf16", rope_base=500000.0, n_microbatches=3, seqs_per_mb=20, ctx_lo=1, ctx_hi=300,
+                decode_steps=9)
+    base.update(kw)
+    return StageShape(**base)
+
+
+def _ragged_ctx(shape, syn):
+    ctx = {mb: syn.ctx_lens(mb).copy() for mb in range(shape.n_microbatches)}
+    ctx[0][:6] = [0, 1, 15, 16, 17, 300]         # empty prompt, page-boundary cases, the longest
+    return ctx
+
+
+def test_bf16_matrix_core_path_ragged():
+    """bf16 stage on the matrix-core kernels: ragged batch (20 rows: one partial 32-row tile), ragged
+    contexts including an empty prompt and page-boundary lengths, several GEMM tiles and attention
+    chunks, 3 micro-batches streamed through 2 arenas."""
+    from paper_2605_02189_amd import binding as pm
+    shape = _mid_shape()
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    syn = SynthInputs(shape, seed=2, pool_elems=1 << 23, gain_jitter=0.1)
+    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=_ragged_ctx(shape, syn)).load()
+    assert runner.stage.get_stats()["engine"] == 1
+    orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-2, tol_delta=3e-2)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-2)
+    runner.stage.destroy()
+
+
+def test_bf16_generic_path_matches_oracle_and_matrix_core_path():
+    """The same bf16 workload on the shape-generic kernels (fp32 activations)."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(decode_steps=4, seqs_per_mb=5, ctx_hi=120)
+    syn = SynthInputs(shape, seed=3, pool_elems=1 << 23, gain_jitter=0.1)
+    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS | pm.FLAG_FORCE_GENERIC).load()
+    assert runner.stage.get_stats()["engine"] == 0
+    _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=2e-3, tol_delta=1e-2)
+    runner.stage.destroy()
+
+
+def test_long_context_many_chunks_and_wide_group():
+    """One long sequence next to short ones (split-K load balance), G = 8 query heads per KV head."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(n_layers=1, n_q_heads=8, n_kv_heads=1, hidden=512, ffn=1024, n_microbatches=1,
+                       seqs_per_mb=3, decode_steps=3, ctx_hi=3000)
+    syn = SynthInputs(shape, seed=4, pool_elems=1 << 23, gain_jitter=0.1)
+    ctx = {0: np.array([2999, 40, 1025], dtype=np.int32)}
+    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx).load()
+    assert runner.stage.get_stats()["engine"] == 1
+    _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-2, tol_delta=3e-2)
+    runner.stage.destroy()
+
+
+def test_offload_then_prefetch_is_a_bit_identical_round_trip():
+    """Bytes written to the host replica come back from the GPU pages unchanged, wherever the pages
+    land; evicting and prefetching again (into other physical pages) changes nothing."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS
+    for shape in (CONFIGS["C1"], _mid_shape(n_layers=3, seqs_per_mb=4, ctx_hi=90)):
+        runner, syn = _runner(shape, seed=5)
+        runner.load_kv()
+        st = runner.stage
+        st.prefetch_kv(1)
+        st.prefetch_kv(0, [2, 0])
+        g_before = {s: st.get_block_table(0, s)[0].copy() for s in (0, 2)}
+        st.evict_kv(0, [0])
+        st.prefetch_kv(0, [1])                        # takes seq 0's old pages first (lowest index first)
+        st.prefetch_kv(0, [0])
+        g_after, _ = st.get_block_table(0, 0)
+        assert len(g_before[0]) == 0 or g_after.tolist() != g_before[0].tolist()
+        st.sync()
+        check_tables(runner)
+        for mb, seqs in ((0, [0, 1, 2]), (1, range(runner.b_of[1]))):
+            for s in seqs:
+                L = int(runner.ctx0[mb][s])
+                for l in range(shape.n_layers):
+                    K0, V0 = syn.kv_prefix(mb, s, l, L)
+                    Kd, Vd = st.kv_dev_read(mb, s, l, 0, L)
+                    np.testing.assert_array_equal(Kd, K0)
+                    np.testing.assert_array_equal(Vd, V0)
+                    # partial ranges address the same bytes
+                    if L > 20:
+                        Kp, Vp = st.kv_dev_read(mb, s, l, 13, 7)
+                        np.testing.assert_array_equal(Kp, K0[13:20])
+                        np.testing.assert_array_equal(Vp, V0[13:20])
+        with pytest.raises(pm.PipemaxError) as e:
+            st.kv_dev_read(0, 3, 0, 0, 1)
+        assert e.value.code == pm.ERR_NOT_RESIDENT
+        st.destroy()
+
+
+def test_results_do_not_depend_on_physical_page_placement():
+    """Same inputs, different page placement (other sequences prefetched first, a hole punched in the
+    pool) -> identical outputs, bit for bit."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(n_microbatches=2, seqs_per_mb=6, ctx_hi=200, decode_steps=2)
+    outs, tables = [], []
+    for variant in range(2):
+        syn = SynthInputs(shape, seed=6, pool_elems=1 << 23, gain_jitter=0.1)
+        runner = StageRunner(shape, syn, sigma=0.0).load()
+        st = runner.stage
+        if variant == 0:
+            st.prefetch_kv(0)
+        else:
+            st.prefetch_kv(1, [3, 4])
+            st.prefetch_kv(0, [5, 4, 3])
+            st.evict_kv(1, [3])
+            st.prefetch_kv(0)
+        tables.append(st.get_block_table(0, 0)[0].tolist())
+        hin = runner.hidden_tensor(0, 0)
+        res = []
+        for t in range(2):
+            hout = torch.empty_like(hin)
+            st.decode_step(0, hin.data_ptr(), hout.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            st.sync()
+            res.append(hout.cpu().view(torch.int16).numpy().copy())
+            hin = hout
+        outs.append(res)
+        st.destroy()
+    assert tables[0] != tables[1]
+    for t in range(2):
+        np.testing.assert_array_equal(outs[0][t], outs[1][t])
+
+
+def test_error_paths_leave_the_stage_unchanged():
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from oracle.bookkeeping_oracle import ResidencyModel, BookkeepingError
+    shape = _mid_shape(n_layers=1, hidden=256, ffn=256, n_q_heads=2, n_kv_heads=1, n_microbatches=2)
+    page = shape.page_bytes
+    st = pm.Stage(n_layers=1, hidden=256, n_q_heads=2, n_kv_heads=1, head_dim=128, ffn=256, rope_base=1e4,
+                  rms_eps=1e-5, dtype=pm.BF16, n_microbatches=2, max_seqs_per_mb=2, max_ctx=40,
+                  gpu_kv_bytes=4 * page, host_kv_bytes=10 * page)
+    model = ResidencyModel(2, 16, max_ctx=40, gpu_pages=4, host_pages=10)
+    code = {"ARG": pm.ERR_ARG, "NOT_RESIDENT": pm.ERR_NOT_RESIDENT, "POOL_EXHAUSTED": pm.ERR_POOL_EXHAUSTED,
+            "STATE": pm.ERR_STATE}
+    h = torch.zeros(2, 256, dtype=torch.bfloat16, device="cuda")
+    o = torch.empty_like(h)
+    sp = torch.cuda.current_stream().cuda_stream
+
+    def both(name, *args):
+        """Applies a call to the model and to the library; both must agree on success / error kind."""
+        want = None
+        try:
+            getattr(model, name)(*args)
+        except BookkeepingError as e:
+            want = code[e.kind]
+        lib_call = {"mb_define": lambda mb, lens: st.mb_define(mb, lens),
+                    "prefetch": lambda mb, ids=None: st.prefetch_kv(mb, ids),
+                    "evict": lambda mb, ids=None: st.evict_kv(mb, ids),
+                    "decode_step": lambda mb: st.decode_step(mb, h.data_ptr(), o.data_ptr(), sp)}[name]
+        if want is None:
+            lib_call(*args)
+        else:
+            with pytest.raises(pm.PipemaxError) as e:
+                lib_call(*args)
+            assert e.value.code == want, (name, args, e.value)
+        for mb in model.nseq:
+            assert st.get_ctx_lens(mb).tolist() == model.ctx_lens(mb)
+            assert [int(r != 0) for r in st.get_residency(mb)] == [int(model.resident(mb, s))
+                                                                    for s in range(model.nseq[mb])]
+        s_ = st.get_stats()
+        assert s_["gpu_pages_free"] == model.gpu_free and s_["host_pages_free"] == model.host_free
+
+    both("mb_define", 0, [16, 17])
+    both("mb_define", 1, [40])
+    both("mb_define", 1, [1])                 # already defined
+    both("decode_step", 0)                    # nothing resident
+    both("prefetch", 0)                       # takes 3 of the 4 GPU pages
+    both("prefetch", 1)                       # pool exhausted, nothing applied
+    both("decode_step", 0)                    # works; seq 0 at a page boundary takes the 4th GPU page
+    both("evict", 0, [1])
+    both("prefetch", 0, [1])
+    both("evict", 0)
+    both("prefetch", 1)
+    both("decode_step", 1)                    # at max_ctx
+    both("evict", 1)
+    both("prefetch", 0, [1])
+    both("decode_step", 0)                    # seq 0 not resident
+    both("prefetch", 0, [0])
+    both("decode_step", 0)                    # works, no new page
+    both("prefetch", 0, [7])                  # bad sequence index
+    st.sync()
+    st.destroy()
+
+
+def test_single_sequence_single_microbatch_from_empty_cache():
+    """b = 1, one micro-batch, empty prompt: the first step attends over exactly one token, so the
+    attention output is that token's V (the oracle pins this case bit for bit)."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs, CONFIGS
+    from paper_2605_02189_amd.harness import StageRunner
+    for shape, tl, td in ((CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=1, ctx_lo=0, ctx_hi=0, decode_steps=18), 1e-5, 2e-4),
+                          (_mid_shape(n_microbatches=1, seqs_per_mb=1, ctx_lo=0, ctx_hi=0, decode_steps=18), 1e-2, 3e-2)):
+        syn = SynthInputs(shape, seed=7, pool_elems=1 << 23, gain_jitter=0.1)
+        runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS).load()
+        orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=tl, tol_delta=td)
+        _check_replica(runner, syn, shape, orc, tol_new=tl)
+        assert runner.stage.get_ctx_lens(0).tolist() == [18]
+        assert len(runner.stage.get_block_table(0, 0)[1]) == 2
+        runner.stage.destroy()
