@@ -14,6 +14,25 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpipemax.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_02189_amd.build`")
+
+
+def _preload_torch_hip_runtime():
+    """Device pointers and streams handed to the library come from PyTorch, so both must live in ONE
+    HIP runtime.  The PyTorch wheel ships its own libamdhip64 / libhsa-runtime64; loading them (by
+    path, without importing torch) before libpipemax.so makes the dynamic loader resolve the
+    library's HIP dependency to that same copy, whatever the import order."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return
+    libdir = os.path.join(list(spec.submodule_search_locations)[0], "lib")
+    for name in ("libhsa-runtime64.so", "libamdhip64.so"):
+        path = os.path.join(libdir, name)
+        if os.path.exists(path):
+            C.CDLL(path, mode=C.RTLD_GLOBAL)
+
+
+_preload_torch_hip_runtime()
 _lib = C.CDLL(LIB_PATH)
 
 OK, ERR_ARG, ERR_OOM_DEVICE, ERR_OOM_HOST = 0, -1, -2, -3

@@ -228,7 +228,7 @@ def test_results_do_not_depend_on_physical_page_placement():
             st.prefetch_kv(0, [5, 4, 3])
             st.evict_kv(1, [3])
             st.prefetch_kv(0)
-        tables.append(st.get_block_table(0, 0)[0].tolist())
+        tables.append([st.get_block_table(0, s_)[0].tolist() for s_ in range(runner.b_of[0])])
         hin = runner.hidden_tensor(0, 0)
         res = []
         for t in range(2):
