@@ -201,6 +201,9 @@ int pipemax_sync(pipemax_stage_t* st);
 
 int pipemax_get_stats(pipemax_stage_t* st, pipemax_stats_t* out);   /* synchronises if timing */
 int pipemax_reset_stats(pipemax_stage_t* st);
+/* Sets and clears run-time flags; only PIPEMAX_FLAG_TIME_KERNELS and PIPEMAX_FLAG_NO_WRITEBACK can be
+ * changed after creation (ERR_ARG otherwise).  Synchronises the stage first.                */
+int pipemax_set_flags(pipemax_stage_t* st, uint32_t set, uint32_t clear);
 
 /* out: host pointer to n_seqs int32 (current context lengths).                             */
 int pipemax_get_ctx_lens(pipemax_stage_t* st, int mb, int32_t* out);
@@ -216,6 +219,14 @@ int pipemax_get_layer_outputs(pipemax_stage_t* st, float* out, size_t bytes);
 
 const char* pipemax_last_error(void);
 const char* pipemax_version(void);
+
+/* ---- measurement aid ------------------------------------------------------------------------ */
+
+/* Launches a plain device-to-device copy kernel (named k_probe_copy in profiles) of `bytes` bytes
+ * (a multiple of 16; dst and src are 16-byte-aligned device pointers that do not overlap) on
+ * hip_stream (NULL = default stream).  Its known traffic calibrates the hardware counters that
+ * the HBM-traffic figures are derived from.                                                   */
+int pipemax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* ---- host-side planning helpers (pure host code; also used by the CPU tests) ------------- */
 

@@ -50,7 +50,7 @@ SYMBOLS = [
     "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
-    "pipemax_reset_stats", "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
+    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
     "pipemax_plan_copy_runs", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
     "pipemax_pool_free", "pipemax_pool_free_count",
@@ -101,6 +101,8 @@ _sig = {
     "pipemax_sync": (C.c_int, [_vp]),
     "pipemax_get_stats": (C.c_int, [_vp, C.POINTER(Stats)]),
     "pipemax_reset_stats": (C.c_int, [_vp]),
+    "pipemax_set_flags": (C.c_int, [_vp, C.c_uint32, C.c_uint32]),
+    "pipemax_probe_copy": (C.c_int, [_vp, _vp, C.c_size_t, _vp]),
     "pipemax_get_ctx_lens": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_residency": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_block_table": (C.c_int, [_vp, C.c_int, C.c_int, _i32p, _i32p, C.POINTER(C.c_int)]),
@@ -231,6 +233,9 @@ class Stage:
     def reset_stats(self):
         _check(_lib.pipemax_reset_stats(self._h))
 
+    def set_flags(self, set_: int = 0, clear: int = 0):
+        _check(_lib.pipemax_set_flags(self._h, set_, clear))
+
     def get_ctx_lens(self, mb) -> np.ndarray:
         out = np.empty(self._nseq[mb], dtype=np.int32)
         _check(_lib.pipemax_get_ctx_lens(self._h, mb, out.ctypes.data_as(_i32p)))
@@ -255,6 +260,10 @@ class Stage:
         out = np.empty((self.cfg.n_layers, b, self.cfg.hidden), dtype=np.float32)
         _check(_lib.pipemax_get_layer_outputs(self._h, _ptr(out), out.nbytes))
         return out
+
+
+def probe_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream_ptr: int = 0):
+    _check(_lib.pipemax_probe_copy(_vp(dst_ptr), _vp(src_ptr), nbytes, _vp(stream_ptr) if stream_ptr else None))
 
 
 # -- host-side planning helpers ---------------------------------------------------------------

@@ -18,6 +18,8 @@ struct Dims {
 // cs[i][j] = (cos, sin)(ctx[i] * base^(-2j/d)), angle formed in double precision.
 void launch_rope_table(hipStream_t s, const int* ctx, float2* cs, int b, int d, float base);
 void launch_advance_ctx(hipStream_t s, int* ctx, int b);
+// plain grid-stride 16-byte copy, a counter-calibration aid
+void launch_probe_copy(hipStream_t s, void* dst, const void* src, size_t bytes);
 
 // ---- shape-generic engine (T = float or bf16 bit patterns as uint16_t) ---------------------------
 template <typename T>

@@ -1,6 +1,8 @@
 // Shape-generic kernels of the stage decode step (any hidden / head_dim % 32 == 0 / ffn; element
 // type float or bf16).  They serve the fp32 configuration and shapes the matrix-core kernels do
 // not cover; activations are kept in fp32, only stored K,V and weights are in the element type.
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace pmx {
@@ -51,6 +53,11 @@ __global__ void k_rope_table(const int* ctx, float2* cs, int b, int half, int d,
 __global__ void k_advance_ctx(int* ctx, int b) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < b) ctx[i] += 1;
+}
+
+__global__ __launch_bounds__(256) void k_probe_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
 }
 
 // ---- generic engine ------------------------------------------------------------------------------
@@ -193,6 +200,12 @@ void launch_rope_table(hipStream_t s, const int* ctx, float2* cs, int b, int d, 
   int n = b * (d / 2);
   hipLaunchKernelGGL(k_rope_table, dim3(cdiv(n, 256)), dim3(256), 0, s, ctx, cs, b, d / 2, d,
                      (double)base);
+}
+void launch_probe_copy(hipStream_t s, void* dst, const void* src, size_t bytes) {
+  const size_t n = bytes / 16;
+  const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 32);
+  if (n == 0) return;
+  hipLaunchKernelGGL(k_probe_copy, dim3(blocks), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, n);
 }
 void launch_advance_ctx(hipStream_t s, int* ctx, int b) {
   hipLaunchKernelGGL(k_advance_ctx, dim3(cdiv(b, 256)), dim3(256), 0, s, ctx, b);

@@ -715,6 +715,7 @@ int pipemax_kv_host_write(pipemax_stage_t* st, int mb, int seq, int layer, int t
   if (S.state != ST_HOST) PMX_FAIL(PIPEMAX_ERR_STATE, "kv_host_write needs a HOST-resident sequence");
   st->wait_mb_writeback(mb);
   const size_t row = (size_t)st->D.Hkv * st->D.d;
+#pragma omp parallel for schedule(static) if (ntok >= 256)
   for (int t = 0; t < ntok; ++t) {
     const int tok = tok0 + t;
     char* page = st->host_page_ptr(S.host[tok / kPageTokens]);
@@ -1143,6 +1144,25 @@ int pipemax_reset_stats(pipemax_stage_t* st) {
   std::lock_guard<std::mutex> lk(st->mu);
   st->st = pipemax_stats_t{};
   st->st.engine = st->engine;
+  return PIPEMAX_OK;
+}
+
+int pipemax_set_flags(pipemax_stage_t* st, uint32_t set, uint32_t clear) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  const uint32_t allowed = PIPEMAX_FLAG_TIME_KERNELS | PIPEMAX_FLAG_NO_WRITEBACK;
+  if ((set | clear) & ~allowed) PMX_FAIL(PIPEMAX_ERR_ARG, "only the timing and no-write-back flags can change");
+  int rc = pipemax_sync(st);
+  if (rc) return rc;
+  if (st->timing()) st->resolve_timers();
+  st->cfg.flags = (st->cfg.flags | set) & ~clear;
+  return PIPEMAX_OK;
+}
+
+int pipemax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+    PMX_FAIL(PIPEMAX_ERR_ARG, "probe copy needs 16-byte aligned pointers and size");
+  launch_probe_copy((hipStream_t)hip_stream, dst, src, bytes);
+  PMX_HIP(hipGetLastError());
   return PIPEMAX_OK;
 }
 

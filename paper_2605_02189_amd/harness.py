@@ -25,7 +25,7 @@ class StageRunner:
 
     def __init__(self, shape: StageShape, syn: SynthInputs, *, sigma: float = 1.0, steps: int | None = None,
                  flags: int = 0, device: int = 0, n_microbatches: int | None = None,
-                 ctx_lens: dict | None = None):
+                 ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False):
         self.shape, self.syn = shape, syn
         self.n = n_microbatches or shape.n_microbatches
         self.b = shape.seqs_per_mb
@@ -45,6 +45,8 @@ class StageRunner:
         stream_pages = sorted((sum(full[mb][self.b_of[mb] - self.n_stream[mb]:]) for mb in range(self.n)),
                               reverse=True)
         gpu_pages = resident_pages + sum(stream_pages[:2]) + 8          # two arenas for the streamed part
+        if gpu_pool_all_resident:                                       # room to keep everything on the GPU
+            gpu_pages = host_pages + 8
         max_ctx = int(max(int(c.max()) for c in self.ctx0.values())) + steps_per_mb + 1
         self.stage = pm.Stage(
             n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
@@ -104,15 +106,20 @@ class StageRunner:
                 self.stage.prefetch_kv(mb, np.arange(nres, dtype=np.int32))
         self.stage.prefetch_kv(0)
 
-    def step(self, hidden_in: torch.Tensor, hidden_out: torch.Tensor, stream: torch.cuda.Stream | None = None):
-        """Iteration t of the cyclic schedule: overwrite D_k, prefetch D_j, execute D_i (Eq. 3)."""
+    def step(self, hidden_in: torch.Tensor | None, hidden_out: torch.Tensor | None,
+             stream: torch.cuda.Stream | None = None, transfers: bool = True, compute: bool = True):
+        """Iteration t of the cyclic schedule: overwrite D_k, prefetch D_j, execute D_i (Eq. 3).
+        transfers=False keeps everything where it is (all micro-batches must be resident);
+        compute=False issues only the evict / prefetch traffic of the iteration."""
         n, t = self.n, self.t
         i, j, k = t % n, (t + 1) % n, (t - 1) % n
-        if t > 0 and self.n_stream[k] and k != i and k != j:
-            self.stage.evict_kv(k, self.stream_ids[k])
-        if j != i and self.n_stream[j]:
-            self.stage.prefetch_kv(j, self.stream_ids[j])
-        sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
-        self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
+        if transfers:
+            if t > 0 and self.n_stream[k] and k != i and k != j:
+                self.stage.evict_kv(k, self.stream_ids[k])
+            if j != i and self.n_stream[j]:
+                self.stage.prefetch_kv(j, self.stream_ids[j])
+        if compute:
+            sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+            self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         self.t += 1
         return i
