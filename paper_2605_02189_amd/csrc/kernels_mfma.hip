@@ -189,6 +189,99 @@ __global__ __launch_bounds__(WN * 64) void k_gemm(const uint4* __restrict__ Xt,
 }
 
 // =================================================================================================
+// skinny GEMM for at most 64 rows (MT <= 2): barrier-free streaming
+//   grid (N / (32*NT), S), block = NWK waves.  The block owns NT adjacent 32-column tiles and the
+//   K range of split blockIdx.y; its waves take the k-steps of that range round-robin.  Every wave
+//   streams its weight fragments from HBM and its X fragments from L2 (both lane-linear 1 KiB loads,
+//   U k-steps ahead) with no LDS and no barrier in the loop; the waves' accumulators are summed once
+//   through LDS at the end.  EPI 0: fp32 partial part[s][m][n].  EPI 1 (NT = 2 = gate tile + up tile
+//   of the interleaved gate/up matrix, S = 1): act = silu(gate) * up written as A-tiled bf16.
+// =================================================================================================
+template <int MT, int NT, int NWK, int U, int EPI>
+__global__ __launch_bounds__(NWK * 64) void k_gemm_s(const uint4* __restrict__ Xt,
+                                                     const uint4* __restrict__ Wt,
+                                                     float* __restrict__ part, uint16_t* __restrict__ act_t,
+                                                     int M, int N, int KT, int ksp, int64_t split_stride) {
+  __shared__ float red[NWK][NT * 16][64];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt0 = blockIdx.x * NT;
+  const int kb0 = blockIdx.y * ksp;
+  const int kb1 = min(KT, kb0 + ksp);
+  const int nsteps = (kb1 - kb0 > w) ? (kb1 - kb0 - w + NWK - 1) / NWK : 0;   // k-steps kb0 + w + j*NWK
+  const uint4* wp = Wt + ((int64_t)nt0 * KT + kb0 + w) * 64 + lane;             // + nt*KT*64 + j*NWK*64
+  const uint4* xp = Xt + ((int64_t)kb0 + w) * 64 + lane;                        // + mt*KT*64 + j*NWK*64
+
+  f32x16 acc[NT * MT];
+#pragma unroll
+  for (int t = 0; t < NT * MT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  uint4 wb[U][NT], xb[U][MT];
+  auto load = [&](int j, uint4* wd, uint4* xd) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wd[nt] = ld_stream(wp + ((int64_t)nt * KT + (int64_t)j * NWK) * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xd[mt] = xp[((int64_t)mt * KT + (int64_t)j * NWK) * 64];
+  };
+#pragma unroll
+  for (int r = 0; r < U; ++r)
+    if (r < nsteps) load(r, wb[r], xb[r]);
+  for (int j0 = 0; j0 < nsteps; j0 += U) {
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const int j = j0 + r;
+      if (j < nsteps) {
+        bf16x8 A[MT], B[NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) A[mt] = __builtin_bit_cast(bf16x8, xb[r][mt]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) B[nt] = __builtin_bit_cast(bf16x8, wb[r][nt]);
+        if (j + U < nsteps) load(j + U, wb[r], xb[r]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[nt * MT + mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[mt], B[nt], acc[nt * MT + mt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- sum the NWK waves' accumulators through LDS (one row tile at a time), then the epilogue ---
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt) __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[w][nt * 16 + r][lane] = acc[nt * MT + mt][r];
+    __syncthreads();
+    for (int r = w; r < 16; r += NWK) {
+      float v[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float a = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NWK; ++ww) a += red[ww][nt * 16 + r][lane];
+        v[nt] = a;
+      }
+      const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (m < M) {
+        if (EPI == 0) {
+          float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + (lane & 31);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) out[nt * 32] = v[nt];
+        } else {
+          const int f = blockIdx.x * 32 + (lane & 31);
+          const float g = v[0], u = v[NT - 1];
+          act_t[a_tiled_idx(N >> 5, m, f)] = f2bf(g / (1.0f + expf(-g)) * u);   // down GEMM: K = N/2, KT = N/32
+        }
+      }
+    }
+  }
+}
+
+// =================================================================================================
 // RoPE + KV append + write-back staging; also reduces the split-K partials of the QKV GEMM
 //   grid (b, Hq + 2 Hkv), block 64: thread j rotates the pair (j, j + 64)
 // =================================================================================================
@@ -242,9 +335,8 @@ __global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const flo
 
 // =================================================================================================
 // GQA paged decode attention, split-K over the context
-//   grid (chunk, kv head, sequence), block = 4 waves.  A block owns a run of pages of one (sequence,
-//   kv head); its waves take the pages round-robin, each keeping an online-softmax state for the G
-//   query heads of the group (padded to the 16 columns of the MFMA tile), and merge through LDS.
+//   A wave owns a run of consecutive pages of one (sequence, kv head) and keeps an online-softmax
+//   state for the G query heads of the group (padded to the 16 columns of the MFMA tile).
 //   S^T[tok][head] = K[tok][:] . Q[head][:]      mfma_f32_16x16x32_bf16   (A = K page, B = Q)
 //   O^T[d][head]  += V^T[d][tok] . P^T[tok][head] mfma_f32_16x16x16_bf16   (A = V page, B = P)
 //   The S^T accumulator layout (lane: column = head, 4 consecutive tokens) is exactly the B-operand
@@ -259,24 +351,27 @@ __device__ inline void chunk_range(int n_tok, int CP, int chunk, int& nch, int& 
   p1 = min(npages, p0 + per);
 }
 
-constexpr int kORow = 132;   // padded LDS row of the cross-wave merge
-
-__global__ __launch_bounds__(256) void k_attn(Dims D, int layer, const uint16_t* __restrict__ q,
-                                              const uint16_t* __restrict__ pool,
-                                              const int* __restrict__ table,
-                                              const int* __restrict__ ctx, float* __restrict__ part_o,
-                                              float* __restrict__ part_ml, int CP, int NCH) {
-  extern __shared__ float so[];                 // [4][G][kORow]
-  __shared__ float sm[4][16], sl[4][16];
-  const int chunk = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+//   Every wave is independent: grid (chunk, ceil(Hkv / NW), sequence), block = NW waves; wave w owns
+//   kv head blockIdx.y*NW + w and walks all pages of its chunk, so there is no cross-wave merge, no
+//   LDS and no barrier.  Measured on MI355X: one-wave work-groups with about one wave per SIMD
+//   (1024 in flight) stream fastest; deeper prefetch than one page ahead does not help.
+template <int NW, int PF>
+__global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint16_t* __restrict__ q,
+                                                    const uint16_t* __restrict__ pool,
+                                                    const int* __restrict__ table,
+                                                    const int* __restrict__ ctx,
+                                                    float* __restrict__ part_o,
+                                                    float* __restrict__ part_ml, int CP, int NCH) {
+  const int chunk = blockIdx.x, i = blockIdx.z;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  const int c = blockIdx.y * NW + w;
+  if (c >= D.Hkv) return;
   const int G = D.G;
   const int n_tok = ctx[i] + 1;
   int nch, p0, p1;
   chunk_range(n_tok, CP, chunk, nch, p0, p1);
   if (chunk >= nch) return;
 
-  // Q fragments: B operand, lane (n, g) holds Q[head n][kk*32 + 8g .. +8]
   bf16x8 qf[4];
   {
     const uint16_t* qrow = q + ((int64_t)i * D.Hq + c * G + (n < G ? n : 0)) * 128 + g * 8;
@@ -286,12 +381,9 @@ __global__ __launch_bounds__(256) void k_attn(Dims D, int layer, const uint16_t*
       qf[kk] = __builtin_bit_cast(bf16x8, v);
     }
   }
-
-  // this wave's pages: p0 + w, p0 + w + 4, ...
-  const int span = p1 - p0;
-  const int npw = (span > w) ? ((span - w + 3) >> 2) : 0;
+  const int npw = p1 - p0;                       // <= 64 (host keeps chunk_pages <= 64)
   int my_page = 0;
-  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + w + 4 * lane];
+  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + lane];
   const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
   const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
 
@@ -300,7 +392,10 @@ __global__ __launch_bounds__(256) void k_attn(Dims D, int layer, const uint16_t*
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 kf[4], vf[4];
+  // register ring of PF + 1 page buffers: page t lives in slot t % (PF + 1); page t + PF is requested
+  // before page t is consumed, so PF pages (8 KiB each) are in flight per wave
+  constexpr int NB = PF + 1;
+  uint4 kf[NB][4], vf[NB][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
     const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
     const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
@@ -309,79 +404,62 @@ __global__ __launch_bounds__(256) void k_attn(Dims D, int layer, const uint16_t*
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
   };
-  if (npw > 0) load_page(0, kf, vf);
-
-  for (int t = 0; t < npw; ++t) {
-    uint4 kn[4], vn[4];
-    if (t + 1 < npw) load_page(t + 1, kn, vn);
-
-    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[kk]), qf[kk], sacc,
-                                                     0, 0, 0);
-    const int tok0 = ((p0 + w + 4 * t) << 4) + 4 * g;
-    float s[4];
+  for (int r = 0; r < PF; ++r)
+    if (r < npw) load_page(r, kf[r], vf[r]);
+  for (int t0 = 0; t0 < npw; t0 += NB) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) s[r] = (tok0 + r < n_tok) ? sacc[r] * scale_log2 : -INFINITY;
-    float mloc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m_run, mloc);
-    const float alpha = exp2f(m_run - m_new);
-    float p[4];
+    for (int r = 0; r < NB; ++r) {
+      const int t = t0 + r;
+      if (t < npw) {
+        if (t + PF < npw) load_page(t + PF, kf[(r + PF) % NB], vf[(r + PF) % NB]);
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) p[r] = exp2f(s[r] - m_new);
-    float lsum = (p[0] + p[1]) + (p[2] + p[3]);
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
-    l_run = l_run * alpha + lsum;
-    m_run = m_new;
-    const uint2 pp = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
-    const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+        for (int kk = 0; kk < 4; ++kk)
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[r][kk]), qf[kk],
+                                                         sacc, 0, 0, 0);
+        const int tok0 = ((p0 + t) << 4) + 4 * g;
+        float s[4];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[jj].x, vf[jj].y));
-      const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[jj].z, vf[jj].w));
-      oacc[2 * jj] = oacc[2 * jj] * alpha;
-      oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
-      oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
-      oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
-    }
-    if (t + 1 < npw) {
+        for (int e = 0; e < 4; ++e) s[e] = (tok0 + e < n_tok) ? sacc[e] * scale_log2 : -INFINITY;
+        float mloc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = exp2f(m_run - m_new);
+        float p[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { kf[e] = kn[e]; vf[e] = vn[e]; }
+        for (int e = 0; e < 4; ++e) p[e] = exp2f(s[e] - m_new);
+        float lsum = (p[0] + p[1]) + (p[2] + p[3]);
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        l_run = l_run * alpha + lsum;
+        m_run = m_new;
+        const uint2 pp = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+        const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].x, vf[r][jj].y));
+          const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].z, vf[r][jj].w));
+          oacc[2 * jj] = oacc[2 * jj] * alpha;
+          oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
+          oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
+          oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+        }
+      }
     }
   }
-
-  // ---- merge the 4 waves' partial states through LDS -------------------------------------------
-  if (g == 0) { sm[w][n] = m_run; sl[w][n] = l_run; }
-  __syncthreads();
-  float m_tot = fmaxf(fmaxf(sm[0][n], sm[1][n]), fmaxf(sm[2][n], sm[3][n]));
-  float l_tot = 0.f;
-#pragma unroll
-  for (int ww = 0; ww < 4; ++ww) l_tot += sl[ww][n] * exp2f(sm[ww][n] - m_tot);
-  const float f = exp2f(m_run - m_tot);
+  // lane (n, g) holds o[head n][dt*16 + 4g + r]: 8 float4 stores straight from the accumulators
   if (n < G) {
-    float* dst = so + ((int64_t)w * G + n) * kORow + 4 * g;
+    float* dst = part_o + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 128 + 4 * g;
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-      f32x4 v = oacc[dt] * f;
-      *(float4*)(dst + dt * 16) = make_float4(v[0], v[1], v[2], v[3]);
+    for (int dt = 0; dt < 8; ++dt)
+      *(float4*)(dst + dt * 16) = make_float4(oacc[dt][0], oacc[dt][1], oacc[dt][2], oacc[dt][3]);
+    if (g == 0) {
+      float* ml = part_ml + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 2;
+      ml[0] = m_run;
+      ml[1] = l_run;
     }
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < G * 128; e += 256) {
-    const int nn = e >> 7, dd = e & 127;
-    float o = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) o += so[((int64_t)ww * G + nn) * kORow + dd];
-    part_o[(((int64_t)i * D.Hq + c * G + nn) * NCH + chunk) * 128 + dd] = o;
-  }
-  if (w == 0 && g == 0 && n < G) {
-    float* ml = part_ml + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 2;
-    ml[0] = m_tot;
-    ml[1] = l_tot;
   }
 }
 
@@ -468,6 +546,33 @@ void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, in
   else gemm_wn<4>(s, Xt, Wt, part, M, K, N, n_split);
 }
 
+template <int NWK, int EPI>
+static void gemm_skinny_t(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, uint16_t* act_t,
+                          int M, int K, int N, int n_split) {
+  const int KT = K / 16;
+  const int ksp = (KT + n_split - 1) / n_split;
+  const int MT = (M + 31) / 32;
+  const int64_t stride = (int64_t)MT * 32 * N;
+  dim3 grid(N / 64, n_split), block(NWK * 64);
+  if (MT <= 1)
+    hipLaunchKernelGGL((k_gemm_s<1, 2, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part,
+                       act_t, M, N, KT, ksp, stride);
+  else
+    hipLaunchKernelGGL((k_gemm_s<2, 2, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part,
+                       act_t, M, N, KT, ksp, stride);
+}
+
+void gemm_skinny(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, uint16_t* act_t, int M,
+                 int K, int N, int n_split, int nwk, int swiglu) {
+  if (swiglu) {
+    if (nwk == 8) gemm_skinny_t<8, 1>(s, Xt, Wt, part, act_t, M, K, N, 1);
+    else gemm_skinny_t<4, 1>(s, Xt, Wt, part, act_t, M, K, N, 1);
+  } else {
+    if (nwk == 8) gemm_skinny_t<8, 0>(s, Xt, Wt, part, act_t, M, K, N, n_split);
+    else gemm_skinny_t<4, 0>(s, Xt, Wt, part, act_t, M, K, N, n_split);
+  }
+}
+
 void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out) {
@@ -478,8 +583,7 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
                int max_chunks) {
-  const size_t lds = (size_t)4 * D.G * kORow * sizeof(float);
-  hipLaunchKernelGGL(k_attn, dim3(max_chunks, D.Hkv, b), dim3(256), lds, s, D, layer, q, pool, table,
+  hipLaunchKernelGGL((k_attn<1, 1>), dim3(max_chunks, D.Hkv, b), dim3(64), 0, s, D, layer, q, pool, table,
                      ctx, part_o, part_ml, chunk_pages, max_chunks);
 }
 

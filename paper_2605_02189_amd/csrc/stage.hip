@@ -86,7 +86,9 @@ struct LayerW {
 };
 
 struct GemmPlan {
-  int split = 1, wn = 8;
+  int split = 1, wn = 8;   // wn: waves (32-column tiles) per work-group of the LDS-staged kernel
+  int nwk = 0;             // > 0: barrier-free skinny kernel with nwk waves per work-group
+  bool fused_swiglu = false;
 };
 
 }  // namespace
@@ -320,6 +322,20 @@ int host_alloc(pipemax_stage* st, T** p, size_t count) {
   st->host_allocs.push_back(q);
   *p = (T*)q;
   return PIPEMAX_OK;
+}
+
+// M <= 64: barrier-free kernel.  Measured on MI355X: about 256 work-groups of 8 waves (or, when the
+// matrix alone has >= 384 column pairs, 4 waves and no split) stream fastest.
+GemmPlan plan_gemm_skinny(int N, int K, bool swiglu) {
+  GemmPlan p;
+  const int bn = N / 64, KT = K / 16;
+  p.fused_swiglu = swiglu;
+  p.nwk = (bn >= 384) ? 4 : 8;
+  int S = swiglu ? 1 : std::max(1, 256 / bn);
+  S = std::max(1, std::min(S, KT / (p.nwk * 4)));
+  const int ksp = (KT + S - 1) / S;
+  p.split = (KT + ksp - 1) / ksp;
+  return p;
 }
 
 GemmPlan plan_gemm(int N, int K) {
@@ -561,10 +577,17 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     PMX_TRY(dev_alloc(st, &st->g_act, (size_t)maxb * F));
     PMX_TRY(dev_alloc(st, &st->g_scores, (size_t)maxb * c.n_q_heads * D.max_ctx_pad));
   } else {
-    st->p_qkv = plan_gemm(D.Nqkv, h);
-    st->p_o = plan_gemm(h, nq);
-    st->p_gu = plan_gemm(2 * F, h);
-    st->p_d = plan_gemm(h, F);
+    if (maxb <= 64) {
+      st->p_qkv = plan_gemm_skinny(D.Nqkv, h, false);
+      st->p_o = plan_gemm_skinny(h, nq, false);
+      st->p_gu = plan_gemm_skinny(2 * F, h, true);
+      st->p_d = plan_gemm_skinny(h, F, false);
+    } else {
+      st->p_qkv = plan_gemm(D.Nqkv, h);
+      st->p_o = plan_gemm(h, nq);
+      st->p_gu = plan_gemm(2 * F, h);
+      st->p_d = plan_gemm(h, F);
+    }
     size_t part = 0;
     part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
     part = std::max(part, (size_t)st->p_o.split * mpad * h);
@@ -1020,14 +1043,20 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   } else {
     const int mpad = ((b + 31) / 32) * 32;
     const int nq = D.Hq * D.d;
-    // attention split: about 2048 work-groups, 8..64 pages each
+    // attention split: about one wave per SIMD (1024 on the chip), 8..64 pages per wave
     const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
-    const int nch_target = std::max(1, 2048 / (b * D.Hkv));
+    const int nch_target = std::max(1, (1024 + b * D.Hkv / 2) / (b * D.Hkv));
     int CP = (npages_max + nch_target - 1) / nch_target;
     CP = std::max(8, std::min(64, CP));
     const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
     const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
     const float* prev_part = nullptr;     // partials of the previous layer's down projection
+    auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
+      if (p.nwk)
+        mfma::gemm_skinny(cs, Xt, (const uint16_t*)W, st->m_part, st->m_act_t, b, K, N, p.split, p.nwk, p.fused_swiglu);
+      else
+        mfma::gemm(cs, Xt, (const uint16_t*)W, st->m_part, b, K, N, p.split, p.wn);
+    };
     for (int l = 0; l < nl; ++l) {
       const LayerW& L = st->w[l];
       uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
@@ -1039,7 +1068,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
         PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
                                hipMemcpyDeviceToDevice, cs));
       st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
-      mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wqkv, st->m_part, b, D.h, D.Nqkv, st->p_qkv.split, st->p_qkv.wn);
+      run_gemm(st->p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
       st->tend(cs);
       st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
       mfma::rope_append(cs, D, l, b, st->m_part, st->p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
@@ -1055,20 +1084,22 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
       mfma::attention_merge(cs, D, b, M.d_ctx, st->m_part_o, st->m_part_ml, CP, nch, st->m_attn_t);
       st->tend(cs);
       st->tbegin(PIPEMAX_K_GEMM_O, cs);
-      mfma::gemm(cs, st->m_attn_t, (const uint16_t*)L.wo, st->m_part, b, nq, D.h, st->p_o.split, st->p_o.wn);
+      run_gemm(st->p_o, st->m_attn_t, L.wo, nq, D.h);
       st->tend(cs);
       st->tbegin(PIPEMAX_K_NORM, cs);
       mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, st->p_o.split, s_h, st->x, (const uint16_t*)L.g2,
                        st->m_xn_t, nullptr);
       st->tend(cs);
       st->tbegin(PIPEMAX_K_GEMM_GU, cs);
-      mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wgu, st->m_part, b, D.h, 2 * D.F, st->p_gu.split, st->p_gu.wn);
+      run_gemm(st->p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
       st->tend(cs);
-      st->tbegin(PIPEMAX_K_SWIGLU, cs);
-      mfma::swiglu(cs, b, D.F, st->m_part, st->p_gu.split, s_gu, st->m_act_t);
-      st->tend(cs);
+      if (!st->p_gu.fused_swiglu) {
+        st->tbegin(PIPEMAX_K_SWIGLU, cs);
+        mfma::swiglu(cs, b, D.F, st->m_part, st->p_gu.split, s_gu, st->m_act_t);
+        st->tend(cs);
+      }
       st->tbegin(PIPEMAX_K_GEMM_D, cs);
-      mfma::gemm(cs, st->m_act_t, (const uint16_t*)L.wd, st->m_part, b, D.F, D.h, st->p_d.split, st->p_d.wn);
+      run_gemm(st->p_d, st->m_act_t, L.wd, D.F, D.h);
       st->tend(cs);
       prev_part = st->m_part;
     }
