@@ -63,13 +63,33 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);
 
-// Split-K paged GQA decode attention + merge.  chunk_pages = target pages per work-group,
-// max_chunks = grid extent along the context axis (>= ceil(max pages / chunk_pages)).
+// Split-K paged GQA decode attention.  chunk_pages = target pages per wave (<= 64), max_chunks = grid
+// extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
+// (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)
+// and writes the A-tiled bf16 input of the output projection.
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q,
                const uint16_t* pool, const int* table, const int* ctx, float* part_o, float* part_ml,
-               int chunk_pages, int max_chunks);
-void attention_merge(hipStream_t s, const Dims& D, int b, const int* ctx, const float* part_o,
-                     const float* part_ml, int chunk_pages, int max_chunks, uint16_t* out_t);
+               int chunk_pages, int max_chunks, int* counters, uint16_t* out_t);
+
+// ---- fused pipeline for b <= 64 rows -----------------------------------------------------------------
+// x = hidden_in; ssq_out[i][0] = sum of squares of row i (other nb-1 entries 0); xg_t = x * gain as
+// A-tiled bf16; cs = RoPE table of this step.
+void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uint16_t* gain, uint16_t* xg_t,
+           float* ssq_out, int nb, const int* ctx, float2* cs, float rope_base);
+// QKV projection of the un-normalised xg_t with the RMSNorm row factor, RoPE, q rows, paged K/V append
+// and write-back staging in the epilogue.  counters: Nqkv / 64 ints, zero, self-resetting.
+void gemm_qkv_rope_append(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* xg_t, const uint16_t* Wt,
+                          float* part, int* counters, const float* ssq_in, int n_ssq_in, const float2* cs,
+                          const int* ctx, const int* table, uint16_t* pool, uint16_t* staging, uint16_t* q_out,
+                          int n_split, int nwk);
+// x += X @ W; then either (hout == null) xg_t = x * gain_next (A-tiled bf16) and ssq_out[m][N/64] partial
+// sums of squares, or hout = bf16(x) row-major.  ctx_advance != null: ctx_advance[i] += 1 for i < b.
+void gemm_resid(hipStream_t s, int b, int K, int N, const uint16_t* Xt, const uint16_t* Wt, float* part,
+                int* counters, float* x, const uint16_t* gain_next, uint16_t* xg_t, float* ssq_out,
+                uint16_t* hout, int* ctx_advance, int n_split, int nwk);
+// act_t = silu(r g) * (r u) with the RMSNorm row factor r from ssq_in; W = interleaved gate/up.
+void gemm_swiglu(hipStream_t s, int b, int K, int F, float eps, const uint16_t* xg_t, const uint16_t* Wt,
+                 const float* ssq_in, int n_ssq_in, uint16_t* act_t, int nwk);
 
 // act_t (A-tiled, KT = F/16) = silu(sum_s gate) * sum_s up ; partial columns are in the
 // gate/up-interleaved order of the tiled W_gu (32 gate columns, then the 32 up columns).

@@ -282,6 +282,262 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_s(const uint4* __restrict__ X
 }
 
 // =================================================================================================
+// The same streaming GEMM with the consumer fused into its epilogue (M <= 64 rows, NT = 2).
+//   Split-K across work-groups (gridDim.y > 1) is resolved inside the kernel: every block stores its
+//   fp32 partial, and the block that arrives last at the column block's counter sums all partials in
+//   split order (so the result does not depend on which block was last) and runs the epilogue.
+//   The RMSNorm of the A operand is folded in: A holds x * gain (bf16, not normalised) and the row
+//   factor r_m = rsqrt(mean(x_m^2) + eps) is applied to the accumulators; the sums of squares come
+//   from the producing epilogue as per-column-block partials (deterministic, no atomics on floats).
+//   EPI_SWIGLU: act = silu(r g) * (r u)                      -> A-tiled bf16 (gate/up interleaved W)
+//   EPI_RESID : x += acc; partial sums of x^2; x * gain_next -> A-tiled bf16 (or the bf16 stage output)
+//   EPI_QKV   : r * acc, RoPE, q -> bf16 rows, k / v -> page slot + write-back staging
+//               (W_qkv tiles are ordered so that a block holds columns j and j + 64 of one head)
+// =================================================================================================
+enum { EPI_SWIGLU = 1, EPI_RESID = 2, EPI_QKV = 3 };
+
+struct FusedArgs {
+  int* counters;          // one per 64-column block; zero at launch, reset by the last arriver
+  const float* ssq_in;    // [64][n_ssq_in] partial sums of squares of A's rows, or null (no row factor)
+  int n_ssq_in;
+  float inv_h, eps;
+  uint16_t* act_t;        // EPI_SWIGLU
+  float* x;               // EPI_RESID
+  const uint16_t* gain_next;
+  uint16_t* xg_t;
+  float* ssq_out;
+  uint16_t* hout;
+  int* ctx_advance;
+  int layer;              // EPI_QKV
+  const float2* cs;
+  const int* ctx;
+  const int* table;
+  uint16_t* pool;
+  uint16_t* staging;
+  uint16_t* q_out;
+  int Hq, Hkv, max_pages;
+  int64_t page_elems;
+};
+
+template <int MT, int NWK, int U, int EPI>
+__global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ Xt,
+                                                     const uint4* __restrict__ Wt,
+                                                     float* __restrict__ part, FusedArgs A, int M, int N,
+                                                     int KT, int ksp, int64_t split_stride) {
+  constexpr int NT = 2;
+  __shared__ float red[NWK][NT * 16][64];
+  __shared__ float rs[MT * 32];
+  __shared__ int s_last;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int nt0 = blockIdx.x * NT;
+  const int kb0 = blockIdx.y * ksp;
+  const int kb1 = min(KT, kb0 + ksp);
+  const int nsteps = (kb1 - kb0 > w) ? (kb1 - kb0 - w + NWK - 1) / NWK : 0;
+  const uint4* wp = Wt + ((int64_t)nt0 * KT + kb0 + w) * 64 + lane;
+  const uint4* xp = Xt + ((int64_t)kb0 + w) * 64 + lane;
+
+  f32x16 acc[NT * MT];
+#pragma unroll
+  for (int t = 0; t < NT * MT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  uint4 wb[U][NT], xb[U][MT];
+  auto load = [&](int j, uint4* wd, uint4* xd) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wd[nt] = ld_stream(wp + ((int64_t)nt * KT + (int64_t)j * NWK) * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xd[mt] = xp[((int64_t)mt * KT + (int64_t)j * NWK) * 64];
+  };
+#pragma unroll
+  for (int r = 0; r < U; ++r)
+    if (r < nsteps) load(r, wb[r], xb[r]);
+
+  // row factors of the folded RMSNorm (the loads overlap the first weight fragments' latency)
+  if (A.ssq_in != nullptr && tid < MT * 32) {
+    const float* p = A.ssq_in + (int64_t)tid * A.n_ssq_in;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int t = 0;
+    for (; t + 3 < A.n_ssq_in; t += 4) { s0 += p[t]; s1 += p[t + 1]; s2 += p[t + 2]; s3 += p[t + 3]; }
+    for (; t < A.n_ssq_in; ++t) s0 += p[t];
+    rs[tid] = 1.0f / sqrtf(((s0 + s1) + (s2 + s3)) * A.inv_h + A.eps);
+  }
+
+  for (int j0 = 0; j0 < nsteps; j0 += U) {
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const int j = j0 + r;
+      if (j < nsteps) {
+        bf16x8 Af[MT], Bf[NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) Af[mt] = __builtin_bit_cast(bf16x8, xb[r][mt]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) Bf[nt] = __builtin_bit_cast(bf16x8, wb[r][nt]);
+        if (j + U < nsteps) load(j + U, wb[r], xb[r]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[nt * MT + mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[mt], Bf[nt], acc[nt * MT + mt], 0, 0, 0);
+      }
+    }
+  }
+
+  // the epilogue of output element pair (row m; columns c and c + 32 of the block), c = lane & 31.
+  // All 64 lanes call it together (it contains wave shuffles); the 32 lanes of a half-wave share m.
+  auto epi = [&](int m, int c, float lo, float hi) {
+    const bool ok = m < M;
+    if (EPI == EPI_SWIGLU) {
+      if (ok) {
+        const float r = A.ssq_in ? rs[m] : 1.0f;
+        const float g = lo * r, u = hi * r;
+        A.act_t[a_tiled_idx(N >> 5, m, blockIdx.x * 32 + c)] = f2bf(g / (1.0f + expf(-g)) * u);
+      }
+    } else if (EPI == EPI_RESID) {
+      const int64_t o = (int64_t)m * N + (int64_t)blockIdx.x * 64 + c;
+      float xl = 0.f, xh = 0.f;
+      if (ok) {
+        xl = A.x[o] + lo;
+        xh = A.x[o + 32] + hi;
+        A.x[o] = xl;
+        A.x[o + 32] = xh;
+        if (A.hout) {
+          A.hout[o] = f2bf(xl);
+          A.hout[o + 32] = f2bf(xh);
+        } else {
+          const int n = blockIdx.x * 64 + c;
+          A.xg_t[a_tiled_idx(N >> 4, m, n)] = f2bf(xl * bf2f(A.gain_next[n]));
+          A.xg_t[a_tiled_idx(N >> 4, m, n + 32)] = f2bf(xh * bf2f(A.gain_next[n + 32]));
+        }
+      }
+      float ss = xl * xl + xh * xh;
+#pragma unroll
+      for (int o2 = 16; o2 > 0; o2 >>= 1) ss += __shfl_xor(ss, o2);
+      if (ok && c == 0 && A.ssq_out) A.ssq_out[(int64_t)m * gridDim.x + blockIdx.x] = ss;
+    } else {
+      if (ok) {
+        const float r = rs[m];
+        lo *= r;
+        hi *= r;
+        const int hd = blockIdx.x >> 1, j = ((blockIdx.x & 1) << 5) + c;
+        if (hd < A.Hq) {
+          const float2 cs = A.cs[m * 64 + j];
+          uint16_t* q = A.q_out + ((int64_t)m * A.Hq + hd) * 128;
+          q[j] = f2bf(lo * cs.x - hi * cs.y);
+          q[j + 64] = f2bf(hi * cs.x + lo * cs.y);
+        } else {
+          const int kv = (hd < A.Hq + A.Hkv) ? 0 : 1;
+          const int head = hd - A.Hq - kv * A.Hkv;
+          if (kv == 0) {
+            const float2 cs = A.cs[m * 64 + j];
+            const float a = lo * cs.x - hi * cs.y, b2 = hi * cs.x + lo * cs.y;
+            lo = a;
+            hi = b2;
+          }
+          const int pos = A.ctx[m];
+          const int phys = A.table[(int64_t)m * A.max_pages + (pos >> 4)];
+          const int slot = pos & 15;
+          uint16_t* sub = A.pool + (int64_t)phys * A.page_elems + sub_block_off(A.Hkv, 128, A.layer, head, kv);
+          const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
+          if (kv == 0) {
+            sub[k_sub_idx(slot, j)] = blo;
+            sub[k_sub_idx(slot, j + 64)] = bhi;
+          } else {
+            sub[v_sub_idx(slot, j)] = blo;
+            sub[v_sub_idx(slot, j + 64)] = bhi;
+          }
+          uint16_t* st = A.staging + (((int64_t)m * 2 + kv) * A.Hkv + head) * 128;
+          st[j] = blo;
+          st[j + 64] = bhi;
+        }
+      }
+    }
+  };
+
+  const bool split = gridDim.y > 1;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt) __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[w][nt * 16 + r][lane] = acc[nt * MT + mt][r];
+    __syncthreads();            // also orders the rs[] writes before their use
+    for (int r = w; r < 16; r += NWK) {
+      float v[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float a = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NWK; ++ww) a += red[ww][nt * 16 + r][lane];
+        v[nt] = a;
+      }
+      const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (split) {
+        if (m < M) {
+          float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + (lane & 31);
+          out[0] = v[0];
+          out[32] = v[1];
+        }
+      } else {
+        epi(m, lane & 31, v[0], v[1]);
+      }
+    }
+  }
+  if (split) {
+    __threadfence();                       // this block's partial is visible device-wide ...
+    __syncthreads();
+    if (tid == 0) s_last = (atomicAdd(&A.counters[blockIdx.x], 1) == (int)gridDim.y - 1);
+    __syncthreads();                       // ... before its arrival is counted
+    if (!s_last) return;
+    __threadfence();                       // the other blocks' partials are visible to this block
+    if (tid == 0) A.counters[blockIdx.x] = 0;
+    for (int e = tid; e < MT * 1024; e += NWK * 64) {
+      const int m = e >> 5, c = e & 31;
+      float lo = 0.f, hi = 0.f;
+      if (m < M) {
+        const float* p = part + (int64_t)m * N + (int64_t)nt0 * 32 + c;
+        for (int s = 0; s < (int)gridDim.y; ++s) {
+          lo += p[s * split_stride];
+          hi += p[s * split_stride + 32];
+        }
+      }
+      epi(m, c, lo, hi);
+    }
+  }
+  if (EPI == EPI_RESID && A.ctx_advance != nullptr && blockIdx.x == 0 && tid < M) A.ctx_advance[tid] += 1;
+}
+
+// first kernel of a step: x = hidden_in, sums of squares, x * gain -> A-tiled bf16, RoPE table
+//   grid (b), block 256.  ssq_out[i][0] = sum of squares of row i, [1..nb) = 0.
+__global__ __launch_bounds__(256) void k_first(int h, const uint16_t* __restrict__ hin, float* __restrict__ x,
+                                               const uint16_t* __restrict__ gain, uint16_t* __restrict__ xg_t,
+                                               float* __restrict__ ssq_out, int nb, const int* __restrict__ ctx,
+                                               float2* __restrict__ cs, double base) {
+  __shared__ float sh[4];
+  const int i = blockIdx.x;
+  const int KT = h >> 4;
+  float ss = 0.f;
+  for (int j0 = threadIdx.x * 8; j0 < h; j0 += 256 * 8) {
+    float v[8], gv[8];
+    unpack8(*(const uint4*)(hin + (int64_t)i * h + j0), v);
+    unpack8(*(const uint4*)(gain + j0), gv);
+    *(float4*)(x + (int64_t)i * h + j0) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(x + (int64_t)i * h + j0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ss += v[e] * v[e]; v[e] *= gv[e]; }
+    *(uint4*)(xg_t + a_tiled_idx(KT, i, j0)) = pack8(v);
+  }
+  ss = block_sum256(ss, sh);
+  for (int t = threadIdx.x; t < nb; t += 256) ssq_out[(int64_t)i * nb + t] = (t == 0) ? ss : 0.f;
+  if (threadIdx.x < 64) {
+    const int j = threadIdx.x;
+    const double ang = (double)ctx[i] * pow(base, -2.0 * (double)j / 128.0);
+    cs[i * 64 + j] = make_float2((float)cos(ang), (float)sin(ang));
+  }
+}
+
+// =================================================================================================
 // RoPE + KV append + write-back staging; also reduces the split-K partials of the QKV GEMM
 //   grid (b, Hq + 2 Hkv), block 64: thread j rotates the pair (j, j + 64)
 // =================================================================================================
@@ -290,11 +546,14 @@ __global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const flo
                                                     const int* ctx, const int* table, uint16_t* pool,
                                                     uint16_t* staging, uint16_t* q_out) {
   const int i = blockIdx.x, hd = blockIdx.y, j = threadIdx.x;
+  // the tiled W_qkv orders the four 32-column tiles of a head as (0, 2, 1, 3): element j of the
+  // head is GEMM output column j (j < 32), j + 32 (32 <= j < 64), j - 32 (64 <= j < 96), j (j >= 96)
   const float* row = part + (int64_t)i * D.Nqkv + (int64_t)hd * 128;
+  const int c_lo = (j < 32) ? j : j + 32, c_hi = (j < 32) ? j + 32 : j + 64;
   float lo = 0.f, hi = 0.f;
   for (int s = 0; s < n_split; ++s) {
-    lo += row[s * split_stride + j];
-    hi += row[s * split_stride + j + 64];
+    lo += row[s * split_stride + c_lo];
+    hi += row[s * split_stride + c_hi];
   }
   const int pos = ctx[i];
   if (hd < D.Hq) {
@@ -315,11 +574,6 @@ __global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const flo
   const int phys = table[(int64_t)i * D.max_pages + (pos >> 4)];
   const int slot = pos & 15;
   uint16_t* sub = pool + (int64_t)phys * D.page_elems + sub_block_off(D.Hkv, 128, layer, head, kv);
-  if (slot == 0) {     // first token of a fresh page: clear the 4 KiB sub-block first
-    uint4* z = (uint4*)sub;
-    for (int e = j; e < 256; e += 64) z[e] = make_uint4(0, 0, 0, 0);
-    __syncthreads();
-  }
   const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
   if (kv == 0) {
     sub[k_sub_idx(slot, j)] = blo;
@@ -361,7 +615,9 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
                                                     const int* __restrict__ table,
                                                     const int* __restrict__ ctx,
                                                     float* __restrict__ part_o,
-                                                    float* __restrict__ part_ml, int CP, int NCH) {
+                                                    float* __restrict__ part_ml, int CP, int NCH,
+                                                    int* __restrict__ counters,
+                                                    uint16_t* __restrict__ out_t) {
   const int chunk = blockIdx.x, i = blockIdx.z;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
   const int c = blockIdx.y * NW + w;
@@ -437,10 +693,18 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
         m_run = m_new;
         const uint2 pp = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
         const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+        // slots past the sequence's last token hold whatever the page held before: their weight is
+        // 0, but 0 * NaN is NaN, so the V operand of the last (partial) page is masked as well
+        uint32_t vm0 = 0xffffffffu, vm1 = 0xffffffffu;
+        if (tok0 + 3 >= n_tok) {
+          const int valid = n_tok - tok0;                       // tokens tok0 .. tok0+3 of this lane
+          vm0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+          vm1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+        }
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].x, vf[r][jj].y));
-          const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].z, vf[r][jj].w));
+          const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].x & vm0, vf[r][jj].y & vm1));
+          const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].z & vm0, vf[r][jj].w & vm1));
           oacc[2 * jj] = oacc[2 * jj] * alpha;
           oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
           oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
@@ -449,7 +713,20 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
       }
     }
   }
-  // lane (n, g) holds o[head n][dt*16 + 4g + r]: 8 float4 stores straight from the accumulators
+  const int KTo = D.Hq * 128 / 16;
+  if (nch == 1) {
+    // one chunk: lane (n, g) holds o[head n][dt*16 + 4g + r]; normalise and write the A-tiled bf16
+    // input of the output projection straight from the accumulators
+    if (n < G) {
+      const float inv = 1.0f / l_run;
+      const int k0 = (c * G + n) * 128 + 4 * g;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out_t[a_tiled_idx(KTo, i, k0 + dt * 16 + e)] = f2bf(oacc[dt][e] * inv);
+    }
+    return;
+  }
   if (n < G) {
     float* dst = part_o + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 128 + 4 * g;
 #pragma unroll
@@ -461,27 +738,31 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
       ml[1] = l_run;
     }
   }
-}
-
-// grid (b, Hq), block 128 (one thread per output dimension); writes the A-tiled bf16 input of the
-// output projection
-__global__ __launch_bounds__(128) void k_attn_merge(Dims D, const int* ctx, const float* part_o,
-                                                    const float* part_ml, int CP, int NCH,
-                                                    uint16_t* out_t) {
-  const int i = blockIdx.x, u = blockIdx.y, dd = threadIdx.x;
-  int nch, p0, p1;
-  chunk_range(ctx[i] + 1, CP, 0, nch, p0, p1);
-  const float* ml = part_ml + ((int64_t)i * D.Hq + u) * NCH * 2;
-  const float* po = part_o + ((int64_t)i * D.Hq + u) * NCH * 128 + dd;
-  float m_tot = -INFINITY;
-  for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ml[2 * j]);
-  float l = 0.f, o = 0.f;
-  for (int j = 0; j < nch; ++j) {
-    const float fj = exp2f(ml[2 * j] - m_tot);
-    l += ml[2 * j + 1] * fj;
-    o += po[(int64_t)j * 128] * fj;
+  // the wave that arrives last at the (sequence, kv head) counter merges the chunks, in chunk order
+  __threadfence();
+  int old = 0;
+  if (lane == 0) old = atomicAdd(&counters[i * D.Hkv + c], 1);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != nch - 1) return;
+  __threadfence();
+  if (lane == 0) counters[i * D.Hkv + c] = 0;
+  for (int nn = 0; nn < G; ++nn) {
+    const float* ml = part_ml + ((int64_t)i * D.Hq + c * G + nn) * NCH * 2;
+    const float* po = part_o + ((int64_t)i * D.Hq + c * G + nn) * NCH * 128;
+    float m_tot = -INFINITY;
+    for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ml[2 * j]);
+    float l = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int j = 0; j < nch; ++j) {
+      const float fj = exp2f(ml[2 * j] - m_tot);
+      l += ml[2 * j + 1] * fj;
+      o0 += po[(int64_t)j * 128 + lane] * fj;
+      o1 += po[(int64_t)j * 128 + 64 + lane] * fj;
+    }
+    const float inv = 1.0f / l;
+    const int k0 = (c * G + nn) * 128;
+    out_t[a_tiled_idx(KTo, i, k0 + lane)] = f2bf(o0 * inv);
+    out_t[a_tiled_idx(KTo, i, k0 + 64 + lane)] = f2bf(o1 * inv);
   }
-  out_t[a_tiled_idx(D.Hq * 128 / 16, i, u * 128 + dd)] = f2bf(o / l);
 }
 
 // =================================================================================================
@@ -582,15 +863,73 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
 
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
-               int max_chunks) {
+               int max_chunks, int* counters, uint16_t* out_t) {
   hipLaunchKernelGGL((k_attn<1, 1>), dim3(max_chunks, D.Hkv, b), dim3(64), 0, s, D, layer, q, pool, table,
-                     ctx, part_o, part_ml, chunk_pages, max_chunks);
+                     ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t);
 }
 
-void attention_merge(hipStream_t s, const Dims& D, int b, const int* ctx, const float* part_o,
-                     const float* part_ml, int chunk_pages, int max_chunks, uint16_t* out_t) {
-  hipLaunchKernelGGL(k_attn_merge, dim3(b, D.Hq), dim3(128), 0, s, D, ctx, part_o, part_ml,
-                     chunk_pages, max_chunks, out_t);
+void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uint16_t* gain, uint16_t* xg_t,
+           float* ssq_out, int nb, const int* ctx, float2* cs, float rope_base) {
+  hipLaunchKernelGGL(k_first, dim3(b), dim3(256), 0, s, h, hin, x, gain, xg_t, ssq_out, nb, ctx, cs,
+                     (double)rope_base);
+}
+
+template <int NWK, int EPI>
+static void gemm_fused_t(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, const FusedArgs& A,
+                         int M, int K, int N, int n_split) {
+  const int KT = K / 16;
+  const int ksp = (KT + n_split - 1) / n_split;
+  const int S = (KT + ksp - 1) / ksp;
+  const int MT = (M + 31) / 32;
+  const int64_t stride = (int64_t)MT * 32 * N;
+  dim3 grid(N / 64, S), block(NWK * 64);
+  if (MT <= 1)
+    hipLaunchKernelGGL((k_gemm_f<1, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
+                       N, KT, ksp, stride);
+  else
+    hipLaunchKernelGGL((k_gemm_f<2, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
+                       N, KT, ksp, stride);
+}
+
+static void gemm_fused(hipStream_t s, int epi, const uint16_t* Xt, const uint16_t* Wt, float* part,
+                       const FusedArgs& A, int M, int K, int N, int n_split, int nwk) {
+  if (epi == EPI_SWIGLU) {
+    if (nwk == 8) gemm_fused_t<8, EPI_SWIGLU>(s, Xt, Wt, part, A, M, K, N, 1);
+    else gemm_fused_t<4, EPI_SWIGLU>(s, Xt, Wt, part, A, M, K, N, 1);
+  } else if (epi == EPI_RESID) {
+    if (nwk == 8) gemm_fused_t<8, EPI_RESID>(s, Xt, Wt, part, A, M, K, N, n_split);
+    else gemm_fused_t<4, EPI_RESID>(s, Xt, Wt, part, A, M, K, N, n_split);
+  } else {
+    if (nwk == 8) gemm_fused_t<8, EPI_QKV>(s, Xt, Wt, part, A, M, K, N, n_split);
+    else gemm_fused_t<4, EPI_QKV>(s, Xt, Wt, part, A, M, K, N, n_split);
+  }
+}
+
+void gemm_qkv_rope_append(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* xg_t, const uint16_t* Wt,
+                          float* part, int* counters, const float* ssq_in, int n_ssq_in, const float2* cs,
+                          const int* ctx, const int* table, uint16_t* pool, uint16_t* staging, uint16_t* q_out,
+                          int n_split, int nwk) {
+  FusedArgs A{};
+  A.counters = counters; A.ssq_in = ssq_in; A.n_ssq_in = n_ssq_in; A.inv_h = 1.0f / (float)D.h; A.eps = D.eps;
+  A.layer = layer; A.cs = cs; A.ctx = ctx; A.table = table; A.pool = pool; A.staging = staging; A.q_out = q_out;
+  A.Hq = D.Hq; A.Hkv = D.Hkv; A.max_pages = D.max_pages; A.page_elems = D.page_elems;
+  gemm_fused(s, EPI_QKV, xg_t, Wt, part, A, b, D.h, D.Nqkv, n_split, nwk);
+}
+
+void gemm_resid(hipStream_t s, int b, int K, int N, const uint16_t* Xt, const uint16_t* Wt, float* part,
+                int* counters, float* x, const uint16_t* gain_next, uint16_t* xg_t, float* ssq_out,
+                uint16_t* hout, int* ctx_advance, int n_split, int nwk) {
+  FusedArgs A{};
+  A.counters = counters; A.x = x; A.gain_next = gain_next; A.xg_t = xg_t; A.ssq_out = ssq_out; A.hout = hout;
+  A.ctx_advance = ctx_advance;
+  gemm_fused(s, EPI_RESID, Xt, Wt, part, A, b, K, N, n_split, nwk);
+}
+
+void gemm_swiglu(hipStream_t s, int b, int K, int F, float eps, const uint16_t* xg_t, const uint16_t* Wt,
+                 const float* ssq_in, int n_ssq_in, uint16_t* act_t, int nwk) {
+  FusedArgs A{};
+  A.ssq_in = ssq_in; A.n_ssq_in = n_ssq_in; A.inv_h = 1.0f / (float)K; A.eps = eps; A.act_t = act_t;
+  gemm_fused(s, EPI_SWIGLU, xg_t, Wt, nullptr, A, b, K, 2 * F, 1, nwk);
 }
 
 void swiglu(hipStream_t s, int b, int F, const float* part, int n_split, int64_t split_stride,

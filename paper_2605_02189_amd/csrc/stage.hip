@@ -122,7 +122,9 @@ struct pipemax_stage {
   float *g_xn = nullptr, *g_qkv = nullptr, *g_q = nullptr, *g_attn = nullptr, *g_gu = nullptr,
         *g_act = nullptr, *g_scores = nullptr;
   uint16_t *m_xn_t = nullptr, *m_q = nullptr, *m_attn_t = nullptr, *m_act_t = nullptr;
-  float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr;
+  float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr, *m_ssq = nullptr;
+  int *m_cnt_gemm = nullptr, *m_cnt_attn = nullptr;
+  bool fused = false;   // b <= 64: consumers fused into the GEMM epilogues
   GemmPlan p_qkv, p_o, p_gu, p_d;
   int nch_alloc = 1;
   float* layer_out = nullptr;
@@ -604,6 +606,14 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     st->nch_alloc = (D.max_pages + 7) / 8;
     PMX_TRY(dev_alloc(st, &st->m_part_o, (size_t)maxb * c.n_q_heads * st->nch_alloc * 128));
     PMX_TRY(dev_alloc(st, &st->m_part_ml, (size_t)maxb * c.n_q_heads * st->nch_alloc * 2));
+    st->fused = (maxb <= 64);
+    const size_t n_cnt = (size_t)std::max(D.Nqkv, h) / 64 + 1;
+    PMX_TRY(dev_alloc(st, &st->m_cnt_gemm, n_cnt));
+    PMX_TRY(dev_alloc(st, &st->m_cnt_attn, (size_t)maxb * c.n_kv_heads));
+    PMX_TRY(dev_alloc(st, &st->m_ssq, (size_t)64 * (h / 64)));
+    PMX_TRY_HIP(hipMemset(st->m_cnt_gemm, 0, n_cnt * sizeof(int)));
+    PMX_TRY_HIP(hipMemset(st->m_cnt_attn, 0, (size_t)maxb * c.n_kv_heads * sizeof(int)));
+    PMX_TRY_HIP(hipMemset(st->m_ssq, 0, (size_t)64 * (h / 64) * sizeof(float)));
   }
   if (c.flags & PIPEMAX_FLAG_CAPTURE_LAYERS) PMX_TRY(dev_alloc(st, &st->layer_out, (size_t)c.n_layers * maxb * h));
 
@@ -681,8 +691,16 @@ int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* ho
 #pragma omp parallel for schedule(static)
   for (int nt = 0; nt < NT; ++nt) {
     int src_col0;
-    if (which == PIPEMAX_W_GU) src_col0 = (nt & 1) ? (F + (nt >> 1) * 32) : ((nt >> 1) * 32);
-    else src_col0 = nt * 32;
+    if (which == PIPEMAX_W_GU) {
+      src_col0 = (nt & 1) ? (F + (nt >> 1) * 32) : ((nt >> 1) * 32);
+    } else if (which == PIPEMAX_W_QKV) {
+      // the four 32-column tiles of a head in the order (0, 2, 1, 3): a 64-column block then holds
+      // elements j and j + 64 of the head, i.e. both halves of RoPE pairs
+      static const int order[4] = {0, 64, 32, 96};
+      src_col0 = (nt >> 2) * 128 + order[nt & 3];
+    } else {
+      src_col0 = nt * 32;
+    }
     for (int kt = 0; kt < KT; ++kt) {
       uint16_t* frag = tiled.data() + ((size_t)nt * KT + kt) * 512;
       for (int lane = 0; lane < 64; ++lane) {
@@ -961,9 +979,11 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   const size_t copy_bytes = (size_t)b * 2 * row * st->esz;
 
   // ---- kernels ---------------------------------------------------------------------------------------
-  st->tbegin(PIPEMAX_K_MISC, cs);
-  launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
-  st->tend(cs);
+  if (st->engine == 0) {
+    st->tbegin(PIPEMAX_K_MISC, cs);
+    launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
+    st->tend(cs);
+  }
 
   auto after_append = [&](int l) -> int {
     if (!writeback) return PIPEMAX_OK;
@@ -1050,70 +1070,112 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     CP = std::max(8, std::min(64, CP));
     const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
     const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
-    const float* prev_part = nullptr;     // partials of the previous layer's down projection
     auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
-      if (p.nwk)
-        mfma::gemm_skinny(cs, Xt, (const uint16_t*)W, st->m_part, st->m_act_t, b, K, N, p.split, p.nwk, p.fused_swiglu);
-      else
-        mfma::gemm(cs, Xt, (const uint16_t*)W, st->m_part, b, K, N, p.split, p.wn);
+      mfma::gemm(cs, Xt, (const uint16_t*)W, st->m_part, b, K, N, p.split, p.wn);
     };
-    for (int l = 0; l < nl; ++l) {
-      const LayerW& L = st->w[l];
-      uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
-      st->tbegin(PIPEMAX_K_NORM, cs);
-      mfma::resid_norm(cs, b, D.h, D.eps, l == 0 ? (const uint16_t*)hidden_in : nullptr, prev_part,
-                       st->p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
-      st->tend(cs);
-      if (st->layer_out && l > 0)
-        PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
-                               hipMemcpyDeviceToDevice, cs));
-      st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
-      run_gemm(st->p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
-      st->tend(cs);
-      st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
-      mfma::rope_append(cs, D, l, b, st->m_part, st->p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
-                        (uint16_t*)st->gpu_pool, stage_l, st->m_q);
-      st->tend(cs);
-      int rc2 = after_append(l);
-      if (rc2) return rc2;
+    auto run_attention = [&](int l) {
       st->tbegin(PIPEMAX_K_ATTN, cs);
       mfma::attention(cs, D, l, b, st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, st->m_part_o,
-                      st->m_part_ml, CP, nch);
+                      st->m_part_ml, CP, nch, st->m_cnt_attn, st->m_attn_t);
       st->tend(cs);
-      st->tbegin(PIPEMAX_K_ATTN_MERGE, cs);
-      mfma::attention_merge(cs, D, b, M.d_ctx, st->m_part_o, st->m_part_ml, CP, nch, st->m_attn_t);
-      st->tend(cs);
-      st->tbegin(PIPEMAX_K_GEMM_O, cs);
-      run_gemm(st->p_o, st->m_attn_t, L.wo, nq, D.h);
-      st->tend(cs);
+    };
+    if (st->fused) {
+      // 5 launches per layer: every element-wise consumer runs in the epilogue of the GEMM before it
+      const int nb = D.h / 64;
       st->tbegin(PIPEMAX_K_NORM, cs);
-      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, st->p_o.split, s_h, st->x, (const uint16_t*)L.g2,
-                       st->m_xn_t, nullptr);
+      mfma::first(cs, b, D.h, (const uint16_t*)hidden_in, st->x, (const uint16_t*)st->w[0].g1, st->m_xn_t, st->m_ssq,
+                  nb, M.d_ctx, st->rope_cs, D.rope_base);
       st->tend(cs);
-      st->tbegin(PIPEMAX_K_GEMM_GU, cs);
-      run_gemm(st->p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
+      for (int l = 0; l < nl; ++l) {
+        const LayerW& L = st->w[l];
+        const bool last = (l == nl - 1);
+        uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
+        st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
+        mfma::gemm_qkv_rope_append(cs, D, l, b, st->m_xn_t, (const uint16_t*)L.wqkv, st->m_part, st->m_cnt_gemm,
+                                   st->m_ssq, nb, st->rope_cs, M.d_ctx, M.d_table, (uint16_t*)st->gpu_pool, stage_l,
+                                   st->m_q, st->p_qkv.split, st->p_qkv.nwk);
+        st->tend(cs);
+        int rc2 = after_append(l);
+        if (rc2) return rc2;
+        run_attention(l);
+        st->tbegin(PIPEMAX_K_GEMM_O, cs);
+        mfma::gemm_resid(cs, b, nq, D.h, st->m_attn_t, (const uint16_t*)L.wo, st->m_part, st->m_cnt_gemm, st->x,
+                         (const uint16_t*)L.g2, st->m_xn_t, st->m_ssq, nullptr, nullptr, st->p_o.split, st->p_o.nwk);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_GU, cs);
+        mfma::gemm_swiglu(cs, b, D.h, D.F, D.eps, st->m_xn_t, (const uint16_t*)L.wgu, st->m_ssq, nb, st->m_act_t,
+                          st->p_gu.nwk);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_D, cs);
+        mfma::gemm_resid(cs, b, D.F, D.h, st->m_act_t, (const uint16_t*)L.wd, st->m_part, st->m_cnt_gemm, st->x,
+                         last ? nullptr : (const uint16_t*)st->w[l + 1].g1, st->m_xn_t, last ? nullptr : st->m_ssq,
+                         last ? (uint16_t*)hidden_out : nullptr, last ? M.d_ctx : nullptr, st->p_d.split,
+                         st->p_d.nwk);
+        st->tend(cs);
+        if (st->layer_out)
+          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)l * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                                 hipMemcpyDeviceToDevice, cs));
+      }
+    } else {
+      const float* prev_part = nullptr;     // partials of the previous layer's down projection
+      st->tbegin(PIPEMAX_K_MISC, cs);
+      launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
       st->tend(cs);
-      if (!st->p_gu.fused_swiglu) {
+      for (int l = 0; l < nl; ++l) {
+        const LayerW& L = st->w[l];
+        uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
+        st->tbegin(PIPEMAX_K_NORM, cs);
+        mfma::resid_norm(cs, b, D.h, D.eps, l == 0 ? (const uint16_t*)hidden_in : nullptr, prev_part,
+                         st->p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
+        st->tend(cs);
+        if (st->layer_out && l > 0)
+          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                                 hipMemcpyDeviceToDevice, cs));
+        st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
+        run_gemm(st->p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
+        mfma::rope_append(cs, D, l, b, st->m_part, st->p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
+                          (uint16_t*)st->gpu_pool, stage_l, st->m_q);
+        st->tend(cs);
+        int rc2 = after_append(l);
+        if (rc2) return rc2;
+        run_attention(l);
+        st->tbegin(PIPEMAX_K_GEMM_O, cs);
+        run_gemm(st->p_o, st->m_attn_t, L.wo, nq, D.h);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_NORM, cs);
+        mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, st->p_o.split, s_h, st->x, (const uint16_t*)L.g2,
+                         st->m_xn_t, nullptr);
+        st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_GU, cs);
+        run_gemm(st->p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
+        st->tend(cs);
         st->tbegin(PIPEMAX_K_SWIGLU, cs);
         mfma::swiglu(cs, b, D.F, st->m_part, st->p_gu.split, s_gu, st->m_act_t);
         st->tend(cs);
+        st->tbegin(PIPEMAX_K_GEMM_D, cs);
+        run_gemm(st->p_d, st->m_act_t, L.wd, D.F, D.h);
+        st->tend(cs);
+        prev_part = st->m_part;
       }
-      st->tbegin(PIPEMAX_K_GEMM_D, cs);
-      run_gemm(st->p_d, st->m_act_t, L.wd, D.F, D.h);
+      st->tbegin(PIPEMAX_K_NORM, cs);
+      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, st->p_d.split, s_h, st->x, nullptr, nullptr,
+                       (uint16_t*)hidden_out);
       st->tend(cs);
-      prev_part = st->m_part;
+      if (st->layer_out)
+        PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(nl - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+                               hipMemcpyDeviceToDevice, cs));
+      st->tbegin(PIPEMAX_K_MISC, cs);
+      launch_advance_ctx(cs, M.d_ctx, b);
+      st->tend(cs);
     }
-    st->tbegin(PIPEMAX_K_NORM, cs);
-    mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, st->p_d.split, s_h, st->x, nullptr, nullptr,
-                     (uint16_t*)hidden_out);
-    st->tend(cs);
-    if (st->layer_out)
-      PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(nl - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
-                             hipMemcpyDeviceToDevice, cs));
   }
-  st->tbegin(PIPEMAX_K_MISC, cs);
-  launch_advance_ctx(cs, M.d_ctx, b);
-  st->tend(cs);
+  if (st->engine == 0) {
+    st->tbegin(PIPEMAX_K_MISC, cs);
+    launch_advance_ctx(cs, M.d_ctx, b);
+    st->tend(cs);
+  }
   PMX_HIP(hipEventRecord(M.ev_step, cs));
   PMX_HIP(hipGetLastError());
   M.stepped = true;

@@ -335,3 +335,25 @@ def test_single_sequence_single_microbatch_from_empty_cache():
         assert runner.stage.get_ctx_lens(0).tolist() == [18]
         assert len(runner.stage.get_block_table(0, 0)[1]) == 2
         runner.stage.destroy()
+
+
+def test_config2_full_size_sampled_rows():
+    """configs[1] at full size, in the launch configuration bench.py times (4 micro-batches x 64
+    sequences x 1024-token prompts, sigma = 1, cyclic schedule): the oracle follows a sample of rows
+    (rows are independent) through all 8 layers for two cycles."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = CONFIGS["C2"]
+    syn = SynthInputs(shape, seed=0, gain_jitter=0.1)
+    steps = 2 * shape.n_microbatches
+    runner = StageRunner(shape, syn, steps=steps, flags=pm.FLAG_CAPTURE_LAYERS).load()
+    assert runner.stage.get_stats()["engine"] == 1
+    sample = {mb: [0, 17 + mb, 63] for mb in range(shape.n_microbatches)}
+    orc = _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer=1e-2, tol_delta=3e-2, oracle_seqs=sample)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs=sample)
+    st = runner.stage.get_stats()
+    # every step streamed one whole micro-batch in (64 prefix pages + grown pages per sequence)
+    assert st["h2d_bytes"] >= steps * 64 * 64 * shape.page_bytes
+    runner.stage.destroy()
