@@ -22,6 +22,25 @@ __device__ inline uint4 ld_stream(const uint4* p) {
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)p));
 }
 
+// Split-K partials cross work-groups (and XCDs, whose L2 caches are not coherent with each other)
+// inside one kernel.  They are written and read with agent-scope relaxed atomics, which the hardware
+// executes as write-through stores / coherent loads, so publishing them needs only "wait until my
+// stores are acknowledged" before the arrival counter is bumped, not a write-back or invalidation
+// of the whole L2 (which is what a device-wide fence costs: ~45 us per kernel when measured here).
+__device__ inline void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void publish_stores() {      // all earlier stores of this wave are acknowledged
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+}
+__device__ inline int arrive(int* counter) {
+  return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ inline float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ inline uint16_t f2bf(float v) {
   uint32_t u = __float_as_uint(v);
@@ -353,14 +372,22 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
   for (int r = 0; r < U; ++r)
     if (r < nsteps) load(r, wb[r], xb[r]);
 
-  // row factors of the folded RMSNorm (the loads overlap the first weight fragments' latency)
-  if (A.ssq_in != nullptr && tid < MT * 32) {
-    const float* p = A.ssq_in + (int64_t)tid * A.n_ssq_in;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    int t = 0;
-    for (; t + 3 < A.n_ssq_in; t += 4) { s0 += p[t]; s1 += p[t + 1]; s2 += p[t + 2]; s3 += p[t + 3]; }
-    for (; t < A.n_ssq_in; ++t) s0 += p[t];
-    rs[tid] = 1.0f / sqrtf(((s0 + s1) + (s2 + s3)) * A.inv_h + A.eps);
+  // row factors of the folded RMSNorm: GS threads per row, each sums n_ssq_in / GS partials in a
+  // fixed order, then a fixed shuffle tree (all loads of a thread are in flight together)
+  if (A.ssq_in != nullptr) {
+    constexpr int GS = (NWK * 64) / (MT * 32);
+    const int m = tid / GS, sub = tid % GS;
+    const float* p = A.ssq_in + (int64_t)m * A.n_ssq_in;
+    float v[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) v[t] = (sub + t * GS < A.n_ssq_in) ? p[sub + t * GS] : 0.f;
+    float sacc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) sacc += v[t];
+    for (int t = sub + 16 * GS; t < A.n_ssq_in; t += GS) sacc += p[t];
+#pragma unroll
+    for (int o2 = GS / 2; o2 > 0; o2 >>= 1) sacc += __shfl_xor(sacc, o2);
+    if (sub == 0) rs[m] = 1.0f / sqrtf(sacc * A.inv_h + A.eps);
   }
 
   for (int j0 = 0; j0 < nsteps; j0 += U) {
@@ -476,8 +503,8 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
       if (split) {
         if (m < M) {
           float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + (lane & 31);
-          out[0] = v[0];
-          out[32] = v[1];
+          st_agent(out, v[0]);
+          st_agent(out + 32, v[1]);
         }
       } else {
         epi(m, lane & 31, v[0], v[1]);
@@ -485,24 +512,41 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
     }
   }
   if (split) {
-    __threadfence();                       // this block's partial is visible device-wide ...
+    publish_stores();                      // this block's partial has reached the coherent level ...
     __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(&A.counters[blockIdx.x], 1) == (int)gridDim.y - 1);
+    if (tid == 0) s_last = (arrive(&A.counters[blockIdx.x]) == (int)gridDim.y - 1);
     __syncthreads();                       // ... before its arrival is counted
     if (!s_last) return;
-    __threadfence();                       // the other blocks' partials are visible to this block
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     if (tid == 0) A.counters[blockIdx.x] = 0;
-    for (int e = tid; e < MT * 1024; e += NWK * 64) {
-      const int m = e >> 5, c = e & 31;
-      float lo = 0.f, hi = 0.f;
-      if (m < M) {
-        const float* p = part + (int64_t)m * N + (int64_t)nt0 * 32 + c;
-        for (int s = 0; s < (int)gridDim.y; ++s) {
-          lo += p[s * split_stride];
-          hi += p[s * split_stride + 32];
-        }
+    constexpr int NE = (MT * 1024) / (NWK * 64);       // output pairs per thread
+    const int S = (int)gridDim.y;
+    float lo[NE], hi[NE];
+#pragma unroll
+    for (int q = 0; q < NE; ++q) {
+      lo[q] = 0.f;
+      hi[q] = 0.f;
+    }
+    // all loads of a split are issued together; the sums run in split order
+    for (int s = 0; s < S; ++s) {
+      float tl[NE], th[NE];
+#pragma unroll
+      for (int q = 0; q < NE; ++q) {
+        const int e = tid + q * NWK * 64, m = e >> 5, c = e & 31;
+        const float* p = part + (int64_t)s * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + c;
+        tl[q] = (m < M) ? ld_agent(p) : 0.f;
+        th[q] = (m < M) ? ld_agent(p + 32) : 0.f;
       }
-      epi(m, c, lo, hi);
+#pragma unroll
+      for (int q = 0; q < NE; ++q) {
+        lo[q] += tl[q];
+        hi[q] += th[q];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NE; ++q) {
+      const int e = tid + q * NWK * 64;
+      epi(e >> 5, e & 31, lo[q], hi[q]);
     }
   }
   if (EPI == EPI_RESID && A.ctx_advance != nullptr && blockIdx.x == 0 && tid < M) A.ctx_advance[tid] += 1;
@@ -731,32 +775,33 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
     float* dst = part_o + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 128 + 4 * g;
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
-      *(float4*)(dst + dt * 16) = make_float4(oacc[dt][0], oacc[dt][1], oacc[dt][2], oacc[dt][3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) st_agent(dst + dt * 16 + e, oacc[dt][e]);
     if (g == 0) {
       float* ml = part_ml + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 2;
-      ml[0] = m_run;
-      ml[1] = l_run;
+      st_agent(ml, m_run);
+      st_agent(ml + 1, l_run);
     }
   }
   // the wave that arrives last at the (sequence, kv head) counter merges the chunks, in chunk order
-  __threadfence();
+  publish_stores();
   int old = 0;
-  if (lane == 0) old = atomicAdd(&counters[i * D.Hkv + c], 1);
+  if (lane == 0) old = arrive(&counters[i * D.Hkv + c]);
   old = __builtin_amdgcn_readfirstlane(old);
   if (old != nch - 1) return;
-  __threadfence();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   if (lane == 0) counters[i * D.Hkv + c] = 0;
   for (int nn = 0; nn < G; ++nn) {
     const float* ml = part_ml + ((int64_t)i * D.Hq + c * G + nn) * NCH * 2;
     const float* po = part_o + ((int64_t)i * D.Hq + c * G + nn) * NCH * 128;
     float m_tot = -INFINITY;
-    for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ml[2 * j]);
+    for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ld_agent(ml + 2 * j));
     float l = 0.f, o0 = 0.f, o1 = 0.f;
     for (int j = 0; j < nch; ++j) {
-      const float fj = exp2f(ml[2 * j] - m_tot);
-      l += ml[2 * j + 1] * fj;
-      o0 += po[(int64_t)j * 128 + lane] * fj;
-      o1 += po[(int64_t)j * 128 + 64 + lane] * fj;
+      const float fj = exp2f(ld_agent(ml + 2 * j) - m_tot);
+      l += ld_agent(ml + 2 * j + 1) * fj;
+      o0 += ld_agent(po + (int64_t)j * 128 + lane) * fj;
+      o1 += ld_agent(po + (int64_t)j * 128 + 64 + lane) * fj;
     }
     const float inv = 1.0f / l;
     const int k0 = (c * G + nn) * 128;
