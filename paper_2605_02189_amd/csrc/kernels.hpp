@@ -63,7 +63,8 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);
 
-// Split-K paged GQA decode attention.  chunk_pages = target pages per wave (<= 64), max_chunks = grid
+constexpr int kAttnWaves = 4;   // waves per attention work-group
+// Split-K paged GQA decode attention.  chunk_pages = target pages per work-group (<= 64 * kAttnWaves), max_chunks = grid
 // extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
 // (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)
 // and writes the A-tiled bf16 input of the output projection.

@@ -33,6 +33,10 @@ __device__ inline void st_agent(float* p, float v) {
 __device__ inline float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline void st_agent2(float* p, float a, float b) {      // 8-byte aligned pair
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store((unsigned long long*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline void publish_stores() {      // all earlier stores of this wave are acknowledged
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_waitcnt(0);
@@ -649,29 +653,34 @@ __device__ inline void chunk_range(int n_tok, int CP, int chunk, int& nch, int& 
   p1 = min(npages, p0 + per);
 }
 
-//   Every wave is independent: grid (chunk, ceil(Hkv / NW), sequence), block = NW waves; wave w owns
-//   kv head blockIdx.y*NW + w and walks all pages of its chunk, so there is no cross-wave merge, no
-//   LDS and no barrier.  Measured on MI355X: one-wave work-groups with about one wave per SIMD
-//   (1024 in flight) stream fastest; deeper prefetch than one page ahead does not help.
-template <int NW, int PF>
+//   grid (chunk, kv head, sequence), block = NW waves that take the chunk's pages round-robin and merge
+//   once through LDS.  With up to 64 * NW pages per block most contexts need a single chunk, and the
+//   block writes the normalised output directly; longer ones are split over blocks and merged by the
+//   block that finishes last.  There is no barrier inside the page loop.  Measured on MI355X: about
+//   one wave per SIMD (1024 in flight) streams fastest; prefetching further than one page ahead does
+//   not help.
+constexpr int kORow = 132;   // padded LDS row of the cross-wave merge
+
+template <int NW>
 __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint16_t* __restrict__ q,
-                                                    const uint16_t* __restrict__ pool,
-                                                    const int* __restrict__ table,
-                                                    const int* __restrict__ ctx,
-                                                    float* __restrict__ part_o,
-                                                    float* __restrict__ part_ml, int CP, int NCH,
-                                                    int* __restrict__ counters,
-                                                    uint16_t* __restrict__ out_t) {
-  const int chunk = blockIdx.x, i = blockIdx.z;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
-  const int c = blockIdx.y * NW + w;
-  if (c >= D.Hkv) return;
+                                                  const uint16_t* __restrict__ pool,
+                                                  const int* __restrict__ table,
+                                                  const int* __restrict__ ctx, float* __restrict__ part_o,
+                                                  float* __restrict__ part_ml, int CP, int NCH,
+                                                  int* __restrict__ counters,
+                                                  uint16_t* __restrict__ out_t) {
+  extern __shared__ float so[];                 // [NW][G][kORow], later [G][kORow] merged
+  __shared__ float sm[NW][16], sl[NW][16];
+  __shared__ int s_last;
+  const int chunk = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
   const int G = D.G;
   const int n_tok = ctx[i] + 1;
   int nch, p0, p1;
   chunk_range(n_tok, CP, chunk, nch, p0, p1);
   if (chunk >= nch) return;
 
+  // Q fragments: B operand, lane (n, g) holds Q[head n][kk*32 + 8g .. +8]
   bf16x8 qf[4];
   {
     const uint16_t* qrow = q + ((int64_t)i * D.Hq + c * G + (n < G ? n : 0)) * 128 + g * 8;
@@ -681,9 +690,11 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
       qf[kk] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  const int npw = p1 - p0;                       // <= 64 (host keeps chunk_pages <= 64)
+  // this wave's pages: p0 + w, p0 + w + NW, ...  (at most 64: the host keeps CP <= 64 * NW)
+  const int span = p1 - p0;
+  const int npw = (span > w) ? ((span - w + NW - 1) / NW) : 0;
   int my_page = 0;
-  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + lane];
+  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + w + NW * lane];
   const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
   const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
 
@@ -692,10 +703,8 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // register ring of PF + 1 page buffers: page t lives in slot t % (PF + 1); page t + PF is requested
-  // before page t is consumed, so PF pages (8 KiB each) are in flight per wave
-  constexpr int NB = PF + 1;
-  uint4 kf[NB][4], vf[NB][4];
+  // two register buffers: the next page is requested before the current one is consumed
+  uint4 kf[2][4], vf[2][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
     const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
     const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
@@ -704,21 +713,19 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
   };
+  if (npw > 0) load_page(0, kf[0], vf[0]);
+  for (int t0 = 0; t0 < npw; t0 += 2) {
 #pragma unroll
-  for (int r = 0; r < PF; ++r)
-    if (r < npw) load_page(r, kf[r], vf[r]);
-  for (int t0 = 0; t0 < npw; t0 += NB) {
-#pragma unroll
-    for (int r = 0; r < NB; ++r) {
+    for (int r = 0; r < 2; ++r) {
       const int t = t0 + r;
       if (t < npw) {
-        if (t + PF < npw) load_page(t + PF, kf[(r + PF) % NB], vf[(r + PF) % NB]);
+        if (t + 1 < npw) load_page(t + 1, kf[r ^ 1], vf[r ^ 1]);
         f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
           sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[r][kk]), qf[kk],
                                                          sacc, 0, 0, 0);
-        const int tok0 = ((p0 + t) << 4) + 4 * g;
+        const int tok0 = ((p0 + w + NW * t) << 4) + 4 * g;
         float s[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) s[e] = (tok0 + e < n_tok) ? sacc[e] * scale_log2 : -INFINITY;
@@ -757,56 +764,92 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
       }
     }
   }
-  const int KTo = D.Hq * 128 / 16;
-  if (nch == 1) {
-    // one chunk: lane (n, g) holds o[head n][dt*16 + 4g + r]; normalise and write the A-tiled bf16
-    // input of the output projection straight from the accumulators
+
+  // ---- merge the NW waves of the block through LDS -------------------------------------------------
+  if (g == 0) { sm[w][n] = m_run; sl[w][n] = l_run; }
+  __syncthreads();
+  float m_blk = sm[0][n];
+#pragma unroll
+  for (int ww = 1; ww < NW; ++ww) m_blk = fmaxf(m_blk, sm[ww][n]);
+  float l_blk = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < NW; ++ww) l_blk += sl[ww][n] * exp2f(sm[ww][n] - m_blk);
+  {
+    const float f = exp2f(m_run - m_blk);          // 0 for a wave that had no page
     if (n < G) {
-      const float inv = 1.0f / l_run;
-      const int k0 = (c * G + n) * 128 + 4 * g;
+      float* dst = so + ((int64_t)w * G + n) * kORow + 4 * g;
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt)
+      for (int dt = 0; dt < 8; ++dt) {
+        f32x4 v = oacc[dt] * f;
+        *(float4*)(dst + dt * 16) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  }
+  __syncthreads();
+  // thread e8 < G*16 owns 8 consecutive output dimensions of one query head
+  const int KTo = D.Hq * 128 / 16;
+  const int nn8 = tid >> 4, dd8 = (tid & 15) * 8;
+  const bool owner = tid < G * 16;
+  float o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float m8 = 0.f, l8 = 1.f;
+  if (owner) {
+    m8 = sm[0][nn8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out_t[a_tiled_idx(KTo, i, k0 + dt * 16 + e)] = f2bf(oacc[dt][e] * inv);
+    for (int ww = 1; ww < NW; ++ww) m8 = fmaxf(m8, sm[ww][nn8]);
+    l8 = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) l8 += sl[ww][nn8] * exp2f(sm[ww][nn8] - m8);
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {
+      const float* src = so + ((int64_t)ww * G + nn8) * kORow + dd8;
+      const float4 a = *(const float4*)src, b2 = *(const float4*)(src + 4);
+      o8[0] += a.x; o8[1] += a.y; o8[2] += a.z; o8[3] += a.w;
+      o8[4] += b2.x; o8[5] += b2.y; o8[6] += b2.z; o8[7] += b2.w;
+    }
+  }
+  if (nch == 1) {          // the block saw the whole context: normalise and write the A-tiled bf16 row
+    if (owner) {
+      const float inv = 1.0f / l8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o8[e] *= inv;
+      *(uint4*)(out_t + a_tiled_idx(KTo, i, (c * G + nn8) * 128 + dd8)) = pack8(o8);
     }
     return;
   }
-  if (n < G) {
-    float* dst = part_o + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 128 + 4 * g;
+  // several chunks: publish this block's (m, l, o); the block that arrives last at the
+  // (sequence, kv head) counter merges all chunks, in chunk order
+  if (owner) {
+    float* dst = part_o + (((int64_t)i * D.Hq + c * G + nn8) * NCH + chunk) * 128 + dd8;
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) st_agent(dst + dt * 16 + e, oacc[dt][e]);
-    if (g == 0) {
-      float* ml = part_ml + (((int64_t)i * D.Hq + c * G + n) * NCH + chunk) * 2;
-      st_agent(ml, m_run);
-      st_agent(ml + 1, l_run);
-    }
+    for (int e = 0; e < 8; e += 2) st_agent2(dst + e, o8[e], o8[e + 1]);
+    if (dd8 == 0) st_agent2(part_ml + (((int64_t)i * D.Hq + c * G + nn8) * NCH + chunk) * 2, m8, l8);
   }
-  // the wave that arrives last at the (sequence, kv head) counter merges the chunks, in chunk order
   publish_stores();
-  int old = 0;
-  if (lane == 0) old = arrive(&counters[i * D.Hkv + c]);
-  old = __builtin_amdgcn_readfirstlane(old);
-  if (old != nch - 1) return;
+  __syncthreads();
+  if (tid == 0) s_last = (arrive(&counters[i * D.Hkv + c]) == nch - 1);
+  __syncthreads();
+  if (!s_last) return;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  if (lane == 0) counters[i * D.Hkv + c] = 0;
-  for (int nn = 0; nn < G; ++nn) {
-    const float* ml = part_ml + ((int64_t)i * D.Hq + c * G + nn) * NCH * 2;
-    const float* po = part_o + ((int64_t)i * D.Hq + c * G + nn) * NCH * 128;
+  if (tid == 0) counters[i * D.Hkv + c] = 0;
+  if (owner) {
+    const float* ml = part_ml + ((int64_t)i * D.Hq + c * G + nn8) * NCH * 2;
+    const float* po = part_o + ((int64_t)i * D.Hq + c * G + nn8) * NCH * 128 + dd8;
     float m_tot = -INFINITY;
     for (int j = 0; j < nch; ++j) m_tot = fmaxf(m_tot, ld_agent(ml + 2 * j));
-    float l = 0.f, o0 = 0.f, o1 = 0.f;
+    float l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int j = 0; j < nch; ++j) {
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = ld_agent(po + (int64_t)j * 128 + e);
       const float fj = exp2f(ld_agent(ml + 2 * j) - m_tot);
       l += ld_agent(ml + 2 * j + 1) * fj;
-      o0 += ld_agent(po + (int64_t)j * 128 + lane) * fj;
-      o1 += ld_agent(po + (int64_t)j * 128 + 64 + lane) * fj;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += v[e] * fj;
     }
     const float inv = 1.0f / l;
-    const int k0 = (c * G + nn) * 128;
-    out_t[a_tiled_idx(KTo, i, k0 + lane)] = f2bf(o0 * inv);
-    out_t[a_tiled_idx(KTo, i, k0 + 64 + lane)] = f2bf(o1 * inv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= inv;
+    *(uint4*)(out_t + a_tiled_idx(KTo, i, (c * G + nn8) * 128 + dd8)) = pack8(o);
   }
 }
 
@@ -909,7 +952,9 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
                int max_chunks, int* counters, uint16_t* out_t) {
-  hipLaunchKernelGGL((k_attn<1, 1>), dim3(max_chunks, D.Hkv, b), dim3(64), 0, s, D, layer, q, pool, table,
+  constexpr int NW = kAttnWaves;
+  const size_t lds = (size_t)NW * D.G * kORow * sizeof(float);
+  hipLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), lds, s, D, layer, q, pool, table,
                      ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t);
 }
 

@@ -1063,11 +1063,13 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   } else {
     const int mpad = ((b + 31) / 32) * 32;
     const int nq = D.Hq * D.d;
-    // attention split: about one wave per SIMD (1024 on the chip), 8..64 pages per wave
+    // attention split: about one wave per SIMD (1024 on the chip); a work-group of kAttnWaves waves
+    // covers up to 64 pages per wave, so most contexts are a single chunk
     const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
-    const int nch_target = std::max(1, (1024 + b * D.Hkv / 2) / (b * D.Hkv));
+    const int per_chunk_waves = b * D.Hkv * mfma::kAttnWaves;
+    const int nch_target = std::max(1, (1024 + per_chunk_waves / 2) / per_chunk_waves);
     int CP = (npages_max + nch_target - 1) / nch_target;
-    CP = std::max(8, std::min(64, CP));
+    CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
     const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
     const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
     auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
