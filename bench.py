@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the compute-only / transfer-only legs")
+    ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
     ap.add_argument("--cpu-seqs", type=int, default=8)
     ap.add_argument("--cpu-steps", type=int, default=4)
     args = ap.parse_args()
@@ -104,12 +105,13 @@ def main():
     n = shape.n_microbatches
     K = args.steps if args.steps is not None else shape.decode_steps
     W = args.warmup if args.warmup is not None else 2 * n
-    legs_steps = 0 if args.no_legs else (W + min(K, 16 * n))
-    total_steps = 2 * (W + K) + legs_steps + 4 * n
+    legs_steps = 0 if args.no_legs else (W + 3 * min(K, 16 * n))
+    total_steps = (W + K) + legs_steps + 4 * n
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
-    run = StageRunner(shape, syn, sigma=args.sigma, steps=total_steps, gpu_pool_all_resident=not args.no_legs)
+    run = StageRunner(shape, syn, sigma=args.sigma, steps=total_steps, gpu_pool_all_resident=not args.no_legs,
+                      flags=pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
     st = run.stage
     run.load()
     hin = [run.hidden_tensor(mb, mb) for mb in range(n)]
@@ -150,20 +152,31 @@ def main():
             i = run.t % n
             run.step(hin[i], hout[i], stream, transfers=False)
         sync()
-        st.set_flags(pm.FLAG_TIME_KERNELS, 0)
-        st.reset_stats()
         Kc = min(K, 16 * n)
+        # (a) only the attention kernel bracketed by HIP events on the compute stream: the roofline figure
+        st.set_flags(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY, 0)
+        st.reset_stats()
         bytes_attn = 0
-        t0 = time.perf_counter()
         for _ in range(Kc):
             i = run.t % n
             bytes_attn += shape.n_layers * attn_bytes(shape, st.get_ctx_lens(i))
             run.step(hin[i], hout[i], stream, transfers=False)
         sync()
+        s0 = st.get_stats()
+        attn_ms = s0["kernel_ms"]["attn"] / max(s0["kernel_launches"]["attn"], 1)
+        attn_launches = int(s0["kernel_launches"]["attn"])
+        # (b) every kernel class bracketed: the per-class breakdown (the brackets themselves cost time)
+        st.set_flags(pm.FLAG_TIME_KERNELS, pm.FLAG_TIME_ATTN_ONLY)
+        st.reset_stats()
+        t0 = time.perf_counter()
+        for _ in range(Kc):
+            i = run.t % n
+            run.step(hin[i], hout[i], stream, transfers=False)
+        sync()
         t_timed = time.perf_counter() - t0
         s1 = st.get_stats()
         st.set_flags(0, pm.FLAG_TIME_KERNELS)
-        # same steps without the event brackets: the compute-only step time
+        # (c) the same steps without any bracket: the compute-only step time
         t0 = time.perf_counter()
         for _ in range(Kc):
             i = run.t % n
@@ -171,13 +184,12 @@ def main():
         sync()
         t_c = (time.perf_counter() - t0) / Kc
         kms, kl = s1["kernel_ms"], s1["kernel_launches"]
-        attn_ms = kms["attn"] / max(kl["attn"], 1)
-        achieved = bytes_attn / max(kl["attn"], 1) / (attn_ms * 1e-3) / 1e9
+        achieved = bytes_attn / max(attn_launches, 1) / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                    "avg_launch_us": round(attn_ms * 1e3, 2), "launches": int(kl["attn"]),
-                    "bytes_per_launch": int(bytes_attn / max(kl["attn"], 1))}
+                    "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_launches,
+                    "bytes_per_launch": int(bytes_attn / max(attn_launches, 1))}
         hbm_bytes_step = shape.weight_bytes + bytes_attn / Kc
         legs["compute_only"] = {
             "ms_per_step": round(t_c * 1e3, 4), "tokens_per_s": round(run.b / t_c, 1),
@@ -235,7 +247,7 @@ def main():
         "metric": "stage decode tokens/sec with host-offloaded KV", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
-        "data": "synthetic",
+        "data": "synthetic" if not args.no_writeback else "synthetic (DIAGNOSTIC RUN WITHOUT KV WRITE-BACK: not a result)",
         "config": {"workload": f"{shape.name}: {shape.n_layers} layers, hidden {shape.hidden}, "
                                f"{shape.n_q_heads}Q/{shape.n_kv_heads}KV heads x {shape.head_dim}, ffn {shape.ffn}, "
                                f"{n} micro-batches x {shape.seqs_per_mb} seqs, prompts {shape.ctx_lo}-{shape.ctx_hi} tokens",

@@ -72,8 +72,10 @@ enum {
                                        decode_step (see pipemax_get_layer_outputs)               */
   PIPEMAX_FLAG_TIME_KERNELS   = 4,  /* bracket every kernel class and every transfer with HIP
                                        events and accumulate their durations in the stats        */
-  PIPEMAX_FLAG_NO_WRITEBACK   = 8   /* do not write new K,V through to the host replica
+  PIPEMAX_FLAG_NO_WRITEBACK   = 8,  /* do not write new K,V through to the host replica
                                        (compute-only timing runs; evict then loses new tokens)   */
+  PIPEMAX_FLAG_TIME_ATTN_ONLY = 16  /* with TIME_KERNELS: bracket only the attention kernel, so that
+                                       the other launches' event records do not perturb it       */
 };
 
 typedef struct {
@@ -88,6 +90,12 @@ typedef struct {
   uint64_t host_kv_bytes;    /* size of the pinned host page pool                            */
   int32_t  device;           /* HIP device ordinal                                           */
   uint32_t flags;            /* PIPEMAX_FLAG_*                                               */
+  int32_t  host_reserve_tokens;  /* mb_define reserves host pages for min(max_ctx, len + this) tokens
+                                    per sequence, consecutively, so that a sequence that grows stays
+                                    one contiguous run of host pages (one copy per prefetch); 0 = none */
+  int32_t  wb_layers_per_copy;   /* layers per write-back copy: 1 = one device->host copy per layer
+                                    right after its QKV projection (the timeline of the paper's
+                                    Sec. 3.4.2); 0 = all layers of a step in one copy             */
 } pipemax_config_t;
 
 /* kernel classes of the per-class timers (PIPEMAX_FLAG_TIME_KERNELS) */
@@ -142,7 +150,8 @@ int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* ho
 
 /* Defines micro-batch `mb` (0 <= mb < n_microbatches, not yet defined) with n_seqs sequences
  * whose prompts have ctx_lens[i] cached tokens (host pointer; 0 <= len <= max_ctx).
- * Allocates ceil(len/16) host pages per sequence, consecutively, lowest index first.
+ * Allocates ceil(len/16) host pages per sequence (plus the reservation of host_reserve_tokens),
+ * consecutively, lowest index first.
  * All sequences start HOST-resident.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED.                */
 int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ctx_lens);
 
@@ -201,7 +210,7 @@ int pipemax_sync(pipemax_stage_t* st);
 
 int pipemax_get_stats(pipemax_stage_t* st, pipemax_stats_t* out);   /* synchronises if timing */
 int pipemax_reset_stats(pipemax_stage_t* st);
-/* Sets and clears run-time flags; only PIPEMAX_FLAG_TIME_KERNELS and PIPEMAX_FLAG_NO_WRITEBACK can be
+/* Sets and clears run-time flags; only the PIPEMAX_FLAG_TIME_* flags and PIPEMAX_FLAG_NO_WRITEBACK can be
  * changed after creation (ERR_ARG otherwise).  Synchronises the stage first.                */
 int pipemax_set_flags(pipemax_stage_t* st, uint32_t set, uint32_t clear);
 

@@ -58,12 +58,14 @@ class ResidencyModel:
     """
 
     def __init__(self, n_microbatches: int, page_tokens: int, max_ctx: int,
-                 gpu_pages: int, host_pages: int):
+                 gpu_pages: int, host_pages: int, host_reserve_tokens: int = 0):
         self.n = n_microbatches
         self.pt = page_tokens
         self.max_ctx = max_ctx
         self.gpu_free = gpu_pages
         self.host_free = host_pages
+        self.reserve = host_reserve_tokens
+        self.host_held = {}   # (mb, seq) -> host pages held (in use + reserved)
         self.len = {}      # (mb, seq) -> tokens
         self.state = {}    # (mb, seq) -> HOST | INFLIGHT | GPU
         self.nseq = {}     # mb -> number of sequences
@@ -74,14 +76,15 @@ class ResidencyModel:
             raise BookkeepingError("ARG")
         if any(l < 0 or l > self.max_ctx for l in ctx_lens):
             raise BookkeepingError("ARG")
-        need = sum(pages_for(l, self.pt) for l in ctx_lens)
-        if need > self.host_free:
+        held = [pages_for(min(self.max_ctx, l + self.reserve), self.pt) for l in ctx_lens]
+        if sum(held) > self.host_free:
             raise BookkeepingError("POOL_EXHAUSTED")
-        self.host_free -= need
+        self.host_free -= sum(held)
         self.nseq[mb] = len(ctx_lens)
         for s, l in enumerate(ctx_lens):
             self.len[(mb, s)] = int(l)
             self.state[(mb, s)] = HOST
+            self.host_held[(mb, s)] = held[s]
 
     def _seqs(self, mb, seq_ids):
         if mb not in self.nseq:
@@ -108,11 +111,15 @@ class ResidencyModel:
             raise BookkeepingError("NOT_RESIDENT")
         if any(self.len[(mb, s)] + 1 > self.max_ctx for s in seqs):
             raise BookkeepingError("STATE")
-        grow = sum(1 for s in seqs if self.len[(mb, s)] % self.pt == 0)
-        if grow > self.gpu_free or grow > self.host_free:
+        growing = [s for s in seqs if self.len[(mb, s)] % self.pt == 0]
+        # a growing sequence first uses a page it holds in reserve, then the pool
+        from_pool = [s for s in growing if self.host_held[(mb, s)] <= pages_for(self.len[(mb, s)], self.pt)]
+        if len(growing) > self.gpu_free or len(from_pool) > self.host_free:
             raise BookkeepingError("POOL_EXHAUSTED")
-        self.gpu_free -= grow
-        self.host_free -= grow
+        self.gpu_free -= len(growing)
+        self.host_free -= len(from_pool)
+        for s in from_pool:
+            self.host_held[(mb, s)] += 1
         for s in seqs:
             self.len[(mb, s)] += 1
             self.state[(mb, s)] = GPU

@@ -40,6 +40,7 @@ ERR_NOT_RESIDENT, ERR_POOL_EXHAUSTED, ERR_HIP, ERR_STATE = -4, -5, -6, -7
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GU, W_D, G_ATTN, G_FFN = range(6)
 FLAG_FORCE_GENERIC, FLAG_CAPTURE_LAYERS, FLAG_TIME_KERNELS, FLAG_NO_WRITEBACK = 1, 2, 4, 8
+FLAG_TIME_ATTN_ONLY = 16
 K_CLASSES = ["norm", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gu", "swiglu",
              "gemm_d", "misc"]
 N_KCLASS = len(K_CLASSES)
@@ -64,7 +65,8 @@ class Config(C.Structure):
                 ("page_tokens", C.c_int32), ("n_microbatches", C.c_int32),
                 ("max_seqs_per_mb", C.c_int32), ("max_ctx", C.c_int32),
                 ("gpu_kv_bytes", C.c_uint64), ("host_kv_bytes", C.c_uint64),
-                ("device", C.c_int32), ("flags", C.c_uint32)]
+                ("device", C.c_int32), ("flags", C.c_uint32),
+                ("host_reserve_tokens", C.c_int32), ("wb_layers_per_copy", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -158,10 +160,11 @@ class Stage:
 
     def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps,
                  dtype, n_microbatches, max_seqs_per_mb, max_ctx, gpu_kv_bytes, host_kv_bytes,
-                 device=0, flags=0, page_tokens=16):
+                 device=0, flags=0, page_tokens=16, host_reserve_tokens=0, wb_layers_per_copy=0):
         self.cfg = Config(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rope_base, rms_eps,
                           dtype, page_tokens, n_microbatches, max_seqs_per_mb, max_ctx,
-                          int(gpu_kv_bytes), int(host_kv_bytes), device, flags)
+                          int(gpu_kv_bytes), int(host_kv_bytes), device, flags, host_reserve_tokens,
+                          wb_layers_per_copy)
         self._h = _vp()
         _check(_lib.pipemax_stage_create(C.byref(self.cfg), C.byref(self._h)))
         self.np_dtype = np.float32 if dtype == F32 else np.uint16

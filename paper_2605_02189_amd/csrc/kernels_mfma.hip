@@ -644,21 +644,15 @@ __global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const flo
 //   The S^T accumulator layout (lane: column = head, 4 consecutive tokens) is exactly the B-operand
 //   layout of the second product, so P never leaves its registers.
 // =================================================================================================
+// chunk j of a sequence covers pages [j*CP, min(npages, (j+1)*CP)): the boundaries do not depend on
+// the sequence's length, so the block-table entries can be requested before the length has arrived
 __device__ inline void chunk_range(int n_tok, int CP, int chunk, int& nch, int& p0, int& p1) {
   const int npages = (n_tok + 15) >> 4;
-  const int nch0 = (npages + CP - 1) / CP;
-  const int per = (npages + nch0 - 1) / nch0;
-  nch = (npages + per - 1) / per;
-  p0 = chunk * per;
-  p1 = min(npages, p0 + per);
+  nch = (npages + CP - 1) / CP;
+  p0 = chunk * CP;
+  p1 = min(npages, p0 + CP);
 }
 
-//   grid (chunk, kv head, sequence), block = NW waves that take the chunk's pages round-robin and merge
-//   once through LDS.  With up to 64 * NW pages per block most contexts need a single chunk, and the
-//   block writes the normalised output directly; longer ones are split over blocks and merged by the
-//   block that finishes last.  There is no barrier inside the page loop.  Measured on MI355X: about
-//   one wave per SIMD (1024 in flight) streams fastest; prefetching further than one page ahead does
-//   not help.
 constexpr int kORow = 132;   // padded LDS row of the cross-wave merge
 
 template <int NW>
@@ -675,6 +669,12 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
   const int chunk = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
   const int G = D.G;
+  // issue the three independent first loads together: length, this wave's page ids, Q
+  int my_page = 0;
+  {
+    const int pidx = chunk * CP + w + NW * lane;          // this wave's pages: p0 + w, p0 + w + NW, ...
+    if (NW * lane + w < CP && pidx < D.max_pages) my_page = table[(int64_t)i * D.max_pages + pidx];
+  }
   const int n_tok = ctx[i] + 1;
   int nch, p0, p1;
   chunk_range(n_tok, CP, chunk, nch, p0, p1);
@@ -690,11 +690,9 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
       qf[kk] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  // this wave's pages: p0 + w, p0 + w + NW, ...  (at most 64: the host keeps CP <= 64 * NW)
+  // at most 64 pages per wave: the host keeps CP <= 64 * NW
   const int span = p1 - p0;
   const int npw = (span > w) ? ((span - w + NW - 1) / NW) : 0;
-  int my_page = 0;
-  if (lane < npw) my_page = table[(int64_t)i * D.max_pages + p0 + w + NW * lane];
   const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
   const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
 

@@ -53,6 +53,7 @@ struct SeqState {
   int len = 0;
   int state = ST_HOST;
   std::vector<int32_t> gpu, host;
+  std::vector<int32_t> host_reserved;   // pages right after `host`, taken first when the sequence grows
 };
 
 struct MicroBatch {
@@ -71,7 +72,7 @@ struct MicroBatch {
 
 struct WbJob {
   hipEvent_t ev = nullptr;
-  int mb = 0, layer = 0, slot = 0, b = 0;
+  int mb = 0, layer = 0, n_layers = 1, slot = 0, b = 0;
   std::shared_ptr<std::vector<std::pair<int32_t, int>>> where;   // per sequence: host page, slot
   bool stop = false;
 };
@@ -166,17 +167,22 @@ struct pipemax_stage {
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
   }
+  bool t_open = false;
   void tbegin(int cls, hipStream_t s) {
+    t_open = false;
     if (!timing()) return;
+    if ((cfg.flags & PIPEMAX_FLAG_TIME_ATTN_ONLY) && cls != PIPEMAX_K_ATTN) return;
     if (timed.size() >= 4096) resolve_timers(true);
     Timed t{cls, get_event(), get_event()};
     if (!t.a || !t.b) return;
     (void)hipEventRecord(t.a, s);
     timed.push_back(t);
+    t_open = true;
   }
   void tend(hipStream_t s) {
-    if (!timing() || timed.empty()) return;
+    if (!t_open) return;
     (void)hipEventRecord(timed.back().b, s);
+    t_open = false;
   }
   // only_ready: keep the pairs whose second event has not completed yet
   void resolve_timers(bool only_ready = false) {
@@ -275,23 +281,25 @@ void worker_main(pipemax_stage* st) {
     (void)hipEventSynchronize(job.ev);
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
     const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
-    const char* src = (const char*)st->h_stage[job.slot] + (size_t)job.layer * layer_elems * st->esz;
-    for (int i = 0; i < job.b; ++i) {
-      const auto& wh = (*job.where)[i];
-      char* page = st->host_page_ptr(wh.first);
-      const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
-      const char* vr = src + ((size_t)i * 2 + 1) * row * st->esz;
-      if (st->esz == 4)
-        scatter_token<float>(st, (float*)page, job.layer, wh.second, (const float*)kr, (const float*)vr);
-      else
-        scatter_token<uint16_t>(st, (uint16_t*)page, job.layer, wh.second, (const uint16_t*)kr,
-                                (const uint16_t*)vr);
+    for (int layer = job.layer; layer < job.layer + job.n_layers; ++layer) {
+      const char* src = (const char*)st->h_stage[job.slot] + (size_t)layer * layer_elems * st->esz;
+      for (int i = 0; i < job.b; ++i) {
+        const auto& wh = (*job.where)[i];
+        char* page = st->host_page_ptr(wh.first);
+        const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
+        const char* vr = src + ((size_t)i * 2 + 1) * row * st->esz;
+        if (st->esz == 4)
+          scatter_token<float>(st, (float*)page, layer, wh.second, (const float*)kr, (const float*)vr);
+        else
+          scatter_token<uint16_t>(st, (uint16_t*)page, layer, wh.second, (const uint16_t*)kr,
+                                  (const uint16_t*)vr);
+      }
     }
     {
       std::lock_guard<std::mutex> lk(st->mu);
       st->mbs[job.mb].wb_pending -= 1;
       st->slot_pending[job.slot] -= 1;
-      st->st.relayout_jobs += 1;
+      st->st.relayout_jobs += job.n_layers;
     }
     st->cv_done.notify_all();
   }
@@ -452,6 +460,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
       c.ffn < 1 || c.n_microbatches < 1 || c.max_seqs_per_mb < 1 || c.max_ctx < 1)
     PMX_FAIL(PIPEMAX_ERR_ARG, "non-positive shape field");
   if (c.dtype != PIPEMAX_F32 && c.dtype != PIPEMAX_BF16) PMX_FAIL(PIPEMAX_ERR_ARG, "unknown dtype %d", c.dtype);
+  if (c.host_reserve_tokens < 0 || c.wb_layers_per_copy < 0) PMX_FAIL(PIPEMAX_ERR_ARG, "negative reserve / write-back group");
   if (c.page_tokens != kPageTokens) PMX_FAIL(PIPEMAX_ERR_ARG, "page_tokens must be %d", kPageTokens);
   if (c.n_q_heads % c.n_kv_heads) PMX_FAIL(PIPEMAX_ERR_ARG, "n_q_heads must be a multiple of n_kv_heads");
   if (c.head_dim % 32 || c.head_dim > 512) PMX_FAIL(PIPEMAX_ERR_ARG, "head_dim must be a multiple of 32, at most 512");
@@ -725,7 +734,8 @@ int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ct
   for (int i = 0; i < n_seqs; ++i) {
     if (ctx_lens[i] < 0 || ctx_lens[i] > st->cfg.max_ctx)
       PMX_FAIL(PIPEMAX_ERR_ARG, "context length %d outside [0, %d]", ctx_lens[i], st->cfg.max_ctx);
-    need += (ctx_lens[i] + kPageTokens - 1) / kPageTokens;
+    const int res_len = std::min(st->cfg.max_ctx, ctx_lens[i] + st->cfg.host_reserve_tokens);
+    need += (res_len + kPageTokens - 1) / kPageTokens;
   }
   if (need > st->host_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "host pool has %d free pages, %lld needed", st->host_pages->free_count(),
@@ -737,8 +747,12 @@ int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ct
     S.len = ctx_lens[i];
     S.state = ST_HOST;
     const int np = (S.len + kPageTokens - 1) / kPageTokens;
+    const int res_len = std::min(st->cfg.max_ctx, S.len + st->cfg.host_reserve_tokens);
+    const int np_res = (res_len + kPageTokens - 1) / kPageTokens;
+    S.host.resize(np_res);
+    st->host_pages->alloc(np_res, S.host.data());
+    S.host_reserved.assign(S.host.begin() + np, S.host.end());
     S.host.resize(np);
-    st->host_pages->alloc(np, S.host.data());
   }
   PMX_HIP(hipMemcpy(M.d_ctx, ctx_lens, (size_t)n_seqs * sizeof(int), hipMemcpyHostToDevice));
   M.b = n_seqs;
@@ -911,7 +925,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   MicroBatch& M = st->mbs[mb];
   const Dims& D = st->D;
   const int b = M.b, nl = st->cfg.n_layers;
-  int grow = 0, max_len = 0;
+  int grow = 0, grow_host = 0, max_len = 0;
   for (int i = 0; i < b; ++i)
     if (M.seq[i].state == ST_HOST)
       PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", i, mb);
@@ -919,10 +933,13 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     const SeqState& S = M.seq[i];
     if (S.len + 1 > st->cfg.max_ctx)
       PMX_FAIL(PIPEMAX_ERR_STATE, "sequence %d of micro-batch %d is at max_ctx %d", i, mb, st->cfg.max_ctx);
-    if (S.len % kPageTokens == 0) ++grow;
+    if (S.len % kPageTokens == 0) {
+      ++grow;
+      if (S.host_reserved.empty()) ++grow_host;
+    }
     max_len = std::max(max_len, S.len);
   }
-  if (grow > st->gpu_pages->free_count() || grow > st->host_pages->free_count())
+  if (grow > st->gpu_pages->free_count() || grow_host > st->host_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", grow,
              st->gpu_pages->free_count(), st->host_pages->free_count());
   PMX_HIP(hipSetDevice(st->dev));
@@ -937,7 +954,12 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     if (S.len % kPageTokens == 0) {
       int32_t gp, hp;
       st->gpu_pages->alloc(1, &gp);
-      st->host_pages->alloc(1, &hp);
+      if (!S.host_reserved.empty()) {
+        hp = S.host_reserved.front();
+        S.host_reserved.erase(S.host_reserved.begin());
+      } else {
+        st->host_pages->alloc(1, &hp);
+      }
       S.gpu.push_back(gp);
       S.host.push_back(hp);
       M.table_dirty = true;
@@ -985,19 +1007,25 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     st->tend(cs);
   }
 
+  // write-back: layers are copied in groups of wb_layers_per_copy (0 = the whole step in one copy)
+  const int wb_group = (st->cfg.wb_layers_per_copy > 0) ? std::min(st->cfg.wb_layers_per_copy, nl) : nl;
   auto after_append = [&](int l) -> int {
     if (!writeback) return PIPEMAX_OK;
+    if ((l + 1) % wb_group != 0 && l != nl - 1) return PIPEMAX_OK;
+    const int l0 = (l / wb_group) * wb_group, nlay = l - l0 + 1;
     PMX_HIP(hipEventRecord(st->ev_ready[slot][l], cs));
     PMX_HIP(hipStreamWaitEvent(st->s_d2h, st->ev_ready[slot][l], 0));
     st->tbegin(TC_D2H, st->s_d2h);
-    PMX_HIP(hipMemcpyAsync((char*)st->h_stage[slot] + (size_t)l * layer_elems * st->esz,
-                           (char*)st->d_stage[slot] + (size_t)l * layer_elems * st->esz, copy_bytes,
+    // one layer's rows are contiguous for b sequences; a group spans whole layer slots
+    const size_t group_bytes = (size_t)(nlay - 1) * layer_elems * st->esz + copy_bytes;
+    PMX_HIP(hipMemcpyAsync((char*)st->h_stage[slot] + (size_t)l0 * layer_elems * st->esz,
+                           (char*)st->d_stage[slot] + (size_t)l0 * layer_elems * st->esz, group_bytes,
                            hipMemcpyDeviceToHost, st->s_d2h));
     st->tend(st->s_d2h);
     PMX_HIP(hipEventRecord(st->ev_copied[slot][l], st->s_d2h));
     WbJob job;
     job.ev = st->ev_copied[slot][l];
-    job.mb = mb; job.layer = l; job.slot = slot; job.b = b; job.where = where;
+    job.mb = mb; job.layer = l0; job.n_layers = nlay; job.slot = slot; job.b = b; job.where = where;
     {
       std::lock_guard<std::mutex> lk(st->mu);
       M.wb_pending += 1;
@@ -1005,7 +1033,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
       st->jobs.push_back(job);
     }
     st->cv_job.notify_one();
-    st->st.d2h_bytes += copy_bytes;
+    st->st.d2h_bytes += group_bytes;
     st->st.d2h_copies += 1;
     return PIPEMAX_OK;
   };
@@ -1244,7 +1272,7 @@ int pipemax_reset_stats(pipemax_stage_t* st) {
 
 int pipemax_set_flags(pipemax_stage_t* st, uint32_t set, uint32_t clear) {
   if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
-  const uint32_t allowed = PIPEMAX_FLAG_TIME_KERNELS | PIPEMAX_FLAG_NO_WRITEBACK;
+  const uint32_t allowed = PIPEMAX_FLAG_TIME_KERNELS | PIPEMAX_FLAG_NO_WRITEBACK | PIPEMAX_FLAG_TIME_ATTN_ONLY;
   if ((set | clear) & ~allowed) PMX_FAIL(PIPEMAX_ERR_ARG, "only the timing and no-write-back flags can change");
   int rc = pipemax_sync(st);
   if (rc) return rc;

@@ -25,7 +25,8 @@ class StageRunner:
 
     def __init__(self, shape: StageShape, syn: SynthInputs, *, sigma: float = 1.0, steps: int | None = None,
                  flags: int = 0, device: int = 0, n_microbatches: int | None = None,
-                 ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False):
+                 ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False,
+                 wb_layers_per_copy: int = 0, reserve: bool = True):
         self.shape, self.syn = shape, syn
         self.n = n_microbatches or shape.n_microbatches
         self.b = shape.seqs_per_mb
@@ -55,7 +56,8 @@ class StageRunner:
             dtype=pm.F32 if shape.dtype == "fp32" else pm.BF16, n_microbatches=self.n,
             max_seqs_per_mb=max(self.b_of.values()), max_ctx=max_ctx,
             gpu_kv_bytes=gpu_pages * shape.page_bytes, host_kv_bytes=(host_pages + 8) * shape.page_bytes,
-            device=device, flags=flags)
+            device=device, flags=flags, host_reserve_tokens=(steps_per_mb + 1) if reserve else 0,
+            wb_layers_per_copy=wb_layers_per_copy)
         self.torch_dtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
         self.t = 0
 

@@ -114,3 +114,17 @@ def test_residency_model_errors():
         m.decode_step(1)                # already at max_ctx
     with pytest.raises(bk.BookkeepingError, match="ARG"):
         m.mb_define(1, [1])
+
+
+def test_residency_model_host_reservation():
+    m = bk.ResidencyModel(1, 16, max_ctx=64, gpu_pages=10, host_pages=10, host_reserve_tokens=20)
+    m.mb_define(0, [16, 60])            # holds pages for 36 -> 3 and min(64, 80) -> 4
+    assert m.host_free == 3
+    m.prefetch(0)                       # 1 + 4 GPU pages
+    assert m.gpu_free == 5
+    for _ in range(4):
+        m.decode_step(0)                # 16 -> 17 takes a GPU page and a reserved host page
+    assert m.gpu_free == 4 and m.host_free == 3
+    assert m.ctx_lens(0) == [20, 64]
+    with pytest.raises(bk.BookkeepingError, match="STATE"):
+        m.decode_step(0)

@@ -21,8 +21,8 @@ def test_library_exports_every_symbol_of_the_header(lib):
 
 def test_struct_sizes_match_the_header(lib):
     import ctypes as C
-    # pipemax_config_t: 6 int32, 2 float, 5 int32, (pad) 2 uint64, int32, uint32
-    assert C.sizeof(lib.Config) == 80
+    # pipemax_config_t: 6 int32, 2 float, 5 int32, (pad) 2 uint64, int32, uint32, 2 int32
+    assert C.sizeof(lib.Config) == 88
     assert lib.Config.gpu_kv_bytes.offset == 56
     assert C.sizeof(lib.Stats) == 8 * 8 + 4 * 8 + lib.N_KCLASS * 16 + 5 * 4 + 4 + 8
 

@@ -95,13 +95,14 @@ def test_config1_tiny_fp32_full_schedule():
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import CONFIGS
     shape = CONFIGS["C1"]
-    runner, syn = _runner(shape, seed=1, flags=pm.FLAG_CAPTURE_LAYERS)
+    runner, syn = _runner(shape, seed=1, flags=pm.FLAG_CAPTURE_LAYERS, wb_layers_per_copy=1, reserve=False)
     runner.load()
     assert runner.stage.get_stats()["engine"] == 0
     orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-5, tol_delta=2e-4)
     check_tables(runner)
     _check_replica(runner, syn, shape, orc, tol_new=1e-5)
     st = runner.stage.get_stats()
+    assert st["host_pages_free"] == st["host_pages_total"] - 4 * 8 * 9     # no reservation: 9 pages per sequence
     assert st["steps"] == 16 and st["tokens"] == 16 * 8
     assert st["d2h_copies"] == 16 * shape.n_layers and st["relayout_jobs"] == 16 * shape.n_layers
     # every micro-batch was streamed in once per cycle (4 cycles), whole prompts + grown tokens
