@@ -41,6 +41,18 @@ def attn_bytes(shape, lens_before):
     return sum(2 * shape.n_kv_heads * shape.head_dim * shape.elem_bytes * (int(L) + 1) for L in lens_before)
 
 
+def measured_traffic(config_name):
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload."""
+    path = os.path.join(ROOT, "profiles", f"attn_{config_name}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(shape, syn, ctx0, k_seqs, n_steps):
     """The oracle as it stands on a sample of micro-batch 0: k sequences, all layers, full context."""
     import numpy as np
@@ -86,6 +98,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the compute-only / transfer-only legs")
     ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also launch the library's plain copy kernel (256 MiB, 3 times): calibration for --pmc runs")
     ap.add_argument("--cpu-seqs", type=int, default=8)
     ap.add_argument("--cpu-steps", type=int, default=4)
     args = ap.parse_args()
@@ -187,7 +201,7 @@ def main():
         achieved = bytes_attn / max(attn_launches, 1) / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(shape.name),
                     "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_launches,
                     "bytes_per_launch": int(bytes_attn / max(attn_launches, 1))}
         hbm_bytes_step = shape.weight_bytes + bytes_attn / Kc
@@ -255,6 +269,14 @@ def main():
                    "inactive_kv": "pinned host memory", "page_tokens": 16},
         "roofline": roofline, "legs": legs,
     }
+    if args.probe_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            pm.probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), stream.cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         st.destroy()
         del run
