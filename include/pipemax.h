@@ -226,6 +226,16 @@ int pipemax_get_block_table(pipemax_stage_t* st, int mb, int seq, int32_t* gpu_p
  * out = host pointer to [n_layers][b][hidden] float.  Synchronises.                        */
 int pipemax_get_layer_outputs(pipemax_stage_t* st, float* out, size_t bytes);
 
+/* ---- test hooks (host-forced conditions; every kernel still runs to completion) --------------- */
+
+/* Fills every currently free GPU page with the 16-bit pattern (e.g. 0x7FC0, a bf16 NaN), after
+ * synchronising the stage: any read of a page that no live sequence owns then poisons the output. */
+int pipemax_debug_fill_free_gpu_pages(pipemax_stage_t* st, uint16_t pattern);
+/* Delays, in microseconds, injected from now on before every prefetch batch (on the host->device
+ * stream), before every write-back copy (on the device->host stream) and before every re-layout job
+ * (in the worker thread).  Results must not depend on them: they only move work in time.         */
+int pipemax_debug_set_delays(pipemax_stage_t* st, int h2d_us, int d2h_us, int worker_us);
+
 const char* pipemax_last_error(void);
 const char* pipemax_version(void);
 

@@ -52,7 +52,8 @@ SYMBOLS = [
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
     "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
-    "pipemax_get_layer_outputs", "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
+    "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
+    "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
     "pipemax_plan_copy_runs", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
     "pipemax_pool_free", "pipemax_pool_free_count",
 ]
@@ -109,6 +110,8 @@ _sig = {
     "pipemax_get_residency": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_block_table": (C.c_int, [_vp, C.c_int, C.c_int, _i32p, _i32p, C.POINTER(C.c_int)]),
     "pipemax_get_layer_outputs": (C.c_int, [_vp, _vp, C.c_size_t]),
+    "pipemax_debug_fill_free_gpu_pages": (C.c_int, [_vp, C.c_uint16]),
+    "pipemax_debug_set_delays": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int]),
     "pipemax_last_error": (C.c_char_p, []),
     "pipemax_version": (C.c_char_p, []),
     "pipemax_page_elem_offset": (C.c_int64, [C.c_int] * 8),
@@ -258,6 +261,12 @@ class Stage:
         _check(_lib.pipemax_get_block_table(self._h, mb, seq, g.ctypes.data_as(_i32p),
                                             h.ctypes.data_as(_i32p), C.byref(m)))
         return g[: m.value], h[: m.value]
+
+    def debug_fill_free_gpu_pages(self, pattern: int):
+        _check(_lib.pipemax_debug_fill_free_gpu_pages(self._h, pattern))
+
+    def debug_set_delays(self, h2d_us: int = 0, d2h_us: int = 0, worker_us: int = 0):
+        _check(_lib.pipemax_debug_set_delays(self._h, h2d_us, d2h_us, worker_us))
 
     def get_layer_outputs(self, b: int) -> np.ndarray:
         out = np.empty((self.cfg.n_layers, b, self.cfg.hidden), dtype=np.float32)

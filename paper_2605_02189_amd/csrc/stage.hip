@@ -150,6 +150,8 @@ struct pipemax_stage {
   std::condition_variable cv_job, cv_done;
   std::deque<WbJob> jobs;
   bool worker_started = false;
+  // test hooks
+  std::atomic<int> dly_h2d{0}, dly_d2h{0}, dly_worker{0};
   // stats / timing
   pipemax_stats_t st{};
   std::vector<Timed> timed;
@@ -279,6 +281,7 @@ void worker_main(pipemax_stage* st) {
     }
     if (job.stop) return;
     (void)hipEventSynchronize(job.ev);
+    if (int us = st->dly_worker.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
     const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
     for (int layer = job.layer; layer < job.layer + job.n_layers; ++layer) {
@@ -303,6 +306,10 @@ void worker_main(pipemax_stage* st) {
     }
     st->cv_done.notify_all();
   }
+}
+
+void host_sleep_cb(void* arg) {
+  std::this_thread::sleep_for(std::chrono::microseconds((intptr_t)arg));
 }
 
 template <typename T>
@@ -869,6 +876,7 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
   M.table_dirty = true;
   std::vector<CopyRun> runs;
   plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, runs);
+  if (int us = st->dly_h2d.load()) PMX_HIP(hipLaunchHostFunc(st->s_h2d, host_sleep_cb, (void*)(intptr_t)us));
   st->tbegin(TC_H2D, st->s_h2d);
   for (const CopyRun& r : runs) {
     PMX_HIP(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
@@ -1015,6 +1023,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     const int l0 = (l / wb_group) * wb_group, nlay = l - l0 + 1;
     PMX_HIP(hipEventRecord(st->ev_ready[slot][l], cs));
     PMX_HIP(hipStreamWaitEvent(st->s_d2h, st->ev_ready[slot][l], 0));
+    if (int us = st->dly_d2h.load()) PMX_HIP(hipLaunchHostFunc(st->s_d2h, host_sleep_cb, (void*)(intptr_t)us));
     st->tbegin(TC_D2H, st->s_d2h);
     // one layer's rows are contiguous for b sequences; a group spans whole layer slots
     const size_t group_bytes = (size_t)(nlay - 1) * layer_elems * st->esz + copy_bytes;
@@ -1286,6 +1295,33 @@ int pipemax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_strea
     PMX_FAIL(PIPEMAX_ERR_ARG, "probe copy needs 16-byte aligned pointers and size");
   launch_probe_copy((hipStream_t)hip_stream, dst, src, bytes);
   PMX_HIP(hipGetLastError());
+  return PIPEMAX_OK;
+}
+
+int pipemax_debug_fill_free_gpu_pages(pipemax_stage_t* st, uint16_t pattern) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  int rc = pipemax_sync(st);
+  if (rc) return rc;
+  const int total = st->gpu_pages->total();
+  int run0 = -1;
+  for (int p = 0; p <= total; ++p) {
+    const bool fr = (p < total) && st->gpu_pages->is_free(p);
+    if (fr && run0 < 0) run0 = p;
+    if (!fr && run0 >= 0) {
+      PMX_HIP(hipMemsetD16Async((hipDeviceptr_t)st->gpu_page_ptr(run0), pattern,
+                                (size_t)(p - run0) * st->page_bytes / 2, st->s_own));
+      run0 = -1;
+    }
+  }
+  PMX_HIP(hipStreamSynchronize(st->s_own));
+  return PIPEMAX_OK;
+}
+
+int pipemax_debug_set_delays(pipemax_stage_t* st, int h2d_us, int d2h_us, int worker_us) {
+  if (!st || h2d_us < 0 || d2h_us < 0 || worker_us < 0) PMX_FAIL(PIPEMAX_ERR_ARG, "bad argument");
+  st->dly_h2d = h2d_us;
+  st->dly_d2h = d2h_us;
+  st->dly_worker = worker_us;
   return PIPEMAX_OK;
 }
 
