@@ -100,8 +100,11 @@ def main():
     ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the library's plain copy kernel (256 MiB, 3 times): calibration for --pmc runs")
-    ap.add_argument("--cpu-seqs", type=int, default=8)
-    ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time sigma = 1, 1/2, ..., 1/128, 0 (two cycles each) to locate the crossover "
+                         "from link-bound to HBM-bound")
+    ap.add_argument("--cpu-seqs", type=int, default=16)
+    ap.add_argument("--cpu-steps", type=int, default=48)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
@@ -120,7 +123,7 @@ def main():
     K = args.steps if args.steps is not None else shape.decode_steps
     W = args.warmup if args.warmup is not None else 2 * n
     legs_steps = 0 if args.no_legs else (W + 3 * min(K, 16 * n))
-    total_steps = (W + K) + legs_steps + 4 * n
+    total_steps = (W + K) + legs_steps + 4 * n + (9 * 4 * n if args.sweep else 0)
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
@@ -257,6 +260,29 @@ def main():
             "frac_of_link_roofline": round(s3["h2d_bytes"] / dt / 1e9 / LINK_PEAK_GBS, 4),
             "d2h_bytes_per_step": int(s3["d2h_bytes"] / K), "host_wait_s": round(s3["host_wait_s"], 4),
             "host_enqueue_ms_per_step": round(s3["host_enqueue_s"] / K * 1e3, 4)}
+    sweep = None
+    if args.sweep:
+        sweep = []
+        for sg in [1.0] + [2.0 ** -k for k in range(1, 8)] + [0.0]:
+            run.restart(sg)
+            for _ in range(n):
+                i = run.t % n
+                run.step(hin[i], hout[i], stream)
+            sync()
+            st.reset_stats()
+            Ks = 3 * n
+            t0 = time.perf_counter()
+            for _ in range(Ks):
+                i = run.t % n
+                run.step(hin[i], hout[i], stream)
+            sync()
+            dts = time.perf_counter() - t0
+            ss = st.get_stats()
+            sweep.append({"sigma": sg, "streamed_seqs_per_mb": run.n_stream[0], "ms_per_step": round(dts / Ks * 1e3, 3),
+                          "tokens_per_s": round(ss["tokens"] / dts, 1),
+                          "h2d_gb_per_step": round(ss["h2d_bytes"] / Ks / 1e9, 4),
+                          "h2d_gbs_wall": round(ss["h2d_bytes"] / dts / 1e9, 2)})
+            log("sweep:", json.dumps(sweep[-1]))
     out = {
         "metric": "stage decode tokens/sec with host-offloaded KV", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
@@ -269,6 +295,8 @@ def main():
                    "inactive_kv": "pinned host memory", "page_tokens": 16},
         "roofline": roofline, "legs": legs,
     }
+    if sweep is not None:
+        out["sigma_sweep"] = sweep
     if args.probe_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)

@@ -37,9 +37,7 @@ class StageRunner:
         self.b_of = {mb: len(self.ctx0[mb]) for mb in range(self.n)}
         steps_per_mb = -(-self.steps // self.n)
         grow = pages_for(steps_per_mb) + 1
-        self.n_stream = {mb: int(round(sigma * self.b_of[mb])) for mb in range(self.n)}
-        self.stream_ids = {mb: np.arange(self.b_of[mb] - self.n_stream[mb], self.b_of[mb], dtype=np.int32)
-                           for mb in range(self.n)}
+        self._set_sigma(sigma)
         full = {mb: [pages_for(l) + grow for l in self.ctx0[mb]] for mb in range(self.n)}
         host_pages = sum(sum(v) for v in full.values())
         resident_pages = sum(sum(full[mb][: self.b_of[mb] - self.n_stream[mb]]) for mb in range(self.n))
@@ -60,6 +58,23 @@ class StageRunner:
             wb_layers_per_copy=wb_layers_per_copy)
         self.torch_dtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
         self.t = 0
+
+    def _set_sigma(self, sigma: float):
+        self.sigma = float(sigma)
+        self.n_stream = {mb: int(round(sigma * self.b_of[mb])) for mb in range(self.n)}
+        self.stream_ids = {mb: np.arange(self.b_of[mb] - self.n_stream[mb], self.b_of[mb], dtype=np.int32)
+                           for mb in range(self.n)}
+
+    def restart(self, sigma: float):
+        """Evicts everything, changes the streamed fraction and restarts the cycle at iteration 0
+        (needs a GPU pool that can hold the resident parts plus two streamed parts)."""
+        for mb in range(self.n):
+            self.stage.evict_kv(mb)
+        self.stage.sync()
+        self._set_sigma(sigma)
+        self.t = 0
+        self.warm_start()
+        self.stage.sync()
 
     # -- set-up ---------------------------------------------------------------------------------
     def load_weights(self):
