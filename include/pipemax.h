@@ -74,8 +74,11 @@ enum {
                                        events and accumulate their durations in the stats        */
   PIPEMAX_FLAG_NO_WRITEBACK   = 8,  /* do not write new K,V through to the host replica
                                        (compute-only timing runs; evict then loses new tokens)   */
-  PIPEMAX_FLAG_TIME_ATTN_ONLY = 16  /* with TIME_KERNELS: bracket only the attention kernel, so that
+  PIPEMAX_FLAG_TIME_ATTN_ONLY = 16, /* with TIME_KERNELS: bracket only the attention kernel, so that
                                        the other launches' event records do not perturb it       */
+  PIPEMAX_FLAG_STREAM_ORDERED_EVICT = 32  /* order a prefetch after the last reader of the pages it
+                                       re-uses with a stream-side event wait instead of the default
+                                       host-side wait inside pipemax_prefetch_kv (see there)      */
 };
 
 typedef struct {
@@ -178,7 +181,11 @@ int pipemax_kv_dev_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok
  * seq_ids: host pointer to n sequence indices, or NULL for all sequences of mb.  Sequences that
  * already have GPU pages are skipped.  Waits on the host for pending write-back of `mb`
  * (so that the host replica is complete) and, on the stream, for the last reader of any page
- * it re-uses.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED (nothing applied), ERR_HIP.             */
+ * it re-uses.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED (nothing applied), ERR_HIP.
+ * By default the wait for the last reader of re-used pages is taken on the host (the call blocks
+ * until the decode step that last read the evicted pages has finished): a copy stream that waits on
+ * a not-yet-signalled event of another stream was measured to leave gaps of 150-350 us between its
+ * copies on this platform.  PIPEMAX_FLAG_STREAM_ORDERED_EVICT selects the stream-side wait.       */
 int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n);
 
 /* One decode step of the stage on micro-batch `mb` (the op list of the benchmark spec; cost

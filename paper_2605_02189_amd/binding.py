@@ -41,6 +41,7 @@ F32, BF16 = 0, 1
 W_QKV, W_O, W_GU, W_D, G_ATTN, G_FFN = range(6)
 FLAG_FORCE_GENERIC, FLAG_CAPTURE_LAYERS, FLAG_TIME_KERNELS, FLAG_NO_WRITEBACK = 1, 2, 4, 8
 FLAG_TIME_ATTN_ONLY = 16
+FLAG_STREAM_ORDERED_EVICT = 32
 K_CLASSES = ["norm", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gu", "swiglu",
              "gemm_d", "misc"]
 N_KCLASS = len(K_CLASSES)

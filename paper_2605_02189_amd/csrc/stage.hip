@@ -141,6 +141,7 @@ struct pipemax_stage {
   hipEvent_t ev_table[kTableRing] = {};
   bool table_used[kTableRing] = {};
   int table_pos = 0;
+  std::vector<int> release_wait;   // micro-batches evicted since the last prefetch (host-ordered mode)
   // ordering of growth pages against cancelled prefetches
   hipEvent_t ev_h2d_fence = nullptr;
   bool h2d_fence_pending = false;
@@ -862,6 +863,12 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
              (long long)need);
   PMX_HIP(hipSetDevice(st->dev));
   st->wait_mb_writeback(mb);     // the host replica of mb must be complete before it is read
+  if (!st->release_wait.empty()) {     // the pages freed by earlier evictions are no longer being read
+    const double t0 = now_s();
+    for (int k : st->release_wait) PMX_HIP(hipEventSynchronize(st->mbs[k].ev_step));
+    st->release_wait.clear();
+    st->st.host_wait_s += now_s() - t0;
+  }
   std::vector<int32_t> src, dst;
   src.reserve(need);
   dst.reserve(need);
@@ -906,7 +913,10 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
   if (!any) return PIPEMAX_OK;
   PMX_HIP(hipSetDevice(st->dev));
   // later prefetches into these pages must come after the last step that read them
-  if (M.stepped) PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
+  if (M.stepped) {
+    if (st->cfg.flags & PIPEMAX_FLAG_STREAM_ORDERED_EVICT) PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
+    else st->release_wait.push_back(mb);
+  }
   // pages of a cancelled prefetch may be handed to a decode step's growth: fence the compute stream
   if (any_inflight) {
     PMX_HIP(hipEventRecord(st->ev_h2d_fence, st->s_h2d));
