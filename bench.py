@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--sigma", type=float, default=1.0, help="streamed fraction of every micro-batch")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--microbatches", type=int, default=None,
+                    help="run with fewer micro-batches than the configuration names (host memory limits)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the compute-only / transfer-only legs")
     ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
@@ -119,6 +121,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     shape = CONFIGS[args.config]
+    if args.microbatches:
+        shape = shape.with_(n_microbatches=args.microbatches)
     n = shape.n_microbatches
     K = args.steps if args.steps is not None else shape.decode_steps
     W = args.warmup if args.warmup is not None else 2 * n
