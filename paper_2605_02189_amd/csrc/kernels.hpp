@@ -48,7 +48,8 @@ void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, con
                 uint16_t* hout);
 
 // part[s][m][n] = X[m][k-range s] @ W[k-range s][n]   (X A-tiled, W B-tiled, fp32 partials)
-// Mpad = 32*MT rows are computed, rows < M are stored.  N % (32*wn) == 0, wn in {4, 8}.
+// Mpad = 32*MT rows are computed, rows < M are stored.  N % (32*wn) == 0, wn in {4, 8}; wn == 0 selects the
+// large-tile kernel for 65..256 rows (needs N % 256 == 0).
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
           int n_split, int wn);
 

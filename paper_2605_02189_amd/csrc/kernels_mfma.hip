@@ -212,6 +212,117 @@ __global__ __launch_bounds__(WN * 64) void k_gemm(const uint4* __restrict__ Xt,
 }
 
 // =================================================================================================
+// GEMM for 65..256 rows (MT = 4 or 8 row tiles): part[s][m][n] = X[m][k in split s] . W[k][n]
+//   At these heights the product is close to the matrix-core roofline (arithmetic intensity = M
+//   flop/byte against a ridge of about 310), so the tile is chosen for MFMA work per LDS byte:
+//   a work-group of 4 waves owns 256 columns; every wave owns 64 of them (2 column tiles) and ALL
+//   row tiles, i.e. 2*MT accumulator tiles (256 accumulator registers at MT = 8), and re-uses every
+//   X fragment it reads from LDS for two MFMAs.  X fragments of KC k-steps are staged once per
+//   work-group (double-buffered, one barrier per KC * 2 * MT MFMAs per wave); weight fragments are
+//   streamed from HBM into registers one chunk ahead.
+// =================================================================================================
+template <int MT, int KC>
+__global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
+                                                float* __restrict__ part, int M, int N, int KT, int ksp,
+                                                int64_t split_stride) {
+  constexpr int NF = MT * KC;            // X fragments per chunk
+  constexpr int XPT = NF / 4;            // X fragments loaded per wave
+  static_assert(NF % 4 == 0, "chunk must split evenly over 4 waves");
+  __shared__ uint4 xs[2][NF * 64];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt0 = (blockIdx.x * 4 + w) * 2;
+  const int k0 = blockIdx.y * ksp;
+  const int k1 = min(KT, k0 + ksp);
+  const int nchunks = (k1 - k0 + KC - 1) / KC;
+  const uint4* wp0 = Wt + (int64_t)nt0 * KT * 64 + lane;
+  const uint4* wp1 = wp0 + (int64_t)KT * 64;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  f32x16 acc[2][MT];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
+
+  uint4 wc0[KC], wc1[KC], wn0[KC], wn1[KC];
+  // X fragments go from global memory straight into LDS (global_load_lds_dwordx4: lane i of the wave
+  // writes bytes [16 i, 16 i + 16) after the wave-uniform LDS base), no staging registers
+  auto load_x = [&](int kc0, int buf) {
+#pragma unroll
+    for (int t = 0; t < XPT; ++t) {
+      const int f = w + t * 4, mt = f / KC, kk = f - mt * KC;
+      if (kc0 + kk < k1)
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(Xt + ((int64_t)mt * KT + kc0 + kk) * 64 + lane),
+            (void __attribute__((address_space(3)))*)(&xs[buf][f * 64]), 16, 0, 0);
+      else
+        xs[buf][f * 64 + lane] = zero4;
+    }
+  };
+
+  if (nchunks > 0) {
+    load_x(k0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      const bool ok = k0 + kk < k1;
+      wc0[kk] = ok ? ld_stream(wp0 + (int64_t)(k0 + kk) * 64) : zero4;
+      wc1[kk] = ok ? ld_stream(wp1 + (int64_t)(k0 + kk) * 64) : zero4;
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const int buf = c & 1;
+    const bool more = (c + 1 < nchunks);
+    if (more) {
+      const int kn = k0 + (c + 1) * KC;
+      load_x(kn, buf ^ 1);
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk) {
+        const bool ok = kn + kk < k1;
+        wn0[kk] = ok ? ld_stream(wp0 + (int64_t)(kn + kk) * 64) : zero4;
+        wn1[kk] = ok ? ld_stream(wp1 + (int64_t)(kn + kk) * 64) : zero4;
+      }
+    }
+    // (forcing the LDS reads several fragments ahead of their MFMAs with scheduling barriers was
+    // measured slower than the compiler's read-then-two-MFMAs order: the MFMAs run asynchronously)
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      const bf16x8 B0 = __builtin_bit_cast(bf16x8, wc0[kk]);
+      const bf16x8 B1 = __builtin_bit_cast(bf16x8, wc1[kk]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bf16x8 A = __builtin_bit_cast(bf16x8, xs[buf][(mt * KC + kk) * 64 + lane]);
+        acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B0, acc[0][mt], 0, 0, 0);
+        acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B1, acc[1][mt], 0, 0, 0);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk) {
+        wc0[kk] = wn0[kk];
+        wc1[kk] = wn1[kk];
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);      // the next chunk's direct-to-LDS loads have landed
+    __syncthreads();
+  }
+
+  float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt0 * 32 + (lane & 31);
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < M) out[(int64_t)m * N + nt * 32] = acc[nt][mt][r];
+      }
+}
+
+// =================================================================================================
 // skinny GEMM for at most 64 rows (MT <= 2): barrier-free streaming
 //   grid (N / (32*NT), S), block = NWK waves.  The block owns NT adjacent 32-column tiles and the
 //   K range of split blockIdx.y; its waves take the k-steps of that range round-robin.  Every wave
@@ -907,8 +1018,24 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 #undef PMX_GEMM_CASE
 }
 
+static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
+                       int n_split) {
+  const int KT = K / 16;
+  const int ksp = (KT + n_split - 1) / n_split;
+  const int MT = (M + 31) / 32;
+  const int64_t stride = (int64_t)MT * 32 * N;
+  dim3 grid(N / 256, n_split), block(256);
+  if (MT <= 4)
+    hipLaunchKernelGGL((k_gemm_l<4, 4>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, M, N, KT, ksp,
+                       stride);
+  else
+    hipLaunchKernelGGL((k_gemm_l<8, 4>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, M, N, KT, ksp,
+                       stride);
+}
+
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
           int n_split, int wn) {
+  if (wn == 0) { gemm_large(s, Xt, Wt, part, M, K, N, n_split); return; }
   if (wn == 8) gemm_wn<8>(s, Xt, Wt, part, M, K, N, n_split);
   else gemm_wn<4>(s, Xt, Wt, part, M, K, N, n_split);
 }

@@ -356,6 +356,19 @@ GemmPlan plan_gemm_skinny(int N, int K, bool swiglu) {
   return p;
 }
 
+// 65..256 rows: large-tile kernel, one work-group (4 waves, 256 columns) per CU and about 256
+// work-groups in total
+GemmPlan plan_gemm_large(int N, int K) {
+  GemmPlan p;
+  p.wn = 0;
+  const int bn = N / 256, KT = K / 16;
+  int S = std::max(1, (256 + bn / 2) / bn);
+  S = std::max(1, std::min(S, KT / 16));
+  const int ksp = (KT + S - 1) / S;
+  p.split = (KT + ksp - 1) / ksp;
+  return p;
+}
+
 GemmPlan plan_gemm(int N, int K) {
   GemmPlan p;
   p.wn = (N % 256 == 0) ? 8 : 4;
@@ -602,10 +615,11 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
       st->p_gu = plan_gemm_skinny(2 * F, h, true);
       st->p_d = plan_gemm_skinny(h, F, false);
     } else {
-      st->p_qkv = plan_gemm(D.Nqkv, h);
-      st->p_o = plan_gemm(h, nq);
-      st->p_gu = plan_gemm(2 * F, h);
-      st->p_d = plan_gemm(h, F);
+      auto plan = [&](int N, int K) { return (N % 256 == 0) ? plan_gemm_large(N, K) : plan_gemm(N, K); };
+      st->p_qkv = plan(D.Nqkv, h);
+      st->p_o = plan(h, nq);
+      st->p_gu = plan(2 * F, h);
+      st->p_d = plan(h, F);
     }
     size_t part = 0;
     part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
