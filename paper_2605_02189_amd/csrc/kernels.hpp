@@ -68,10 +68,11 @@ constexpr int kAttnWaves = 4;   // waves per attention work-group
 // Split-K paged GQA decode attention.  chunk_pages = target pages per work-group (<= 64 * kAttnWaves), max_chunks = grid
 // extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
 // (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)
-// and writes the A-tiled bf16 input of the output projection.
+// and writes the A-tiled bf16 input of the output projection.  order[z] = sequence handled by grid
+// slice z (a permutation of 0..b-1, longest context first).
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q,
                const uint16_t* pool, const int* table, const int* ctx, float* part_o, float* part_ml,
-               int chunk_pages, int max_chunks, int* counters, uint16_t* out_t);
+               int chunk_pages, int max_chunks, int* counters, uint16_t* out_t, const int* order);
 
 // ---- fused pipeline for b <= 64 rows -----------------------------------------------------------------
 // x = hidden_in; ssq_out[i][0] = sum of squares of row i (other nb-1 entries 0); xg_t = x * gain as

@@ -773,11 +773,14 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
                                                   const int* __restrict__ ctx, float* __restrict__ part_o,
                                                   float* __restrict__ part_ml, int CP, int NCH,
                                                   int* __restrict__ counters,
-                                                  uint16_t* __restrict__ out_t) {
+                                                  uint16_t* __restrict__ out_t,
+                                                  const int* __restrict__ order) {
   extern __shared__ float so[];                 // [NW][G][kORow], later [G][kORow] merged
   __shared__ float sm[NW][16], sl[NW][16];
   __shared__ int s_last;
-  const int chunk = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+  // work-groups are dispatched in grid order: `order` lists the sequences longest first, so that the
+  // long ones start early and the kernel's tail consists of short ones
+  const int chunk = blockIdx.x, c = blockIdx.y, i = order[blockIdx.z];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
   const int G = D.G;
   // issue the three independent first loads together: length, this wave's page ids, Q
@@ -1076,11 +1079,11 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
 
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
-               int max_chunks, int* counters, uint16_t* out_t) {
+               int max_chunks, int* counters, uint16_t* out_t, const int* order) {
   constexpr int NW = kAttnWaves;
   const size_t lds = (size_t)NW * D.G * kORow * sizeof(float);
   hipLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), lds, s, D, layer, q, pool, table,
-                     ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t);
+                     ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t, order);
 }
 
 void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uint16_t* gain, uint16_t* xg_t,

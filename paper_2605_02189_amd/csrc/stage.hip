@@ -61,7 +61,7 @@ struct MicroBatch {
   int b = 0;
   std::vector<SeqState> seq;
   int* d_ctx = nullptr;
-  int* d_table = nullptr;
+  int* d_table = nullptr;   // [maxb][max_pages] page ids, then [maxb] sequence order (longest first)
   bool table_dirty = true;
   hipEvent_t ev_prefetch = nullptr;
   bool prefetch_pending = false;
@@ -126,6 +126,7 @@ struct pipemax_stage {
   float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr, *m_ssq = nullptr;
   int *m_cnt_gemm = nullptr, *m_cnt_attn = nullptr;
   bool fused = false;   // b <= 64: consumers fused into the GEMM epilogues
+  int attn_cp_override = 0;   // PIPEMAX_ATTN_CHUNK_PAGES: tuning override of the attention chunk size
   GemmPlan p_qkv, p_o, p_gu, p_d;
   int nch_alloc = 1;
   float* layer_out = nullptr;
@@ -568,8 +569,8 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   st->mbs.resize(c.n_microbatches);
   for (auto& M : st->mbs) {
     PMX_TRY(dev_alloc(st, &M.d_ctx, (size_t)maxb));
-    PMX_TRY(dev_alloc(st, &M.d_table, (size_t)maxb * D.max_pages));
-    PMX_TRY_HIP(hipMemset(M.d_table, 0, (size_t)maxb * D.max_pages * sizeof(int)));
+    PMX_TRY(dev_alloc(st, &M.d_table, (size_t)maxb * D.max_pages + maxb));
+    PMX_TRY_HIP(hipMemset(M.d_table, 0, ((size_t)maxb * D.max_pages + maxb) * sizeof(int)));
     PMX_TRY_HIP(hipMemset(M.d_ctx, 0, (size_t)maxb * sizeof(int)));
     PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_prefetch, hipEventDisableTiming));
     PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_step, hipEventDisableTiming));
@@ -662,13 +663,14 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     }
   }
   for (int r = 0; r < kTableRing; ++r) {
-    PMX_TRY(host_alloc(st, &st->h_table[r], (size_t)maxb * D.max_pages));
+    PMX_TRY(host_alloc(st, &st->h_table[r], (size_t)maxb * D.max_pages + maxb));
     PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_table[r], hipEventDisableTiming));
   }
   PMX_TRY_HIP(hipDeviceSynchronize());
 #undef PMX_TRY
 #undef PMX_TRY_HIP
 
+  if (const char* e = getenv("PIPEMAX_ATTN_CHUNK_PAGES")) st->attn_cp_override = atoi(e);
   st->worker = std::thread(worker_main, st);
   st->worker_started = true;
   st->st.engine = st->engine;
@@ -1020,7 +1022,12 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
       std::copy(S.gpu.begin(), S.gpu.end(), rowp);
       std::fill(rowp + S.gpu.size(), rowp + D.max_pages, 0);
     }
-    PMX_HIP(hipMemcpyAsync(M.d_table, ht, (size_t)b * D.max_pages * sizeof(int32_t), hipMemcpyHostToDevice, cs));
+    // sequence order for the attention grid: longest context first (ties by index)
+    int32_t* ord = ht + (size_t)st->cfg.max_seqs_per_mb * D.max_pages;
+    for (int i = 0; i < b; ++i) ord[i] = i;
+    std::stable_sort(ord, ord + b, [&](int a, int c2) { return M.seq[a].len > M.seq[c2].len; });
+    PMX_HIP(hipMemcpyAsync(M.d_table, ht, ((size_t)st->cfg.max_seqs_per_mb * D.max_pages + b) * sizeof(int32_t),
+                           hipMemcpyHostToDevice, cs));
     PMX_HIP(hipEventRecord(st->ev_table[r], cs));
     st->table_used[r] = true;
     M.table_dirty = false;
@@ -1131,6 +1138,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     const int nch_target = std::max(1, (1024 + per_chunk_waves / 2) / per_chunk_waves);
     int CP = (npages_max + nch_target - 1) / nch_target;
     CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
+    if (st->attn_cp_override > 0) CP = std::max(8, std::min(64 * mfma::kAttnWaves, st->attn_cp_override));
     const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
     const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
     auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
@@ -1139,7 +1147,8 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     auto run_attention = [&](int l) {
       st->tbegin(PIPEMAX_K_ATTN, cs);
       mfma::attention(cs, D, l, b, st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, st->m_part_o,
-                      st->m_part_ml, CP, nch, st->m_cnt_attn, st->m_attn_t);
+                      st->m_part_ml, CP, nch, st->m_cnt_attn, st->m_attn_t,
+                      M.d_table + (size_t)st->cfg.max_seqs_per_mb * D.max_pages);
       st->tend(cs);
     };
     if (st->fused) {
