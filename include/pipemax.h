@@ -203,6 +203,16 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
 int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
                         void* hip_stream);
 
+/* The same step over a caller-chosen part of `mb` (Sec. 3.3.2: the executed batch is
+ * D_j^res united with the prefetched set P_t, i.e. the sequences of D_j whose KV is on the GPU;
+ * hybrid batches of Sec. 3.1.2).  seq_ids: host pointer to n distinct sequence indices; row r of
+ * hidden_in / hidden_out ([n][hidden]) belongs to sequence seq_ids[r].  Only the listed
+ * sequences must be resident, only they grow by one token, the others are untouched.  n == 0 is
+ * a successful no-op.  The block table of the step is rebuilt and uploaded on every call.
+ * Errors: as pipemax_decode_step, plus ERR_ARG for an index out of range or listed twice.     */
+int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n,
+                             const void* hidden_in, void* hidden_out, void* hip_stream);
+
 /* Evict (Sec. 3.3.2, "overwriting KV cache blocks associated with the inactive batch D_k"):
  * releases the GPU pages of the named sequences (NULL = all of mb).  No bulk copy is made: the
  * host replica is kept current by the per-layer write-back.  Later prefetches into the freed

@@ -61,7 +61,8 @@ struct MicroBatch {
   int b = 0;
   std::vector<SeqState> seq;
   int* d_ctx = nullptr;
-  int* d_table = nullptr;   // [maxb][max_pages] page ids, then [maxb] sequence order (longest first)
+  int* d_table = nullptr;   // [maxb][max_pages] page ids, [maxb] row order (longest first), [maxb] lengths
+                            // (d_ctx points at the lengths); rows are the sequences of the last step
   bool table_dirty = true;
   hipEvent_t ev_prefetch = nullptr;
   bool prefetch_pending = false;
@@ -568,10 +569,9 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   const int h = c.hidden, F = c.ffn, nq = c.n_q_heads * c.head_dim;
   st->mbs.resize(c.n_microbatches);
   for (auto& M : st->mbs) {
-    PMX_TRY(dev_alloc(st, &M.d_ctx, (size_t)maxb));
-    PMX_TRY(dev_alloc(st, &M.d_table, (size_t)maxb * D.max_pages + maxb));
-    PMX_TRY_HIP(hipMemset(M.d_table, 0, ((size_t)maxb * D.max_pages + maxb) * sizeof(int)));
-    PMX_TRY_HIP(hipMemset(M.d_ctx, 0, (size_t)maxb * sizeof(int)));
+    PMX_TRY(dev_alloc(st, &M.d_table, (size_t)maxb * D.max_pages + 2 * (size_t)maxb));
+    PMX_TRY_HIP(hipMemset(M.d_table, 0, ((size_t)maxb * D.max_pages + 2 * (size_t)maxb) * sizeof(int)));
+    M.d_ctx = M.d_table + (size_t)maxb * D.max_pages + maxb;
     PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_prefetch, hipEventDisableTiming));
     PMX_TRY_HIP(hipEventCreateWithFlags(&M.ev_step, hipEventDisableTiming));
   }
@@ -663,7 +663,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     }
   }
   for (int r = 0; r < kTableRing; ++r) {
-    PMX_TRY(host_alloc(st, &st->h_table[r], (size_t)maxb * D.max_pages + maxb));
+    PMX_TRY(host_alloc(st, &st->h_table[r], (size_t)maxb * D.max_pages + 2 * (size_t)maxb));
     PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_table[r], hipEventDisableTiming));
   }
   PMX_TRY_HIP(hipDeviceSynchronize());
@@ -778,7 +778,6 @@ int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ct
     S.host_reserved.assign(S.host.begin() + np, S.host.end());
     S.host.resize(np);
   }
-  PMX_HIP(hipMemcpy(M.d_ctx, ctx_lens, (size_t)n_seqs * sizeof(int), hipMemcpyHostToDevice));
   M.b = n_seqs;
   M.defined = true;
   M.table_dirty = true;
@@ -950,20 +949,23 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
 }
 
 // ---- the decode step ----------------------------------------------------------------------------------
-int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
-                        void* hip_stream) {
+namespace {
+// One decode step over the rows `sel` (sequence indices of mb, distinct, in row order).  `subset` says that
+// the rows are a caller-chosen list: the device copy of the block table is then rebuilt for this step.
+int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool subset, const void* hidden_in,
+                void* hidden_out, void* hip_stream) {
   const double t_enter = now_s();
-  int rc = check_mb(st, mb, true);
-  if (rc) return rc;
+  int rc;
   if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
   MicroBatch& M = st->mbs[mb];
   const Dims& D = st->D;
-  const int b = M.b, nl = st->cfg.n_layers;
+  const int b = (int)sel.size(), nl = st->cfg.n_layers;
+  if (b == 0) return PIPEMAX_OK;
   int grow = 0, grow_host = 0, max_len = 0;
-  for (int i = 0; i < b; ++i)
+  for (int i : sel)
     if (M.seq[i].state == ST_HOST)
       PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", i, mb);
-  for (int i = 0; i < b; ++i) {
+  for (int i : sel) {
     const SeqState& S = M.seq[i];
     if (S.len + 1 > st->cfg.max_ctx)
       PMX_FAIL(PIPEMAX_ERR_STATE, "sequence %d of micro-batch %d is at max_ctx %d", i, mb, st->cfg.max_ctx);
@@ -983,8 +985,8 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   // ---- bookkeeping: growth pages, positions of the new token ----------------------------------------
   const bool writeback = !(st->cfg.flags & PIPEMAX_FLAG_NO_WRITEBACK);
   auto where = std::make_shared<std::vector<std::pair<int32_t, int>>>(b);
-  for (int i = 0; i < b; ++i) {
-    SeqState& S = M.seq[i];
+  for (int r = 0; r < b; ++r) {
+    SeqState& S = M.seq[sel[r]];
     if (S.len % kPageTokens == 0) {
       int32_t gp, hp;
       st->gpu_pages->alloc(1, &gp);
@@ -998,7 +1000,7 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
       S.host.push_back(hp);
       M.table_dirty = true;
     }
-    (*where)[i] = {S.host[S.len / kPageTokens], S.len % kPageTokens};
+    (*where)[r] = {S.host[S.len / kPageTokens], S.len % kPageTokens};
   }
 
   // ---- stream dependencies -----------------------------------------------------------------------
@@ -1010,27 +1012,32 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     PMX_HIP(hipStreamWaitEvent(cs, st->ev_h2d_fence, 0));
     st->h2d_fence_pending = false;
   }
-  for (auto& S : M.seq) S.state = ST_GPU;
-  if (M.table_dirty) {
+  for (int i : sel) M.seq[i].state = ST_GPU;
+  if (M.table_dirty || subset) {
     const int r = st->table_pos;
     st->table_pos = (st->table_pos + 1) % kTableRing;
     if (st->table_used[r]) PMX_HIP(hipEventSynchronize(st->ev_table[r]));
     int32_t* ht = st->h_table[r];
-    for (int i = 0; i < b; ++i) {
-      const SeqState& S = M.seq[i];
-      int32_t* rowp = ht + (size_t)i * D.max_pages;
+    const int maxb = st->cfg.max_seqs_per_mb;
+    for (int r2 = 0; r2 < b; ++r2) {
+      const SeqState& S = M.seq[sel[r2]];
+      int32_t* rowp = ht + (size_t)r2 * D.max_pages;
       std::copy(S.gpu.begin(), S.gpu.end(), rowp);
       std::fill(rowp + S.gpu.size(), rowp + D.max_pages, 0);
     }
-    // sequence order for the attention grid: longest context first (ties by index)
-    int32_t* ord = ht + (size_t)st->cfg.max_seqs_per_mb * D.max_pages;
-    for (int i = 0; i < b; ++i) ord[i] = i;
-    std::stable_sort(ord, ord + b, [&](int a, int c2) { return M.seq[a].len > M.seq[c2].len; });
-    PMX_HIP(hipMemcpyAsync(M.d_table, ht, ((size_t)st->cfg.max_seqs_per_mb * D.max_pages + b) * sizeof(int32_t),
+    // row order for the attention grid: longest context first (ties by row)
+    int32_t* ord = ht + (size_t)maxb * D.max_pages;
+    for (int r2 = 0; r2 < b; ++r2) ord[r2] = r2;
+    std::stable_sort(ord, ord + b, [&](int a, int c2) { return M.seq[sel[a]].len > M.seq[sel[c2]].len; });
+    std::fill(ord + b, ord + maxb, 0);
+    // lengths before this step; the last kernel of a step advances the device copy
+    int32_t* hl = ord + maxb;
+    for (int r2 = 0; r2 < b; ++r2) hl[r2] = M.seq[sel[r2]].len;
+    PMX_HIP(hipMemcpyAsync(M.d_table, ht, ((size_t)maxb * D.max_pages + maxb + b) * sizeof(int32_t),
                            hipMemcpyHostToDevice, cs));
     PMX_HIP(hipEventRecord(st->ev_table[r], cs));
     st->table_used[r] = true;
-    M.table_dirty = false;
+    M.table_dirty = subset;   // after a caller-chosen row list the device copy does not describe the whole mb
     st->st.table_uploads += 1;
   }
   const int slot = (int)(st->step_no % kSlots);
@@ -1251,13 +1258,40 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
   PMX_HIP(hipEventRecord(M.ev_step, cs));
   PMX_HIP(hipGetLastError());
   M.stepped = true;
-  for (auto& S : M.seq) S.len += 1;
+  for (int i : sel) M.seq[i].len += 1;
   st->last_b = b;
   st->step_no += 1;
   st->st.steps += 1;
   st->st.tokens += (uint64_t)b;
   st->st.host_enqueue_s += now_s() - t_enter;
   return PIPEMAX_OK;
+}
+}  // namespace
+
+int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
+                        void* hip_stream) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  std::vector<int> sel(st->mbs[mb].b);
+  for (int i = 0; i < (int)sel.size(); ++i) sel[i] = i;
+  return decode_rows(st, mb, sel, false, hidden_in, hidden_out, hip_stream);
+}
+
+int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n, const void* hidden_in,
+                             void* hidden_out, void* hip_stream) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!seq_ids && n != 0) PMX_FAIL(PIPEMAX_ERR_ARG, "null sequence list");
+  if (n < 0 || n > st->mbs[mb].b) PMX_FAIL(PIPEMAX_ERR_ARG, "%d rows for a micro-batch of %d", n, st->mbs[mb].b);
+  std::vector<int> sel;
+  std::vector<char> seen(st->mbs[mb].b, 0);
+  for (int k = 0; k < n; ++k) {
+    if (seq_ids[k] < 0 || seq_ids[k] >= st->mbs[mb].b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", seq_ids[k]);
+    if (seen[seq_ids[k]]) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d listed twice", seq_ids[k]);
+    seen[seq_ids[k]] = 1;
+    sel.push_back(seq_ids[k]);
+  }
+  return decode_rows(st, mb, sel, true, hidden_in, hidden_out, hip_stream);
 }
 
 int pipemax_sync(pipemax_stage_t* st) {

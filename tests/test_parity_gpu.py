@@ -259,6 +259,83 @@ def test_results_do_not_depend_on_physical_page_placement():
         np.testing.assert_array_equal(outs[0][t], outs[1][t])
 
 
+@pytest.mark.parametrize("engine", ["mfma", "generic_fp32"])
+def test_decode_over_a_chosen_part_of_a_microbatch(engine):
+    """pipemax_decode_step_seqs: a different subset of each micro-batch, in a shuffled row order, is
+    prefetched and executed at every step; only the listed sequences grow; whole-micro-batch steps in
+    between see the right lengths and tables; the sequences left on the host keep their bytes."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs, CONFIGS
+    from paper_2605_02189_amd.harness import StageRunner
+    from oracle.bookkeeping_oracle import ResidencyModel
+    if engine == "mfma":
+        shape = _mid_shape(n_microbatches=2, seqs_per_mb=12, ctx_hi=200, decode_steps=10)
+        tol_layer, tol_delta = 1e-2, 3e-2
+    else:
+        shape = CONFIGS["C1"].with_(n_microbatches=2, decode_steps=10)
+        tol_layer, tol_delta = 1e-5, 2e-4
+    syn = SynthInputs(shape, seed=11, pool_elems=1 << 23, gain_jitter=0.1)
+    ctx = {mb: syn.ctx_lens(mb).copy() for mb in range(2)}
+    ctx[0][:4] = [0, 15, 16, 31]
+    runner = StageRunner(shape, syn, sigma=0.0, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx,
+                         gpu_pool_all_resident=True).load()
+    st = runner.stage
+    assert st.get_stats()["engine"] == (1 if engine == "mfma" else 0)
+    orc = make_oracle(shape, syn, runner.ctx0)
+    rng = np.random.default_rng(5)
+    cur = torch.cuda.current_stream().cuda_stream
+    b = runner.b_of[0]
+    for t in range(10):
+        mb = t % 2
+        if t in (4, 5):                                   # a whole-micro-batch step between subset steps
+            rows = list(range(b))
+            st.prefetch_kv(mb)
+        else:
+            rows = rng.permutation(b)[: int(rng.integers(1, b + 1))].tolist()
+            st.evict_kv(mb, [s for s in range(b) if s not in rows])
+            st.prefetch_kv(mb, rows)
+        print(f"step {t} mb {mb} rows {rows}", flush=True)
+        x = syn.hidden(t, len(rows))
+        hin = (torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16) if shape.dtype == "bf16"
+               else torch.from_numpy(np.array(x, dtype=np.float32))).to("cuda:0")
+        hout = torch.empty_like(hin)
+        before = st.get_ctx_lens(mb).copy()
+        if t in (4, 5):
+            st.decode_step(mb, hin.data_ptr(), hout.data_ptr(), cur)
+        else:
+            st.decode_step_seqs(mb, rows, hin.data_ptr(), hout.data_ptr(), cur)
+        ref_out, ref_layers = orc.decode_step(mb, syn.as_f32(x), seqs=rows)
+        got_layers = st.get_layer_outputs(len(rows))
+        prev_ref = prev_got = syn.as_f32(x)
+        for l in range(shape.n_layers):
+            assert rel_l2(got_layers[l], ref_layers[l]) <= tol_layer, (t, l)
+            assert rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref) <= tol_delta, (t, l)
+            prev_ref, prev_got = ref_layers[l], got_layers[l]
+        assert rel_l2(runner.to_numpy_f32(hout), ref_out) <= max(tol_layer, 8e-3 if shape.dtype == "bf16" else 0)
+        after = st.get_ctx_lens(mb)
+        want = before.copy()
+        want[rows] += 1
+        np.testing.assert_array_equal(after, want)
+        assert after.tolist() == [orc.ctx_len(mb, s) for s in range(b)]
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=tol_layer)
+    # argument errors: a sequence listed twice, out of range, host-resident; nothing changes
+    lens = st.get_ctx_lens(0).copy()
+    x = torch.zeros(2, shape.hidden, dtype=runner.torch_dtype, device="cuda:0")
+    for bad, code in (([1, 1], pm.ERR_ARG), ([0, b], pm.ERR_ARG)):
+        with pytest.raises(pm.PipemaxError) as e:
+            st.decode_step_seqs(0, bad, x.data_ptr(), x.data_ptr(), cur)
+        assert e.value.code == code
+    st.evict_kv(0, [2])
+    with pytest.raises(pm.PipemaxError) as e:
+        st.decode_step_seqs(0, [2], x.data_ptr(), x.data_ptr(), cur)
+    assert e.value.code == pm.ERR_NOT_RESIDENT
+    st.decode_step_seqs(0, [], x.data_ptr(), x.data_ptr(), cur)          # empty list: no-op
+    np.testing.assert_array_equal(st.get_ctx_lens(0), lens)
+    st.destroy()
+
+
 def test_error_paths_leave_the_stage_unchanged():
     torch = _torch()
     from paper_2605_02189_amd import binding as pm
