@@ -231,6 +231,10 @@ int pipemax_reset_stats(pipemax_stage_t* st);
  * changed after creation (ERR_ARG otherwise).  Synchronises the stage first.                */
 int pipemax_set_flags(pipemax_stage_t* st, uint32_t set, uint32_t clear);
 
+/* Copies the configuration the stage was created with into *out (host pointer).            */
+int pipemax_get_config(pipemax_stage_t* st, pipemax_config_t* out);
+/* *n_seqs (host pointer) receives the number of sequences of mb, 0 if mb is not defined yet. */
+int pipemax_mb_size(pipemax_stage_t* st, int mb, int32_t* n_seqs);
 /* out: host pointer to n_seqs int32 (current context lengths).                             */
 int pipemax_get_ctx_lens(pipemax_stage_t* st, int mb, int32_t* out);
 /* out: host pointer to n_seqs int32: 0 = HOST, 1 = prefetch in flight, 2 = GPU.            */

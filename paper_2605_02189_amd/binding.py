@@ -52,11 +52,19 @@ SYMBOLS = [
     "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_decode_step_seqs", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
-    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
+    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_config", "pipemax_mb_size",
+    "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
     "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
     "pipemax_plan_copy_runs", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
     "pipemax_pool_free", "pipemax_pool_free_count",
+]
+# every symbol include/pipemax_sched.h declares
+SCHED_SYMBOLS = [
+    "pipemax_sched_create", "pipemax_sched_destroy", "pipemax_sched_predict", "pipemax_sched_budget",
+    "pipemax_sched_observe", "pipemax_sched_short_first_fill", "pipemax_sched_greedy_fill",
+    "pipemax_sched_refine", "pipemax_sched_partition", "pipemax_sched_set_batch",
+    "pipemax_sched_set_gpu_pages_free", "pipemax_sched_attach", "pipemax_sched_plan", "pipemax_sched_iterate",
 ]
 
 
@@ -91,7 +99,42 @@ class Stats(C.Structure):
 
 
 _vp, _i32p = C.c_void_p, C.POINTER(C.c_int32)
+
+
+class SchedConfig(C.Structure):
+    _fields_ = [("alpha_s", C.c_double), ("beta_s", C.c_double), ("delta_s", C.c_double),
+                ("link_tokens_per_s", C.c_double), ("steady_rel_range", C.c_double),
+                ("refine_tol_s", C.c_double), ("static_budget_tokens", C.c_int64),
+                ("window", C.c_int32), ("max_refine_steps", C.c_int32), ("n_batches", C.c_int32),
+                ("page_tokens", C.c_int32)]
+
+
+class SchedIter(C.Structure):
+    _fields_ = [("exec_batch", C.c_int32), ("n_exec", C.c_int32), ("prefetch_batch", C.c_int32),
+                ("n_prefetch", C.c_int32), ("evict_batch", C.c_int32), ("n_evict", C.c_int32),
+                ("steady", C.c_int32), ("n_exchanges", C.c_int32), ("budget_tokens", C.c_int64),
+                ("prefetch_tokens", C.c_int64), ("gpu_pages_free", C.c_int64), ("t_hat_s", C.c_double),
+                ("gap_s", C.c_double)]
+
+
 _sig = {
+    "pipemax_sched_create": (C.c_int, [C.POINTER(SchedConfig), C.POINTER(C.c_void_p)]),
+    "pipemax_sched_destroy": (C.c_int, [C.c_void_p]),
+    "pipemax_sched_predict": (C.c_double, [C.c_void_p, C.c_int32, C.c_int64]),
+    "pipemax_sched_budget": (C.c_int64, [C.c_void_p, C.c_double]),
+    "pipemax_sched_observe": (C.c_int, [C.c_void_p, C.c_int64]),
+    "pipemax_sched_short_first_fill": (C.c_int, [_i32p, C.c_int32, C.c_int64, _i32p, _i32p]),
+    "pipemax_sched_greedy_fill": (C.c_int, [_i32p, C.c_int32, C.c_int64, _i32p, _i32p]),
+    "pipemax_sched_refine": (C.c_int, [C.c_void_p, _i32p, C.c_int32, C.c_int64, C.c_double, _i32p, _i32p, _i32p]),
+    "pipemax_sched_partition": (C.c_int, [_i32p, C.c_int32, C.c_int32, _i32p]),
+    "pipemax_sched_set_batch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p]),
+    "pipemax_sched_set_gpu_pages_free": (C.c_int, [C.c_void_p, C.c_int64]),
+    "pipemax_sched_attach": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "pipemax_sched_plan": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(SchedIter), _i32p, _i32p, _i32p]),
+    "pipemax_sched_iterate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(SchedIter), _i32p, _i32p, _i32p]),
+    "pipemax_get_config": (C.c_int, [C.c_void_p, C.POINTER(Config)]),
+    "pipemax_mb_size": (C.c_int, [C.c_void_p, C.c_int, _i32p]),
     "pipemax_stage_create": (C.c_int, [C.POINTER(Config), C.POINTER(_vp)]),
     "pipemax_stage_destroy": (C.c_int, [_vp]),
     "pipemax_set_weight": (C.c_int, [_vp, C.c_int, C.c_int, _vp, C.c_size_t]),
@@ -325,3 +368,112 @@ class Pool:
         if self._h:
             _lib.pipemax_pool_destroy(self._h)
             self._h = _vp()
+
+
+# -- prefetch-aware decode scheduler (include/pipemax_sched.h) ------------------------------------
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(_i32p)
+
+
+def sched_short_first_fill(lens, budget: int) -> list:
+    a, p = _i32(lens)
+    sel, n = np.empty(max(a.size, 1), dtype=np.int32), C.c_int32(0)
+    _check(_lib.pipemax_sched_short_first_fill(p, int(a.size), int(budget), sel.ctypes.data_as(_i32p), C.byref(n)))
+    return sel[: n.value].tolist()
+
+
+def sched_greedy_fill(lens, budget: int) -> list:
+    a, p = _i32(lens)
+    sel, n = np.empty(max(a.size, 1), dtype=np.int32), C.c_int32(0)
+    _check(_lib.pipemax_sched_greedy_fill(p, int(a.size), int(budget), sel.ctypes.data_as(_i32p), C.byref(n)))
+    return sel[: n.value].tolist()
+
+
+def sched_partition(lens, n_batches: int) -> list:
+    a, p = _i32(lens)
+    out = np.empty(max(a.size, 1), dtype=np.int32)
+    _check(_lib.pipemax_sched_partition(p, int(a.size), n_batches, out.ctypes.data_as(_i32p)))
+    return out[: a.size].tolist()
+
+
+class Scheduler:
+    """Thin wrapper of pipemax_sched_t (argument marshalling only)."""
+
+    def __init__(self, *, alpha_s, beta_s, delta_s, link_tokens_per_s, n_batches, window=8, steady_rel_range=0.05,
+                 max_refine_steps=16, refine_tol_s=None, static_budget_tokens=0, page_tokens=16):
+        self.cfg = SchedConfig(alpha_s=alpha_s, beta_s=beta_s, delta_s=delta_s, link_tokens_per_s=link_tokens_per_s,
+                               steady_rel_range=steady_rel_range,
+                               refine_tol_s=alpha_s / 2 if refine_tol_s is None else refine_tol_s,
+                               static_budget_tokens=static_budget_tokens, window=window,
+                               max_refine_steps=max_refine_steps, n_batches=n_batches, page_tokens=page_tokens)
+        self._h = _vp()
+        self._cap = 1
+        _check(_lib.pipemax_sched_create(C.byref(self.cfg), C.byref(self._h)))
+
+    def destroy(self):
+        if self._h:
+            _check(_lib.pipemax_sched_destroy(self._h))
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def predict(self, b: int, total_len: int) -> float:
+        return float(_lib.pipemax_sched_predict(self._h, int(b), int(total_len)))
+
+    def budget(self, t_hat_s: float) -> int:
+        return int(_lib.pipemax_sched_budget(self._h, float(t_hat_s)))
+
+    def observe(self, budget_tokens: int) -> bool:
+        rc = _lib.pipemax_sched_observe(self._h, int(budget_tokens))
+        _check(min(rc, 0))
+        return bool(rc)
+
+    def refine(self, lens, budget: int, gap_s: float, sel):
+        a, p = _i32(lens)
+        buf = np.empty(max(a.size, 1), dtype=np.int32)
+        buf[: len(sel)] = sel
+        n, ex = C.c_int32(len(sel)), C.c_int32(0)
+        _check(_lib.pipemax_sched_refine(self._h, p, int(a.size), int(budget), float(gap_s),
+                                         buf.ctypes.data_as(_i32p), C.byref(n), C.byref(ex)))
+        return buf[: n.value].tolist(), ex.value
+
+    def set_batch(self, mb: int, lens, resident):
+        a, p = _i32(lens)
+        r, q = _i32(resident)
+        assert a.size == r.size
+        _check(_lib.pipemax_sched_set_batch(self._h, mb, int(a.size), p, q))
+        self._cap = max(self._cap, int(a.size))
+
+    def set_gpu_pages_free(self, pages: int):
+        _check(_lib.pipemax_sched_set_gpu_pages_free(self._h, int(pages)))
+
+    def attach(self, stage: "Stage"):
+        _check(_lib.pipemax_sched_attach(self._h, stage._h))
+        self._cap = max(self._cap, int(stage.cfg.max_seqs_per_mb))
+
+    def _result(self, it, e, p, v):
+        d = {n: getattr(it, n) for n, _ in it._fields_}
+        d["exec"] = e[: it.n_exec].tolist()
+        d["prefetch"] = p[: it.n_prefetch].tolist()
+        d["evict"] = v[: it.n_evict].tolist()
+        return d
+
+    def plan(self, t: int) -> dict:
+        it = SchedIter()
+        e, p, v = (np.empty(self._cap, dtype=np.int32) for _ in range(3))
+        _check(_lib.pipemax_sched_plan(self._h, int(t), C.byref(it), e.ctypes.data_as(_i32p),
+                                       p.ctypes.data_as(_i32p), v.ctypes.data_as(_i32p)))
+        return self._result(it, e, p, v)
+
+    def iterate(self, stage: "Stage", t: int, hidden_in_ptr: int, hidden_out_ptr: int, stream_ptr: int = 0) -> dict:
+        it = SchedIter()
+        e, p, v = (np.empty(self._cap, dtype=np.int32) for _ in range(3))
+        _check(_lib.pipemax_sched_iterate(self._h, stage._h, int(t), _vp(hidden_in_ptr), _vp(hidden_out_ptr),
+                                          _vp(stream_ptr) if stream_ptr else None, C.byref(it),
+                                          e.ctypes.data_as(_i32p), p.ctypes.data_as(_i32p), v.ctypes.data_as(_i32p)))
+        return self._result(it, e, p, v)

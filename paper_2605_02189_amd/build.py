@@ -9,13 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipemax.so")
-SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip"]
-FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fopenmp",
-    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
-    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-]
+SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip", "scheduler.cpp"]
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+FLAGS = ["--offload-arch=gfx950", "-fopenmp", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *COMMON]
+HOST_FLAGS = ["-ffp-contract=off", *COMMON]     # host-only sources (.cpp): no device pass
 
 
 def build(verbose: bool = False) -> str:
@@ -25,8 +23,8 @@ def build(verbose: bool = False) -> str:
     os.makedirs(bdir, exist_ok=True)
     objs, procs = [], []
     for src in SOURCES:
-        obj = os.path.join(bdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(bdir, os.path.splitext(src)[0] + ".o")
+        cmd = [hipcc, *(FLAGS if src.endswith(".hip") else HOST_FLAGS), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -1392,6 +1392,20 @@ int pipemax_debug_set_delays(pipemax_stage_t* st, int h2d_us, int d2h_us, int wo
   return PIPEMAX_OK;
 }
 
+int pipemax_get_config(pipemax_stage_t* st, pipemax_config_t* out) {
+  if (!st || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  *out = st->cfg;
+  return PIPEMAX_OK;
+}
+
+int pipemax_mb_size(pipemax_stage_t* st, int mb, int32_t* n_seqs) {
+  int rc = check_mb(st, mb, false);
+  if (rc) return rc;
+  if (!n_seqs) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  *n_seqs = st->mbs[mb].defined ? st->mbs[mb].b : 0;
+  return PIPEMAX_OK;
+}
+
 int pipemax_get_ctx_lens(pipemax_stage_t* st, int mb, int32_t* out) {
   int rc = check_mb(st, mb, true);
   if (rc) return rc;
