@@ -26,8 +26,9 @@ class StageRunner:
     def __init__(self, shape: StageShape, syn: SynthInputs, *, sigma: float = 1.0, steps: int | None = None,
                  flags: int = 0, device: int = 0, n_microbatches: int | None = None,
                  ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False,
-                 wb_layers_per_copy: int = 0, reserve: bool = True):
+                 wb_layers_per_copy: int = 0, reserve: bool = True, gpu_pages: int | None = None):
         self.shape, self.syn = shape, syn
+        pool_override = gpu_pages
         self.n = n_microbatches or shape.n_microbatches
         self.b = shape.seqs_per_mb
         self.steps = steps if steps is not None else shape.decode_steps
@@ -46,6 +47,8 @@ class StageRunner:
         gpu_pages = resident_pages + sum(stream_pages[:2]) + 8          # two arenas for the streamed part
         if gpu_pool_all_resident:                                       # room to keep everything on the GPU
             gpu_pages = host_pages + 8
+        if pool_override is not None:                                   # caller-chosen GPU pool (scheduler runs)
+            gpu_pages = int(pool_override)
         max_ctx = int(max(int(c.max()) for c in self.ctx0.values())) + steps_per_mb + 1
         self.stage = pm.Stage(
             n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
