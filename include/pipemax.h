@@ -213,6 +213,23 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
 int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n,
                              const void* hidden_in, void* hidden_out, void* hip_stream);
 
+/* Prefill (Sec. 3.1.1: the KV cache produced by prefill is offloaded to CPU memory asynchronously;
+ * Sec. 3.4.2: per-layer offload and CPU re-layout): runs the stage over n_tokens NEW tokens of one
+ * sequence, at positions L .. L + n_tokens - 1 where L is the sequence's current length (0 for a fresh
+ * request; a longer prompt may be fed in several calls).  Token t attends to all cached tokens and to
+ * the new tokens up to and including itself (causal).  hidden_in / hidden_out: device pointers,
+ * [n_tokens][hidden] row-major in the stage's element type (may alias).  The tokens are processed in
+ * chunks of at most max_seqs_per_mb rows; each chunk is one pass of the same kernels as a decode step
+ * (more than 64 rows take the large-tile GEMM path), appends its K,V to the sequence's GPU pages and
+ * hands them to the write-back stream and the host re-layout worker exactly like a decode step, so the
+ * host replica is complete once the work has drained and pipemax_evict_kv frees the GPU pages without
+ * a copy.  The sequence must not be HOST-resident (call pipemax_prefetch_kv first, also for an empty
+ * sequence).  Afterwards its length is L + n_tokens.  n_tokens == 0 is a successful no-op.
+ * Errors: ERR_ARG, ERR_NOT_RESIDENT, ERR_STATE (max_ctx), ERR_POOL_EXHAUSTED (checked for the whole
+ * call before anything is enqueued), ERR_HIP.                                                        */
+int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const void* hidden_in,
+                    void* hidden_out, void* hip_stream);
+
 /* Evict (Sec. 3.3.2, "overwriting KV cache blocks associated with the inactive batch D_k"):
  * releases the GPU pages of the named sequences (NULL = all of mb).  No bulk copy is made: the
  * host replica is kept current by the per-layer write-back.  Later prefetches into the freed

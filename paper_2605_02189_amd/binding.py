@@ -51,7 +51,7 @@ HOST, INFLIGHT, GPU = 0, 1, 2
 SYMBOLS = [
     "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
-    "pipemax_decode_step", "pipemax_decode_step_seqs", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
+    "pipemax_decode_step", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
     "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_config", "pipemax_mb_size",
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
@@ -145,6 +145,7 @@ _sig = {
     "pipemax_prefetch_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
     "pipemax_decode_step": (C.c_int, [_vp, C.c_int, _vp, _vp, _vp]),
     "pipemax_decode_step_seqs": (C.c_int, [_vp, C.c_int, _i32p, C.c_int, _vp, _vp, _vp]),
+    "pipemax_prefill": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp]),
     "pipemax_evict_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
     "pipemax_sync": (C.c_int, [_vp]),
     "pipemax_get_stats": (C.c_int, [_vp, C.POINTER(Stats)]),
@@ -274,6 +275,11 @@ class Stage:
         _check(_lib.pipemax_decode_step_seqs(self._h, mb, a.ctypes.data_as(_i32p), int(a.size),
                                              _vp(hidden_in_ptr), _vp(hidden_out_ptr),
                                              _vp(stream_ptr) if stream_ptr else None))
+
+    def prefill(self, mb, seq, n_tokens, hidden_in_ptr: int, hidden_out_ptr: int, stream_ptr: int = 0):
+        """n_tokens new tokens of one sequence; hidden tensors are [n_tokens][hidden] on the device."""
+        _check(_lib.pipemax_prefill(self._h, mb, seq, n_tokens, _vp(hidden_in_ptr), _vp(hidden_out_ptr),
+                                    _vp(stream_ptr) if stream_ptr else None))
 
     def evict_kv(self, mb, seq_ids=None):
         p, n = _ids(seq_ids)

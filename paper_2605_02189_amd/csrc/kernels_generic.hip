@@ -123,10 +123,6 @@ __global__ void k_rope_append(Dims D, int layer, const float* qkv, const float2*
   int phys = table[(int64_t)i * D.max_pages + pos / kPageTokens];
   int slot = pos % kPageTokens;
   T* sub = pool + (int64_t)phys * D.page_elems + sub_block_off(D.Hkv, D.d, layer, head, kv);
-  if (slot == 0) {      // first token of a fresh page: clear the other slots of this sub-block
-    for (int e = j; e < kPageTokens * D.d; e += blockDim.x) stf(sub + e, 0.f);
-    __syncthreads();
-  }
   if (kv == 0) {
     stf(sub + k_sub_idx(slot, j), lo);
     stf(sub + k_sub_idx(slot, j + half), hi);

@@ -126,9 +126,10 @@ struct pipemax_stage {
   uint16_t *m_xn_t = nullptr, *m_q = nullptr, *m_attn_t = nullptr, *m_act_t = nullptr;
   float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr, *m_ssq = nullptr;
   int *m_cnt_gemm = nullptr, *m_cnt_attn = nullptr;
-  bool fused = false;   // b <= 64: consumers fused into the GEMM epilogues
+  // up to 64 rows: consumers fused into the GEMM epilogues (plans f_*); more: large-tile GEMMs with
+  // separate element-wise kernels (plans p_*, present when max_seqs_per_mb > 64)
   int attn_cp_override = 0;   // PIPEMAX_ATTN_CHUNK_PAGES: tuning override of the attention chunk size
-  GemmPlan p_qkv, p_o, p_gu, p_d;
+  GemmPlan p_qkv, p_o, p_gu, p_d, f_qkv, f_o, f_gu, f_d;
   int nch_alloc = 1;
   float* layer_out = nullptr;
   int last_b = 0;
@@ -610,23 +611,27 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     PMX_TRY(dev_alloc(st, &st->g_act, (size_t)maxb * F));
     PMX_TRY(dev_alloc(st, &st->g_scores, (size_t)maxb * c.n_q_heads * D.max_ctx_pad));
   } else {
-    if (maxb <= 64) {
-      st->p_qkv = plan_gemm_skinny(D.Nqkv, h, false);
-      st->p_o = plan_gemm_skinny(h, nq, false);
-      st->p_gu = plan_gemm_skinny(2 * F, h, true);
-      st->p_d = plan_gemm_skinny(h, F, false);
-    } else {
+    st->f_qkv = plan_gemm_skinny(D.Nqkv, h, false);
+    st->f_o = plan_gemm_skinny(h, nq, false);
+    st->f_gu = plan_gemm_skinny(2 * F, h, true);
+    st->f_d = plan_gemm_skinny(h, F, false);
+    const int fpad = std::min(mpad, 64);
+    size_t part = 0;
+    part = std::max(part, (size_t)st->f_qkv.split * fpad * D.Nqkv);
+    part = std::max(part, (size_t)st->f_o.split * fpad * h);
+    part = std::max(part, (size_t)st->f_gu.split * fpad * 2 * F);
+    part = std::max(part, (size_t)st->f_d.split * fpad * h);
+    if (maxb > 64) {
       auto plan = [&](int N, int K) { return (N % 256 == 0) ? plan_gemm_large(N, K) : plan_gemm(N, K); };
       st->p_qkv = plan(D.Nqkv, h);
       st->p_o = plan(h, nq);
       st->p_gu = plan(2 * F, h);
       st->p_d = plan(h, F);
+      part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
+      part = std::max(part, (size_t)st->p_o.split * mpad * h);
+      part = std::max(part, (size_t)st->p_gu.split * mpad * 2 * F);
+      part = std::max(part, (size_t)st->p_d.split * mpad * h);
     }
-    size_t part = 0;
-    part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
-    part = std::max(part, (size_t)st->p_o.split * mpad * h);
-    part = std::max(part, (size_t)st->p_gu.split * mpad * 2 * F);
-    part = std::max(part, (size_t)st->p_d.split * mpad * h);
     PMX_TRY(dev_alloc(st, &st->m_part, part));
     PMX_TRY(dev_alloc(st, &st->m_xn_t, (size_t)mtile * h));
     PMX_TRY(dev_alloc(st, &st->m_q, (size_t)maxb * nq));
@@ -638,7 +643,6 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     st->nch_alloc = (D.max_pages + 7) / 8;
     PMX_TRY(dev_alloc(st, &st->m_part_o, (size_t)maxb * c.n_q_heads * st->nch_alloc * 128));
     PMX_TRY(dev_alloc(st, &st->m_part_ml, (size_t)maxb * c.n_q_heads * st->nch_alloc * 2));
-    st->fused = (maxb <= 64);
     const size_t n_cnt = (size_t)std::max(D.Nqkv, h) / 64 + 1;
     PMX_TRY(dev_alloc(st, &st->m_cnt_gemm, n_cnt));
     PMX_TRY(dev_alloc(st, &st->m_cnt_attn, (size_t)maxb * c.n_kv_heads));
@@ -950,10 +954,16 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
 
 // ---- the decode step ----------------------------------------------------------------------------------
 namespace {
-// One decode step over the rows `sel` (sequence indices of mb, distinct, in row order).  `subset` says that
-// the rows are a caller-chosen list: the device copy of the block table is then rebuilt for this step.
-int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool subset, const void* hidden_in,
-                void* hidden_out, void* hip_stream) {
+// One pass of the stage over a list of rows.  Row r is one new token: of sequence sel[r] at position
+// pos0[r] (= the number of tokens cached before it).  A decode step has one row per sequence at its current
+// length; a prefill chunk has consecutive positions of one sequence.  Rows of the same sequence must be
+// consecutive and in ascending position, continuing from the sequence's length.  `subset` says that the
+// rows are not simply "every sequence of mb": the device copy of the block table is then rebuilt.
+// The kernels see rows only: block-table row r holds the pages of row r's sequence and ctx[r] its position;
+// every row's K,V is appended before any row's attention runs and row r attends to positions <= pos0[r],
+// which is causal attention within a chunk.
+int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const std::vector<int>& pos0, bool subset,
+                const void* hidden_in, void* hidden_out, void* hip_stream) {
   const double t_enter = now_s();
   int rc;
   if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
@@ -965,15 +975,18 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
   for (int i : sel)
     if (M.seq[i].state == ST_HOST)
       PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", i, mb);
-  for (int i : sel) {
-    const SeqState& S = M.seq[i];
-    if (S.len + 1 > st->cfg.max_ctx)
-      PMX_FAIL(PIPEMAX_ERR_STATE, "sequence %d of micro-batch %d is at max_ctx %d", i, mb, st->cfg.max_ctx);
-    if (S.len % kPageTokens == 0) {
+  for (int r = 0; r < b; ++r) {
+    const SeqState& S = M.seq[sel[r]];
+    if (pos0[r] + 1 > st->cfg.max_ctx)
+      PMX_FAIL(PIPEMAX_ERR_STATE, "sequence %d of micro-batch %d is at max_ctx %d", sel[r], mb, st->cfg.max_ctx);
+    if (pos0[r] % kPageTokens == 0) {
       ++grow;
-      if (S.host_reserved.empty()) ++grow_host;
+      // reserved host pages of the sequence are used first; rows of one sequence are consecutive
+      int before = 0;
+      for (int q = r - 1; q >= 0 && sel[q] == sel[r]; --q) before += (pos0[q] % kPageTokens == 0);
+      if (before >= (int)S.host_reserved.size()) ++grow_host;
     }
-    max_len = std::max(max_len, S.len);
+    max_len = std::max(max_len, pos0[r]);
   }
   if (grow > st->gpu_pages->free_count() || grow_host > st->host_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", grow,
@@ -987,7 +1000,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
   auto where = std::make_shared<std::vector<std::pair<int32_t, int>>>(b);
   for (int r = 0; r < b; ++r) {
     SeqState& S = M.seq[sel[r]];
-    if (S.len % kPageTokens == 0) {
+    if (pos0[r] % kPageTokens == 0) {
       int32_t gp, hp;
       st->gpu_pages->alloc(1, &gp);
       if (!S.host_reserved.empty()) {
@@ -1000,7 +1013,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
       S.host.push_back(hp);
       M.table_dirty = true;
     }
-    (*where)[r] = {S.host[S.len / kPageTokens], S.len % kPageTokens};
+    (*where)[r] = {S.host[pos0[r] / kPageTokens], pos0[r] % kPageTokens};
   }
 
   // ---- stream dependencies -----------------------------------------------------------------------
@@ -1028,11 +1041,11 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
     // row order for the attention grid: longest context first (ties by row)
     int32_t* ord = ht + (size_t)maxb * D.max_pages;
     for (int r2 = 0; r2 < b; ++r2) ord[r2] = r2;
-    std::stable_sort(ord, ord + b, [&](int a, int c2) { return M.seq[sel[a]].len > M.seq[sel[c2]].len; });
+    std::stable_sort(ord, ord + b, [&](int a, int c2) { return pos0[a] > pos0[c2]; });
     std::fill(ord + b, ord + maxb, 0);
     // lengths before this step; the last kernel of a step advances the device copy
     int32_t* hl = ord + maxb;
-    for (int r2 = 0; r2 < b; ++r2) hl[r2] = M.seq[sel[r2]].len;
+    for (int r2 = 0; r2 < b; ++r2) hl[r2] = pos0[r2];
     PMX_HIP(hipMemcpyAsync(M.d_table, ht, ((size_t)maxb * D.max_pages + maxb + b) * sizeof(int32_t),
                            hipMemcpyHostToDevice, cs));
     PMX_HIP(hipEventRecord(st->ev_table[r], cs));
@@ -1158,7 +1171,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
                       M.d_table + (size_t)st->cfg.max_seqs_per_mb * D.max_pages);
       st->tend(cs);
     };
-    if (st->fused) {
+    if (b <= 64) {
       // 5 launches per layer: every element-wise consumer runs in the epilogue of the GEMM before it
       const int nb = D.h / 64;
       st->tbegin(PIPEMAX_K_NORM, cs);
@@ -1172,24 +1185,24 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, bool s
         st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
         mfma::gemm_qkv_rope_append(cs, D, l, b, st->m_xn_t, (const uint16_t*)L.wqkv, st->m_part, st->m_cnt_gemm,
                                    st->m_ssq, nb, st->rope_cs, M.d_ctx, M.d_table, (uint16_t*)st->gpu_pool, stage_l,
-                                   st->m_q, st->p_qkv.split, st->p_qkv.nwk);
+                                   st->m_q, st->f_qkv.split, st->f_qkv.nwk);
         st->tend(cs);
         int rc2 = after_append(l);
         if (rc2) return rc2;
         run_attention(l);
         st->tbegin(PIPEMAX_K_GEMM_O, cs);
         mfma::gemm_resid(cs, b, nq, D.h, st->m_attn_t, (const uint16_t*)L.wo, st->m_part, st->m_cnt_gemm, st->x,
-                         (const uint16_t*)L.g2, st->m_xn_t, st->m_ssq, nullptr, nullptr, st->p_o.split, st->p_o.nwk);
+                         (const uint16_t*)L.g2, st->m_xn_t, st->m_ssq, nullptr, nullptr, st->f_o.split, st->f_o.nwk);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
         mfma::gemm_swiglu(cs, b, D.h, D.F, D.eps, st->m_xn_t, (const uint16_t*)L.wgu, st->m_ssq, nb, st->m_act_t,
-                          st->p_gu.nwk);
+                          st->f_gu.nwk);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
         mfma::gemm_resid(cs, b, D.F, D.h, st->m_act_t, (const uint16_t*)L.wd, st->m_part, st->m_cnt_gemm, st->x,
                          last ? nullptr : (const uint16_t*)st->w[l + 1].g1, st->m_xn_t, last ? nullptr : st->m_ssq,
-                         last ? (uint16_t*)hidden_out : nullptr, last ? M.d_ctx : nullptr, st->p_d.split,
-                         st->p_d.nwk);
+                         last ? (uint16_t*)hidden_out : nullptr, last ? M.d_ctx : nullptr, st->f_d.split,
+                         st->f_d.nwk);
         st->tend(cs);
         if (st->layer_out)
           PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)l * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
@@ -1272,9 +1285,12 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
                         void* hip_stream) {
   int rc = check_mb(st, mb, true);
   if (rc) return rc;
-  std::vector<int> sel(st->mbs[mb].b);
-  for (int i = 0; i < (int)sel.size(); ++i) sel[i] = i;
-  return decode_rows(st, mb, sel, false, hidden_in, hidden_out, hip_stream);
+  std::vector<int> sel(st->mbs[mb].b), pos(st->mbs[mb].b);
+  for (int i = 0; i < (int)sel.size(); ++i) {
+    sel[i] = i;
+    pos[i] = st->mbs[mb].seq[i].len;
+  }
+  return decode_rows(st, mb, sel, pos, false, hidden_in, hidden_out, hip_stream);
 }
 
 int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n, const void* hidden_in,
@@ -1283,15 +1299,49 @@ int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids
   if (rc) return rc;
   if (!seq_ids && n != 0) PMX_FAIL(PIPEMAX_ERR_ARG, "null sequence list");
   if (n < 0 || n > st->mbs[mb].b) PMX_FAIL(PIPEMAX_ERR_ARG, "%d rows for a micro-batch of %d", n, st->mbs[mb].b);
-  std::vector<int> sel;
+  std::vector<int> sel, pos;
   std::vector<char> seen(st->mbs[mb].b, 0);
   for (int k = 0; k < n; ++k) {
     if (seq_ids[k] < 0 || seq_ids[k] >= st->mbs[mb].b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", seq_ids[k]);
     if (seen[seq_ids[k]]) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d listed twice", seq_ids[k]);
     seen[seq_ids[k]] = 1;
     sel.push_back(seq_ids[k]);
+    pos.push_back(st->mbs[mb].seq[seq_ids[k]].len);
   }
-  return decode_rows(st, mb, sel, true, hidden_in, hidden_out, hip_stream);
+  return decode_rows(st, mb, sel, pos, true, hidden_in, hidden_out, hip_stream);
+}
+
+int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const void* hidden_in, void* hidden_out,
+                    void* hip_stream) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  if (seq < 0 || seq >= M.b) PMX_FAIL(PIPEMAX_ERR_ARG, "sequence %d out of range", seq);
+  if (n_tokens < 0) PMX_FAIL(PIPEMAX_ERR_ARG, "negative token count");
+  if (n_tokens == 0) return PIPEMAX_OK;
+  if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
+  const SeqState& S = M.seq[seq];
+  if (S.state == ST_HOST)
+    PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", seq, mb);
+  if (S.len + n_tokens > st->cfg.max_ctx)
+    PMX_FAIL(PIPEMAX_ERR_STATE, "%d + %d tokens exceed max_ctx %d", S.len, n_tokens, st->cfg.max_ctx);
+  // all pages of the call are checked up front, so that a later chunk cannot fail for lack of pages
+  const int have = (int)S.host.size(), want = (S.len + n_tokens + kPageTokens - 1) / kPageTokens;
+  const int new_pages = want - have, new_host = std::max(0, new_pages - (int)S.host_reserved.size());
+  if (new_pages > st->gpu_pages->free_count() || new_host > st->host_pages->free_count())
+    PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", new_pages,
+             st->gpu_pages->free_count(), st->host_pages->free_count());
+  const int chunk = st->cfg.max_seqs_per_mb;
+  const size_t row_bytes = (size_t)st->cfg.hidden * st->esz;
+  for (int t0 = 0; t0 < n_tokens; t0 += chunk) {
+    const int rows = std::min(chunk, n_tokens - t0);
+    std::vector<int> sel(rows, seq), pos(rows);
+    for (int r = 0; r < rows; ++r) pos[r] = M.seq[seq].len + r;
+    rc = decode_rows(st, mb, sel, pos, true, (const char*)hidden_in + (size_t)t0 * row_bytes,
+                     (char*)hidden_out + (size_t)t0 * row_bytes, hip_stream);
+    if (rc) return rc;
+  }
+  return PIPEMAX_OK;
 }
 
 int pipemax_sync(pipemax_stage_t* st) {
