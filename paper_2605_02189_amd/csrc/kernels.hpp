@@ -65,6 +65,11 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);
 
 constexpr int kAttnWaves = 4;   // waves per attention work-group
+// Causal attention of a prefill chunk: `rows` consecutive new tokens of one sequence starting at position
+// pos0, K,V already appended; table = the sequence's page ids.  (pos0 + rows) tokens must fit 64 * kAttnWaves
+// pages.  Output rows are written A-tiled like the decode kernel's.
+void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int pos0, const uint16_t* q,
+                       const uint16_t* pool, const int* table, uint16_t* out_t);
 // Split-K paged GQA decode attention.  chunk_pages = target pages per work-group (<= 64 * kAttnWaves), max_chunks = grid
 // extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
 // (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)

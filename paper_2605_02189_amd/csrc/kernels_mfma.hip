@@ -966,6 +966,152 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
 }
 
 // =================================================================================================
+// Causal attention of a prefill chunk: R rows = R consecutive new tokens of ONE sequence, row r at
+// position pos0 + r, whose K,V are already in the sequence's pages.
+//   grid (row tiles of 16, longest first; query heads), block NW waves.  The 16 columns of the MFMA tiles are
+//   16 query rows of one head (in the decode kernel they are the heads of a group); the waves take the pages
+//   of the tile's visible context round-robin and merge once through LDS, exactly as in the decode kernel.
+//   Column n sees tokens <= pos0 + r0 + n.  At most 64 * NW pages (the host checks).
+// =================================================================================================
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_prefill(Dims D, int layer, const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ pool,
+                                                          const int* __restrict__ table, int pos0, int R,
+                                                          uint16_t* __restrict__ out_t) {
+  __shared__ float so[NW][16][kORow];
+  __shared__ float sm[NW][16], sl[NW][16];
+  const int tile = (int)gridDim.x - 1 - (int)blockIdx.x, hq = blockIdx.y, c = hq / D.G;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
+  const int r0 = tile * 16;
+  const int row = min(r0 + n, R - 1);                     // rows past the chunk repeat its last row (not written)
+  const int n_vis = pos0 + row + 1;                       // tokens this column sees
+  const int n_total = pos0 + R;                           // tokens the pages hold
+  const int npages = (pos0 + min(r0 + 15, R - 1)) / 16 + 1;
+  int my_page = 0;
+  {
+    const int pidx = w + NW * lane;                       // this wave's pages: w, w + NW, ...
+    if (pidx < npages) my_page = table[pidx];
+  }
+  bf16x8 qf[4];
+  {
+    const uint16_t* qrow = q + ((int64_t)row * D.Hq + hq) * 128 + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + kk * 32));
+  }
+  const int npw = (npages > w) ? ((npages - w + NW - 1) / NW) : 0;
+  const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
+  const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 oacc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 kf[2][4], vf[2][4];
+  auto load_page = [&](int t, uint4* kd, uint4* vd) {
+    const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
+    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
+  };
+  if (npw > 0) load_page(0, kf[0], vf[0]);
+  for (int t0 = 0; t0 < npw; t0 += 2) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int t = t0 + r;
+      if (t < npw) {
+        if (t + 1 < npw) load_page(t + 1, kf[r ^ 1], vf[r ^ 1]);
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[r][kk]), qf[kk],
+                                                         sacc, 0, 0, 0);
+        const int tok0 = ((w + NW * t) << 4) + 4 * g;
+        float sv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sv[e] = (tok0 + e < n_vis) ? sacc[e] * scale_log2 : -INFINITY;
+        float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        // a column may see nothing of this wave's pages so far: keep the exponents finite
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = exp2f(m_run - m_ref);
+        float pr[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pr[e] = exp2f(sv[e] - m_ref);
+        float lsum = (pr[0] + pr[1]) + (pr[2] + pr[3]);
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        l_run = l_run * alpha + lsum;
+        m_run = m_new;
+        const uint2 pp = make_uint2(pack2(pr[0], pr[1]), pack2(pr[2], pr[3]));
+        const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+        // slots past the last appended token hold whatever the page held before (0 * NaN is NaN)
+        uint32_t vm0 = 0xffffffffu, vm1 = 0xffffffffu;
+        if (tok0 + 3 >= n_total) {
+          const int valid = n_total - tok0;
+          vm0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+          vm1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].x & vm0, vf[r][jj].y & vm1));
+          const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].z & vm0, vf[r][jj].w & vm1));
+          oacc[2 * jj] = oacc[2 * jj] * alpha;
+          oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
+          oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
+          oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- merge the NW waves through LDS (wave 0 always holds page 0, which every column sees) ---------
+  if (g == 0) { sm[w][n] = m_run; sl[w][n] = l_run; }
+  __syncthreads();
+  float m_blk = sm[0][n];
+#pragma unroll
+  for (int ww = 1; ww < NW; ++ww) m_blk = fmaxf(m_blk, sm[ww][n]);
+  {
+    const float f = exp2f(m_run - m_blk);          // 0 for a wave that saw nothing of this column
+    float* dst = &so[w][n][4 * g];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      f32x4 v = oacc[dt] * f;
+      *(float4*)(dst + dt * 16) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+  __syncthreads();
+  // thread (column nn8, 8 consecutive output dimensions): 16 columns x 16 groups = 256 threads
+  const int KTo = D.Hq * 128 / 16;
+  for (int e8 = tid; e8 < 256; e8 += NW * 64) {
+    const int nn8 = e8 >> 4, dd8 = (e8 & 15) * 8;
+    if (r0 + nn8 >= R) continue;
+    float m8 = sm[0][nn8];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) m8 = fmaxf(m8, sm[ww][nn8]);
+    float l8 = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) l8 += sl[ww][nn8] * exp2f(sm[ww][nn8] - m8);
+    float o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {
+      const float* src = &so[ww][nn8][dd8];
+      const float4 a = *(const float4*)src, b2 = *(const float4*)(src + 4);
+      o8[0] += a.x; o8[1] += a.y; o8[2] += a.z; o8[3] += a.w;
+      o8[4] += b2.x; o8[5] += b2.y; o8[6] += b2.z; o8[7] += b2.w;
+    }
+    const float inv = 1.0f / l8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o8[e] *= inv;
+    *(uint4*)(out_t + a_tiled_idx(KTo, r0 + nn8, hq * 128 + dd8)) = pack8(o8);
+  }
+}
+
+// =================================================================================================
 // SwiGLU over the split-K partials of the gate/up GEMM -> A-tiled bf16 input of the down GEMM
 // =================================================================================================
 __global__ __launch_bounds__(256) void k_swiglu(int b, int F, const float* part, int n_split,
@@ -1075,6 +1221,13 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out) {
   hipLaunchKernelGGL(k_rope_append, dim3(b, D.Hq + 2 * D.Hkv), dim3(64), 0, s, D, layer, part, n_split,
                      split_stride, cs, ctx, table, pool, staging, q_out);
+}
+
+void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int pos0, const uint16_t* q,
+                       const uint16_t* pool, const int* table, uint16_t* out_t) {
+  constexpr int NW = kAttnWaves;
+  hipLaunchKernelGGL((k_attn_prefill<NW>), dim3((rows + 15) / 16, D.Hq), dim3(NW * 64), 0, s, D, layer, q, pool,
+                     table, pos0, rows, out_t);
 }
 
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,

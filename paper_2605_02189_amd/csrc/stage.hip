@@ -288,9 +288,14 @@ void worker_main(pipemax_stage* st) {
     if (int us = st->dly_worker.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
     const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
-    for (int layer = job.layer; layer < job.layer + job.n_layers; ++layer) {
+    // rows write disjoint token slots, so a prefill chunk (hundreds of rows) is spread over the host cores
+    const int n_items = job.n_layers * job.b;
+#pragma omp parallel for schedule(static) if (n_items >= 1024)
+    for (int item = 0; item < n_items; ++item) {
+      const int layer = job.layer + item / job.b;
       const char* src = (const char*)st->h_stage[job.slot] + (size_t)layer * layer_elems * st->esz;
-      for (int i = 0; i < job.b; ++i) {
+      {
+        const int i = item % job.b;
         const auto& wh = (*job.where)[i];
         char* page = st->host_page_ptr(wh.first);
         const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
@@ -963,7 +968,7 @@ namespace {
 // every row's K,V is appended before any row's attention runs and row r attends to positions <= pos0[r],
 // which is causal attention within a chunk.
 int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const std::vector<int>& pos0, bool subset,
-                const void* hidden_in, void* hidden_out, void* hip_stream) {
+                const void* hidden_in, void* hidden_out, void* hip_stream, bool one_seq_chunk = false) {
   const double t_enter = now_s();
   int rc;
   if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
@@ -1164,8 +1169,13 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
       mfma::gemm(cs, Xt, (const uint16_t*)W, st->m_part, b, K, N, p.split, p.wn);
     };
+    // a prefill chunk (consecutive positions of one sequence) has its own kernel: 16 rows share every K,V load
+    const bool chunk_kernel = one_seq_chunk && b > 1 && npages_max <= 64 * mfma::kAttnWaves;
     auto run_attention = [&](int l) {
       st->tbegin(PIPEMAX_K_ATTN, cs);
+      if (chunk_kernel)
+        mfma::attention_prefill(cs, D, l, b, pos0[0], st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, st->m_attn_t);
+      else
       mfma::attention(cs, D, l, b, st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, st->m_part_o,
                       st->m_part_ml, CP, nch, st->m_cnt_attn, st->m_attn_t,
                       M.d_table + (size_t)st->cfg.max_seqs_per_mb * D.max_pages);
@@ -1338,7 +1348,7 @@ int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const vo
     std::vector<int> sel(rows, seq), pos(rows);
     for (int r = 0; r < rows; ++r) pos[r] = M.seq[seq].len + r;
     rc = decode_rows(st, mb, sel, pos, true, (const char*)hidden_in + (size_t)t0 * row_bytes,
-                     (char*)hidden_out + (size_t)t0 * row_bytes, hip_stream);
+                     (char*)hidden_out + (size_t)t0 * row_bytes, hip_stream, true);
     if (rc) return rc;
   }
   return PIPEMAX_OK;

@@ -29,7 +29,7 @@ def _oracle_prefill(orc, syn, mb, seq, x):
     return out
 
 
-@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "generic_fp32"])
+@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_long_context", "generic_fp32"])
 def test_prefill_matches_token_by_token_oracle(case):
     import torch
     assert torch.cuda.is_available()
@@ -40,17 +40,19 @@ def test_prefill_matches_token_by_token_oracle(case):
         shape = CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=6)
         tol, plan = 1e-5, [(0, 21), (1, 19), (0, 8)]
     else:
-        b = 20 if case == "mfma_fused_chunks" else 70
+        b = 70 if case == "mfma_wide_chunks" else 20
         shape = StageShape(name=case, n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2816,
                            dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
                            decode_steps=1)
         tol = 1e-2
         # (sequence, new tokens): several chunks each; sequence 1 continues an existing prefix
         plan = [(0, 45), (1, 30), (0, 17)] if b == 20 else [(0, 150), (1, 75)]
+        if case == "mfma_long_context":                    # beyond the chunk kernel's 256 pages: per-row kernel
+            plan = [(1, 30), (0, 5)]
     syn = SynthInputs(shape, seed=31, pool_elems=1 << 23, gain_jitter=0.1)
     ctx = {0: syn.ctx_lens(0).copy()}
     ctx[0][0] = 0                                          # a fresh request
-    ctx[0][1] = 37                                         # a prefix ending inside a page
+    ctx[0][1] = 4085 if case == "mfma_long_context" else 37    # a prefix ending inside a page
     total_new = sum(n for _, n in plan)
     runner = StageRunner(shape, syn, sigma=0.0, steps=total_new + 4, ctx_lens=ctx, gpu_pool_all_resident=True).load()
     st = runner.stage
