@@ -59,6 +59,13 @@ SYMBOLS = [
     "pipemax_plan_copy_runs", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
     "pipemax_pool_free", "pipemax_pool_free_count",
 ]
+# every symbol include/pipemax_xfer.h declares
+XFER_SYMBOLS = [
+    "pipemax_xfer_create", "pipemax_xfer_destroy", "pipemax_xfer_submit", "pipemax_xfer_wait", "pipemax_xfer_poll",
+    "pipemax_xfer_stream_wait", "pipemax_xfer_drain", "pipemax_xfer_get_stats", "pipemax_xfer_reset_stats",
+    "pipemax_xfer_get_log", "pipemax_xfer_debug_set_host_us_per_mib", "pipemax_xfer_debug_pause",
+]
+XFER_URGENT, XFER_BULK, XFER_H2D, XFER_D2H = 0, 1, 0, 1
 # every symbol include/pipemax_sched.h declares
 SCHED_SYMBOLS = [
     "pipemax_sched_create", "pipemax_sched_destroy", "pipemax_sched_predict", "pipemax_sched_budget",
@@ -101,6 +108,21 @@ class Stats(C.Structure):
 _vp, _i32p = C.c_void_p, C.POINTER(C.c_int32)
 
 
+class XferConfig(C.Structure):
+    _fields_ = [("device", C.c_int32), ("max_inflight_bulk", C.c_int32), ("chunk_bytes", C.c_uint64),
+                ("log_capacity", C.c_int32), ("reserved", C.c_int32)]
+
+
+class XferStats(C.Structure):
+    _fields_ = [("requests", C.c_uint64 * 2), ("bytes", C.c_uint64 * 2), ("chunks", C.c_uint64 * 2),
+                ("latency_sum_s", C.c_double * 2), ("latency_max_s", C.c_double * 2)]
+
+
+class XferLog(C.Structure):
+    _fields_ = [("ticket", C.c_uint64), ("offset", C.c_uint64), ("bytes", C.c_uint64), ("kind", C.c_int32),
+                ("dir", C.c_int32)]
+
+
 class SchedConfig(C.Structure):
     _fields_ = [("alpha_s", C.c_double), ("beta_s", C.c_double), ("delta_s", C.c_double),
                 ("link_tokens_per_s", C.c_double), ("steady_rel_range", C.c_double),
@@ -118,6 +140,19 @@ class SchedIter(C.Structure):
 
 
 _sig = {
+    "pipemax_xfer_create": (C.c_int, [C.POINTER(XferConfig), C.POINTER(C.c_void_p)]),
+    "pipemax_xfer_destroy": (C.c_int, [C.c_void_p]),
+    "pipemax_xfer_submit": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                      C.POINTER(C.c_uint64)]),
+    "pipemax_xfer_wait": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pipemax_xfer_poll": (C.c_int, [C.c_void_p, C.c_uint64]),
+    "pipemax_xfer_stream_wait": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "pipemax_xfer_drain": (C.c_int, [C.c_void_p]),
+    "pipemax_xfer_get_stats": (C.c_int, [C.c_void_p, C.POINTER(XferStats)]),
+    "pipemax_xfer_reset_stats": (C.c_int, [C.c_void_p]),
+    "pipemax_xfer_get_log": (C.c_int, [C.c_void_p, C.POINTER(XferLog), C.c_int]),
+    "pipemax_xfer_debug_set_host_us_per_mib": (C.c_int, [C.c_void_p, C.c_int]),
+    "pipemax_xfer_debug_pause": (C.c_int, [C.c_void_p, C.c_int]),
     "pipemax_sched_create": (C.c_int, [C.POINTER(SchedConfig), C.POINTER(C.c_void_p)]),
     "pipemax_sched_destroy": (C.c_int, [C.c_void_p]),
     "pipemax_sched_predict": (C.c_double, [C.c_void_p, C.c_int32, C.c_int64]),
@@ -483,3 +518,64 @@ class Scheduler:
                                           _vp(stream_ptr) if stream_ptr else None, C.byref(it),
                                           e.ctypes.data_as(_i32p), p.ctypes.data_as(_i32p), v.ctypes.data_as(_i32p)))
         return self._result(it, e, p, v)
+
+
+# -- demand-priority transfer orchestrator (include/pipemax_xfer.h) ---------------------------------
+class Xfer:
+    """Thin wrapper of pipemax_xfer_t.  Pointers are integers (tensor.data_ptr(), ndarray.ctypes.data)."""
+
+    def __init__(self, device: int = 0, max_inflight_bulk: int = 2, chunk_bytes: int = 4 << 20, log_capacity: int = 0):
+        self.cfg = XferConfig(device=device, max_inflight_bulk=max_inflight_bulk, chunk_bytes=chunk_bytes,
+                              log_capacity=log_capacity)
+        self._h = _vp()
+        _check(_lib.pipemax_xfer_create(C.byref(self.cfg), C.byref(self._h)))
+
+    def destroy(self):
+        if self._h:
+            _check(_lib.pipemax_xfer_destroy(self._h))
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def submit(self, kind: int, direction: int, dst_ptr: int, src_ptr: int, nbytes: int) -> int:
+        t = C.c_uint64(0)
+        _check(_lib.pipemax_xfer_submit(self._h, kind, direction, _vp(dst_ptr), _vp(src_ptr), nbytes, C.byref(t)))
+        return t.value
+
+    def wait(self, ticket: int):
+        _check(_lib.pipemax_xfer_wait(self._h, ticket))
+
+    def poll(self, ticket: int) -> bool:
+        rc = _lib.pipemax_xfer_poll(self._h, ticket)
+        _check(min(rc, 0))
+        return bool(rc)
+
+    def stream_wait(self, ticket: int, stream_ptr: int):
+        _check(_lib.pipemax_xfer_stream_wait(self._h, ticket, _vp(stream_ptr)))
+
+    def drain(self):
+        _check(_lib.pipemax_xfer_drain(self._h))
+
+    def stats(self) -> dict:
+        s = XferStats()
+        _check(_lib.pipemax_xfer_get_stats(self._h, C.byref(s)))
+        return {k: {"urgent": getattr(s, k)[0], "bulk": getattr(s, k)[1]} for k, _ in s._fields_}
+
+    def reset_stats(self):
+        _check(_lib.pipemax_xfer_reset_stats(self._h))
+
+    def log(self, capacity: int = 4096) -> list:
+        buf = (XferLog * capacity)()
+        n = _lib.pipemax_xfer_get_log(self._h, buf, capacity)
+        _check(min(n, 0))
+        return [(e.ticket, e.offset, e.bytes, e.kind, e.dir) for e in buf[:n]]
+
+    def debug_pause(self, paused: bool):
+        _check(_lib.pipemax_xfer_debug_pause(self._h, int(paused)))
+
+    def debug_set_host_us_per_mib(self, us: int):
+        _check(_lib.pipemax_xfer_debug_set_host_us_per_mib(self._h, us))
