@@ -87,6 +87,13 @@ int pipemax_xfer_debug_set_host_us_per_mib(pipemax_xfer_t* x, int us);
  * order in which they are then issued is fully determined by the queue discipline.                */
 int pipemax_xfer_debug_pause(pipemax_xfer_t* x, int paused);
 
+/* Routes the KV prefetch copies of a stage through the orchestrator (x = NULL: back to the stage's own
+ * prefetch stream).  pipemax_prefetch_kv then queues its copy runs as bulk host-to-device requests, a
+ * decode step waits for them through pipemax_xfer_stream_wait, pipemax_sync drains the orchestrator.
+ * The orchestrator must be on the stage's device and must outlive the attachment.  Synchronises the
+ * stage first.                                                                                      */
+int pipemax_stage_attach_xfer(pipemax_stage_t* st, pipemax_xfer_t* x);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,7 @@ XFER_SYMBOLS = [
     "pipemax_xfer_create", "pipemax_xfer_destroy", "pipemax_xfer_submit", "pipemax_xfer_wait", "pipemax_xfer_poll",
     "pipemax_xfer_stream_wait", "pipemax_xfer_drain", "pipemax_xfer_get_stats", "pipemax_xfer_reset_stats",
     "pipemax_xfer_get_log", "pipemax_xfer_debug_set_host_us_per_mib", "pipemax_xfer_debug_pause",
+    "pipemax_stage_attach_xfer",
 ]
 XFER_URGENT, XFER_BULK, XFER_H2D, XFER_D2H = 0, 1, 0, 1
 # every symbol include/pipemax_sched.h declares
@@ -153,6 +154,7 @@ _sig = {
     "pipemax_xfer_get_log": (C.c_int, [C.c_void_p, C.POINTER(XferLog), C.c_int]),
     "pipemax_xfer_debug_set_host_us_per_mib": (C.c_int, [C.c_void_p, C.c_int]),
     "pipemax_xfer_debug_pause": (C.c_int, [C.c_void_p, C.c_int]),
+    "pipemax_stage_attach_xfer": (C.c_int, [C.c_void_p, C.c_void_p]),
     "pipemax_sched_create": (C.c_int, [C.POINTER(SchedConfig), C.POINTER(C.c_void_p)]),
     "pipemax_sched_destroy": (C.c_int, [C.c_void_p]),
     "pipemax_sched_predict": (C.c_double, [C.c_void_p, C.c_int32, C.c_int64]),
@@ -315,6 +317,11 @@ class Stage:
         """n_tokens new tokens of one sequence; hidden tensors are [n_tokens][hidden] on the device."""
         _check(_lib.pipemax_prefill(self._h, mb, seq, n_tokens, _vp(hidden_in_ptr), _vp(hidden_out_ptr),
                                     _vp(stream_ptr) if stream_ptr else None))
+
+    def attach_xfer(self, xfer):
+        """Prefetch copies go through a transfer orchestrator (None detaches)."""
+        _check(_lib.pipemax_stage_attach_xfer(self._h, xfer._h if xfer is not None else None))
+        self._xfer = xfer           # keeps it alive
 
     def evict_kv(self, mb, seq_ids=None):
         p, n = _ids(seq_ids)

@@ -25,6 +25,7 @@
 #include <vector>
 
 #include "kernels.hpp"
+#include "pipemax_xfer.h"
 #include "kv_pool.hpp"
 
 namespace pmx {
@@ -66,6 +67,7 @@ struct MicroBatch {
   bool table_dirty = true;
   hipEvent_t ev_prefetch = nullptr;
   bool prefetch_pending = false;
+  uint64_t prefetch_ticket = 0;   // last copy of the prefetch when a transfer orchestrator issues the copies
   hipEvent_t ev_step = nullptr;
   bool stepped = false;
   int wb_pending = 0;   // guarded by Stage::mu
@@ -148,6 +150,7 @@ struct pipemax_stage {
   // ordering of growth pages against cancelled prefetches
   hipEvent_t ev_h2d_fence = nullptr;
   bool h2d_fence_pending = false;
+  pipemax_xfer_t* xfer = nullptr;   // not owned: issues the prefetch copies when attached
   // worker
   std::thread worker;
   std::mutex mu;
@@ -908,6 +911,19 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
   std::vector<CopyRun> runs;
   plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, runs);
   if (int us = st->dly_h2d.load()) PMX_HIP(hipLaunchHostFunc(st->s_h2d, host_sleep_cb, (void*)(intptr_t)us));
+  if (st->xfer) {
+    // the orchestrator cuts the runs into chunks and feeds them to the link behind any urgent copy; bulk
+    // requests of one direction complete in order, so the last ticket stands for the whole prefetch
+    for (const CopyRun& r : runs) {
+      rc = pipemax_xfer_submit(st->xfer, PIPEMAX_XFER_BULK, PIPEMAX_XFER_H2D, st->gpu_page_ptr(r.dst),
+                               st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes, &M.prefetch_ticket);
+      if (rc) return rc;
+      st->st.h2d_bytes += (uint64_t)r.count * st->page_bytes;
+      st->st.h2d_copies += 1;
+    }
+    M.prefetch_pending = true;
+    return PIPEMAX_OK;
+  }
   st->tbegin(TC_H2D, st->s_h2d);
   for (const CopyRun& r : runs) {
     PMX_HIP(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
@@ -918,6 +934,7 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
   st->tend(st->s_h2d);
   PMX_HIP(hipEventRecord(M.ev_prefetch, st->s_h2d));
   M.prefetch_pending = true;
+  M.prefetch_ticket = 0;
   return PIPEMAX_OK;
 }
 
@@ -938,11 +955,15 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
   PMX_HIP(hipSetDevice(st->dev));
   // later prefetches into these pages must come after the last step that read them
   if (M.stepped) {
-    if (st->cfg.flags & PIPEMAX_FLAG_STREAM_ORDERED_EVICT) PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
+    if ((st->cfg.flags & PIPEMAX_FLAG_STREAM_ORDERED_EVICT) && !st->xfer)
+      PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
     else st->release_wait.push_back(mb);
   }
   // pages of a cancelled prefetch may be handed to a decode step's growth: fence the compute stream
-  if (any_inflight) {
+  if (any_inflight && st->xfer && M.prefetch_ticket) {
+    rc = pipemax_xfer_wait(st->xfer, M.prefetch_ticket);     // the copies into these pages have landed
+    if (rc) return rc;
+  } else if (any_inflight) {
     PMX_HIP(hipEventRecord(st->ev_h2d_fence, st->s_h2d));
     st->h2d_fence_pending = true;
   }
@@ -1023,7 +1044,12 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
 
   // ---- stream dependencies -----------------------------------------------------------------------
   if (M.prefetch_pending) {
-    PMX_HIP(hipStreamWaitEvent(cs, M.ev_prefetch, 0));
+    if (st->xfer && M.prefetch_ticket) {
+      rc = pipemax_xfer_stream_wait(st->xfer, M.prefetch_ticket, cs);
+      if (rc) return rc;
+    } else {
+      PMX_HIP(hipStreamWaitEvent(cs, M.ev_prefetch, 0));
+    }
     M.prefetch_pending = false;
   }
   if (st->h2d_fence_pending) {
@@ -1357,6 +1383,10 @@ int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const vo
 int pipemax_sync(pipemax_stage_t* st) {
   if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
   PMX_HIP(hipSetDevice(st->dev));
+  if (st->xfer) {
+    int rcx = pipemax_xfer_drain(st->xfer);
+    if (rcx) return rcx;
+  }
   PMX_HIP(hipStreamSynchronize(st->s_last));
   if (st->s_last != st->s_own) PMX_HIP(hipStreamSynchronize(st->s_own));
   PMX_HIP(hipStreamSynchronize(st->s_h2d));
@@ -1373,6 +1403,14 @@ int pipemax_sync(pipemax_stage_t* st) {
 }
 
 // ---- introspection ---------------------------------------------------------------------------------------
+int pipemax_stage_attach_xfer(pipemax_stage_t* st, pipemax_xfer_t* x) {
+  if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  int rc = pipemax_sync(st);
+  if (rc) return rc;
+  st->xfer = x;
+  return PIPEMAX_OK;
+}
+
 int pipemax_get_stats(pipemax_stage_t* st, pipemax_stats_t* out) {
   if (!st || !out) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
   if (st->timing()) {

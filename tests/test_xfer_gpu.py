@@ -86,3 +86,34 @@ def test_urgent_copy_does_not_wait_for_queued_kv_traffic():
     assert still_running
     assert float(np.median(lats)) < 0.003                         # one or two 16 MiB chunks ahead, not 2 GiB
     x.destroy()
+
+
+@pytest.mark.parametrize("config", ["C1_fp32", "mid_bf16"])
+def test_stage_prefetch_through_the_orchestrator_keeps_parity(config):
+    """The cyclic schedule with every prefetch copy cut into small chunks and issued by the orchestrator:
+    same bars as the direct path (stage oracle on every step, bit-exact replica)."""
+    import torch
+    from test_parity_gpu import _check_replica, _mid_shape, _ragged_ctx, _run_cyclic_and_compare
+    from helpers import check_tables
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.harness import StageRunner
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    if config == "C1_fp32":
+        shape, tol, told, ctx = CONFIGS["C1"], 1e-5, 2e-4, None
+    else:
+        shape, tol, told = _mid_shape(), 1e-2, 3e-2
+    syn = SynthInputs(shape, seed=41, pool_elems=1 << 23, gain_jitter=0.1)
+    if config != "C1_fp32":
+        ctx = _ragged_ctx(shape, syn)
+    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx).load()
+    x = pm.Xfer(device=0, max_inflight_bulk=2, chunk_bytes=64 << 10, log_capacity=16)
+    runner.stage.attach_xfer(x)
+    orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=tol, tol_delta=told)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=tol)
+    st = x.stats()
+    assert st["bytes"]["bulk"] == runner.stage.get_stats()["h2d_bytes"] > 0
+    assert st["chunks"]["bulk"] > st["requests"]["bulk"]          # the runs were cut
+    runner.stage.attach_xfer(None)
+    runner.stage.destroy()
+    x.destroy()

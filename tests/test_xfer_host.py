@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_symbol_of_the_transfer_header(lib):
     hdr = open(os.path.join(ROOT, "include", "pipemax_xfer.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(pipemax_xfer_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(pipemax_(?:xfer|stage)_[a-z_]+)\s*\(", hdr))
     assert declared == set(lib.XFER_SYMBOLS)
     import ctypes as C
     assert C.sizeof(lib.XferConfig) == 24 and C.sizeof(lib.XferStats) == 80 and C.sizeof(lib.XferLog) == 32
