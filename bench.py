@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="also time sigma = 1, 1/2, ..., 1/128, 0 (two cycles each) to locate the crossover "
                          "from link-bound to HBM-bound")
+    ap.add_argument("--orchestrated", type=float, default=0.0, metavar="CHUNK_MIB",
+                    help="issue the prefetch copies through the transfer orchestrator in chunks of this many MiB "
+                         "(window of 2); 0 = the stage's own prefetch stream")
     ap.add_argument("--cpu-seqs", type=int, default=16)
     ap.add_argument("--cpu-steps", type=int, default=48)
     args = ap.parse_args()
@@ -135,6 +138,10 @@ def main():
                       flags=pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
     st = run.stage
     run.load()
+    xfer = None
+    if args.orchestrated > 0:
+        xfer = pm.Xfer(device=0, max_inflight_bulk=2, chunk_bytes=int(args.orchestrated * (1 << 20)))
+        st.attach_xfer(xfer)
     hin = [run.hidden_tensor(mb, mb) for mb in range(n)]
     hout = [torch.empty_like(h) for h in hin]
     stream = torch.cuda.current_stream()
@@ -296,7 +303,9 @@ def main():
                                f"{shape.n_q_heads}Q/{shape.n_kv_heads}KV heads x {shape.head_dim}, ffn {shape.ffn}, "
                                f"{n} micro-batches x {shape.seqs_per_mb} seqs, prompts {shape.ctx_lo}-{shape.ctx_hi} tokens",
                    "sigma": args.sigma, "schedule": "cyclic (execute D_i, prefetch D_i+1, overwrite D_i-1)",
-                   "inactive_kv": "pinned host memory", "page_tokens": 16},
+                   "inactive_kv": "pinned host memory", "page_tokens": 16,
+                   "prefetch_issue": (f"transfer orchestrator, {args.orchestrated:g} MiB chunks, window 2"
+                                      if args.orchestrated > 0 else "stage's own prefetch stream, whole runs")},
         "roofline": roofline, "legs": legs,
     }
     if sweep is not None:
@@ -309,6 +318,9 @@ def main():
             pm.probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), stream.cuda_stream)
         torch.cuda.synchronize()
         del src, dst
+    if xfer is not None:
+        st.attach_xfer(None)
+        xfer.destroy()
     if not args.no_cpu_baseline:
         st.destroy()
         del run
