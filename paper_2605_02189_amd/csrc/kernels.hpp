@@ -53,13 +53,6 @@ void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, con
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
           int n_split, int wn);
 
-// Same product for M <= 64 rows with the barrier-free streaming kernel (N % 64 == 0, nwk in {4, 8}
-// waves per work-group).  swiglu = 0: fp32 partials part[s][m][n], n_split of them.  swiglu = 1
-// (W = interleaved gate/up matrix, one split): act_t = A-tiled bf16 silu(gate) * up, K of the next
-// GEMM = N / 2.
-void gemm_skinny(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, uint16_t* act_t, int M,
-                 int K, int N, int n_split, int nwk, int swiglu);
-
 void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);

@@ -231,6 +231,11 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
   __shared__ uint4 xs[2][NF * 64];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nt0 = (blockIdx.x * 4 + w) * 2;
+  // blockIdx.z: block of MT row tiles (more than 256 rows are covered by several row blocks, which re-use the
+  // weight tile through L2 / the memory-side cache while they run side by side)
+  Xt += (int64_t)blockIdx.z * MT * KT * 64;
+  part += (int64_t)blockIdx.z * MT * 32 * N;
+  M -= (int)blockIdx.z * MT * 32;
   const int k0 = blockIdx.y * ksp;
   const int k1 = min(KT, k0 + ksp);
   const int nchunks = (k1 - k0 + KC - 1) / KC;
@@ -323,100 +328,11 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 }
 
 // =================================================================================================
-// skinny GEMM for at most 64 rows (MT <= 2): barrier-free streaming
-//   grid (N / (32*NT), S), block = NWK waves.  The block owns NT adjacent 32-column tiles and the
-//   K range of split blockIdx.y; its waves take the k-steps of that range round-robin.  Every wave
-//   streams its weight fragments from HBM and its X fragments from L2 (both lane-linear 1 KiB loads,
-//   U k-steps ahead) with no LDS and no barrier in the loop; the waves' accumulators are summed once
-//   through LDS at the end.  EPI 0: fp32 partial part[s][m][n].  EPI 1 (NT = 2 = gate tile + up tile
-//   of the interleaved gate/up matrix, S = 1): act = silu(gate) * up written as A-tiled bf16.
-// =================================================================================================
-template <int MT, int NT, int NWK, int U, int EPI>
-__global__ __launch_bounds__(NWK * 64) void k_gemm_s(const uint4* __restrict__ Xt,
-                                                     const uint4* __restrict__ Wt,
-                                                     float* __restrict__ part, uint16_t* __restrict__ act_t,
-                                                     int M, int N, int KT, int ksp, int64_t split_stride) {
-  __shared__ float red[NWK][NT * 16][64];
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nt0 = blockIdx.x * NT;
-  const int kb0 = blockIdx.y * ksp;
-  const int kb1 = min(KT, kb0 + ksp);
-  const int nsteps = (kb1 - kb0 > w) ? (kb1 - kb0 - w + NWK - 1) / NWK : 0;   // k-steps kb0 + w + j*NWK
-  const uint4* wp = Wt + ((int64_t)nt0 * KT + kb0 + w) * 64 + lane;             // + nt*KT*64 + j*NWK*64
-  const uint4* xp = Xt + ((int64_t)kb0 + w) * 64 + lane;                        // + mt*KT*64 + j*NWK*64
-
-  f32x16 acc[NT * MT];
-#pragma unroll
-  for (int t = 0; t < NT * MT; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-
-  uint4 wb[U][NT], xb[U][MT];
-  auto load = [&](int j, uint4* wd, uint4* xd) {
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) wd[nt] = ld_stream(wp + ((int64_t)nt * KT + (int64_t)j * NWK) * 64);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xd[mt] = xp[((int64_t)mt * KT + (int64_t)j * NWK) * 64];
-  };
-#pragma unroll
-  for (int r = 0; r < U; ++r)
-    if (r < nsteps) load(r, wb[r], xb[r]);
-  for (int j0 = 0; j0 < nsteps; j0 += U) {
-#pragma unroll
-    for (int r = 0; r < U; ++r) {
-      const int j = j0 + r;
-      if (j < nsteps) {
-        bf16x8 A[MT], B[NT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) A[mt] = __builtin_bit_cast(bf16x8, xb[r][mt]);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) B[nt] = __builtin_bit_cast(bf16x8, wb[r][nt]);
-        if (j + U < nsteps) load(j + U, wb[r], xb[r]);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[nt * MT + mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[mt], B[nt], acc[nt * MT + mt], 0, 0, 0);
-      }
-    }
-  }
-
-  // ---- sum the NWK waves' accumulators through LDS (one row tile at a time), then the epilogue ---
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    if (mt) __syncthreads();
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) red[w][nt * 16 + r][lane] = acc[nt * MT + mt][r];
-    __syncthreads();
-    for (int r = w; r < 16; r += NWK) {
-      float v[NT];
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        float a = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < NWK; ++ww) a += red[ww][nt * 16 + r][lane];
-        v[nt] = a;
-      }
-      const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      if (m < M) {
-        if (EPI == 0) {
-          float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + (lane & 31);
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) out[nt * 32] = v[nt];
-        } else {
-          const int f = blockIdx.x * 32 + (lane & 31);
-          const float g = v[0], u = v[NT - 1];
-          act_t[a_tiled_idx(N >> 5, m, f)] = f2bf(g / (1.0f + expf(-g)) * u);   // down GEMM: K = N/2, KT = N/32
-        }
-      }
-    }
-  }
-}
-
-// =================================================================================================
-// The same streaming GEMM with the consumer fused into its epilogue (M <= 64 rows, NT = 2).
+// Barrier-free streaming GEMM for at most 64 rows with the consumer fused into its epilogue (NT = 2).
+//   grid (N / 64, S), block = NWK waves.  The block owns two adjacent 32-column tiles and the K range of
+//   split blockIdx.y; its waves take the k-steps of that range round-robin.  Every wave streams its weight
+//   fragments from HBM and its X fragments from L2 (lane-linear 1 KiB loads, U k-steps ahead) with no LDS and
+//   no barrier in the loop; the waves' accumulators are summed once through LDS at the end.
 //   Split-K across work-groups (gridDim.y > 1) is resolved inside the kernel: every block stores its
 //   fp32 partial, and the block that arrives last at the column block's counter sums all partials in
 //   split order (so the result does not depend on which block was last) and runs the epilogue.
@@ -1171,15 +1087,23 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
                        int n_split) {
   const int KT = K / 16;
   const int ksp = (KT + n_split - 1) / n_split;
-  const int MT = (M + 31) / 32;
-  const int64_t stride = (int64_t)MT * 32 * N;
-  dim3 grid(N / 256, n_split), block(256);
-  if (MT <= 4)
-    hipLaunchKernelGGL((k_gemm_l<4, 4>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, M, N, KT, ksp,
-                       stride);
-  else
-    hipLaunchKernelGGL((k_gemm_l<8, 4>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, M, N, KT, ksp,
-                       stride);
+  const int S = (KT + ksp - 1) / ksp;
+  const int MTall = (M + 31) / 32;
+  const int64_t stride = (int64_t)MTall * 32 * N;
+  const int full = M / 256, rem = M - full * 256;
+  dim3 block(256);
+  if (full)      // whole blocks of 256 rows: one launch, row blocks along grid.z (fastest-varying last)
+    hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part,
+                       full * 256, N, KT, ksp, stride);
+  if (rem) {     // the remaining rows with the smallest tile count that covers them
+    const uint4* Xr = (const uint4*)Xt + (int64_t)full * 8 * KT * 64;
+    float* pr = part + (int64_t)full * 256 * N;
+    dim3 grid(N / 256, S);
+    if (rem <= 128)
+      hipLaunchKernelGGL((k_gemm_l<4, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride);
+    else
+      hipLaunchKernelGGL((k_gemm_l<8, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride);
+  }
 }
 
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
@@ -1187,33 +1111,6 @@ void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, in
   if (wn == 0) { gemm_large(s, Xt, Wt, part, M, K, N, n_split); return; }
   if (wn == 8) gemm_wn<8>(s, Xt, Wt, part, M, K, N, n_split);
   else gemm_wn<4>(s, Xt, Wt, part, M, K, N, n_split);
-}
-
-template <int NWK, int EPI>
-static void gemm_skinny_t(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, uint16_t* act_t,
-                          int M, int K, int N, int n_split) {
-  const int KT = K / 16;
-  const int ksp = (KT + n_split - 1) / n_split;
-  const int MT = (M + 31) / 32;
-  const int64_t stride = (int64_t)MT * 32 * N;
-  dim3 grid(N / 64, n_split), block(NWK * 64);
-  if (MT <= 1)
-    hipLaunchKernelGGL((k_gemm_s<1, 2, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part,
-                       act_t, M, N, KT, ksp, stride);
-  else
-    hipLaunchKernelGGL((k_gemm_s<2, 2, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part,
-                       act_t, M, N, KT, ksp, stride);
-}
-
-void gemm_skinny(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, uint16_t* act_t, int M,
-                 int K, int N, int n_split, int nwk, int swiglu) {
-  if (swiglu) {
-    if (nwk == 8) gemm_skinny_t<8, 1>(s, Xt, Wt, part, act_t, M, K, N, 1);
-    else gemm_skinny_t<4, 1>(s, Xt, Wt, part, act_t, M, K, N, 1);
-  } else {
-    if (nwk == 8) gemm_skinny_t<8, 0>(s, Xt, Wt, part, act_t, M, K, N, n_split);
-    else gemm_skinny_t<4, 0>(s, Xt, Wt, part, act_t, M, K, N, n_split);
-  }
 }
 
 void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,

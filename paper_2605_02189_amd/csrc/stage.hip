@@ -129,9 +129,9 @@ struct pipemax_stage {
   float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr, *m_ssq = nullptr;
   int *m_cnt_gemm = nullptr, *m_cnt_attn = nullptr;
   // up to 64 rows: consumers fused into the GEMM epilogues (plans f_*); more: large-tile GEMMs with
-  // separate element-wise kernels (plans p_*, present when max_seqs_per_mb > 64)
+  // separate element-wise kernels, planned per call from the row count
   int attn_cp_override = 0;   // PIPEMAX_ATTN_CHUNK_PAGES: tuning override of the attention chunk size
-  GemmPlan p_qkv, p_o, p_gu, p_d, f_qkv, f_o, f_gu, f_d;
+  GemmPlan f_qkv, f_o, f_gu, f_d;
   int nch_alloc = 1;
   float* layer_out = nullptr;
   int last_b = 0;
@@ -367,18 +367,21 @@ GemmPlan plan_gemm_skinny(int N, int K, bool swiglu) {
   return p;
 }
 
-// 65..256 rows: large-tile kernel, one work-group (4 waves, 256 columns) per CU and about 256
-// work-groups in total
-GemmPlan plan_gemm_large(int N, int K) {
+// more than 64 rows: large-tile kernel, one work-group (4 waves, 256 rows x 256 columns) per CU and about
+// 256 work-groups in total: column blocks x row blocks x K splits
+GemmPlan plan_gemm_large(int N, int K, int M) {
   GemmPlan p;
   p.wn = 0;
-  const int bn = N / 256, KT = K / 16;
+  const int bn = (N / 256) * ((M + 255) / 256), KT = K / 16;
   int S = std::max(1, (256 + bn / 2) / bn);
   S = std::max(1, std::min(S, KT / 16));
   const int ksp = (KT + S - 1) / S;
   p.split = (KT + ksp - 1) / ksp;
   return p;
 }
+
+GemmPlan plan_gemm(int N, int K);
+GemmPlan plan_rows(int N, int K, int M) { return (N % 256 == 0) ? plan_gemm_large(N, K, M) : plan_gemm(N, K); }
 
 GemmPlan plan_gemm(int N, int K) {
   GemmPlan p;
@@ -395,7 +398,11 @@ GemmPlan plan_gemm(int N, int K) {
 bool mfma_shape_ok(const pipemax_config_t& c) {
   const int nq = c.n_q_heads * c.head_dim;
   return c.dtype == PIPEMAX_BF16 && c.head_dim == 128 && c.hidden % 128 == 0 && c.ffn % 64 == 0 &&
-         nq % 16 == 0 && c.max_seqs_per_mb <= 256 && c.n_q_heads / c.n_kv_heads <= 16;
+         nq % 16 == 0 && c.n_q_heads / c.n_kv_heads <= 16 &&
+         // more than 256 rows per pass (prefill chunks) need the large-tile GEMM for every matrix
+         (c.max_seqs_per_mb <= 256 ||
+          (c.max_seqs_per_mb <= 1024 && (nq + 2 * c.n_kv_heads * c.head_dim) % 256 == 0 && c.hidden % 256 == 0 &&
+           (2 * c.ffn) % 256 == 0));
 }
 
 void destroy_impl(pipemax_stage* st) {
@@ -607,7 +614,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   // activations
   const int mpad = ((maxb + 31) / 32) * 32;
   // the GEMM kernels are instantiated for 1, 2, 4 or 8 row tiles of 32 and read all of them
-  const int mtile = (maxb <= 32) ? 32 : (maxb <= 64) ? 64 : (maxb <= 128) ? 128 : 256;
+  const int mtile = (maxb <= 32) ? 32 : (maxb <= 64) ? 64 : (maxb <= 128) ? 128 : ((maxb + 255) / 256) * 256;
   PMX_TRY(dev_alloc(st, &st->x, (size_t)mpad * h));
   PMX_TRY(dev_alloc(st, &st->rope_cs, (size_t)maxb * (c.head_dim / 2)));
   if (st->engine == 0) {
@@ -629,16 +636,12 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     part = std::max(part, (size_t)st->f_o.split * fpad * h);
     part = std::max(part, (size_t)st->f_gu.split * fpad * 2 * F);
     part = std::max(part, (size_t)st->f_d.split * fpad * h);
-    if (maxb > 64) {
-      auto plan = [&](int N, int K) { return (N % 256 == 0) ? plan_gemm_large(N, K) : plan_gemm(N, K); };
-      st->p_qkv = plan(D.Nqkv, h);
-      st->p_o = plan(h, nq);
-      st->p_gu = plan(2 * F, h);
-      st->p_d = plan(h, F);
-      part = std::max(part, (size_t)st->p_qkv.split * mpad * D.Nqkv);
-      part = std::max(part, (size_t)st->p_o.split * mpad * h);
-      part = std::max(part, (size_t)st->p_gu.split * mpad * 2 * F);
-      part = std::max(part, (size_t)st->p_d.split * mpad * h);
+    // the un-fused path plans its split per call from the row count; the partial buffer covers every count
+    for (int rows = 96; rows <= mpad; rows += 32) {
+      part = std::max(part, (size_t)plan_rows(D.Nqkv, h, rows).split * rows * D.Nqkv);
+      part = std::max(part, (size_t)plan_rows(h, nq, rows).split * rows * h);
+      part = std::max(part, (size_t)plan_rows(2 * F, h, rows).split * rows * 2 * F);
+      part = std::max(part, (size_t)plan_rows(h, F, rows).split * rows * h);
     }
     PMX_TRY(dev_alloc(st, &st->m_part, part));
     PMX_TRY(dev_alloc(st, &st->m_xn_t, (size_t)mtile * h));
@@ -1245,6 +1248,8 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
                                  hipMemcpyDeviceToDevice, cs));
       }
     } else {
+      const GemmPlan p_qkv = plan_rows(D.Nqkv, D.h, b), p_o = plan_rows(D.h, nq, b),
+                     p_gu = plan_rows(2 * D.F, D.h, b), p_d = plan_rows(D.h, D.F, b);
       const float* prev_part = nullptr;     // partials of the previous layer's down projection
       st->tbegin(PIPEMAX_K_MISC, cs);
       launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
@@ -1254,41 +1259,41 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
         uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
         st->tbegin(PIPEMAX_K_NORM, cs);
         mfma::resid_norm(cs, b, D.h, D.eps, l == 0 ? (const uint16_t*)hidden_in : nullptr, prev_part,
-                         st->p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
+                         p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
         st->tend(cs);
         if (st->layer_out && l > 0)
           PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
                                  hipMemcpyDeviceToDevice, cs));
         st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
-        run_gemm(st->p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
+        run_gemm(p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
-        mfma::rope_append(cs, D, l, b, st->m_part, st->p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
+        mfma::rope_append(cs, D, l, b, st->m_part, p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
                           (uint16_t*)st->gpu_pool, stage_l, st->m_q);
         st->tend(cs);
         int rc2 = after_append(l);
         if (rc2) return rc2;
         run_attention(l);
         st->tbegin(PIPEMAX_K_GEMM_O, cs);
-        run_gemm(st->p_o, st->m_attn_t, L.wo, nq, D.h);
+        run_gemm(p_o, st->m_attn_t, L.wo, nq, D.h);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_NORM, cs);
-        mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, st->p_o.split, s_h, st->x, (const uint16_t*)L.g2,
+        mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, p_o.split, s_h, st->x, (const uint16_t*)L.g2,
                          st->m_xn_t, nullptr);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
-        run_gemm(st->p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
+        run_gemm(p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_SWIGLU, cs);
-        mfma::swiglu(cs, b, D.F, st->m_part, st->p_gu.split, s_gu, st->m_act_t);
+        mfma::swiglu(cs, b, D.F, st->m_part, p_gu.split, s_gu, st->m_act_t);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
-        run_gemm(st->p_d, st->m_act_t, L.wd, D.F, D.h);
+        run_gemm(p_d, st->m_act_t, L.wd, D.F, D.h);
         st->tend(cs);
         prev_part = st->m_part;
       }
       st->tbegin(PIPEMAX_K_NORM, cs);
-      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, st->p_d.split, s_h, st->x, nullptr, nullptr,
+      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, p_d.split, s_h, st->x, nullptr, nullptr,
                        (uint16_t*)hidden_out);
       st->tend(cs);
       if (st->layer_out)

@@ -26,7 +26,8 @@ class StageRunner:
     def __init__(self, shape: StageShape, syn: SynthInputs, *, sigma: float = 1.0, steps: int | None = None,
                  flags: int = 0, device: int = 0, n_microbatches: int | None = None,
                  ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False,
-                 wb_layers_per_copy: int = 0, reserve: bool = True, gpu_pages: int | None = None):
+                 wb_layers_per_copy: int = 0, reserve: bool = True, gpu_pages: int | None = None,
+                 max_rows: int | None = None):
         self.shape, self.syn = shape, syn
         pool_override = gpu_pages
         self.n = n_microbatches or shape.n_microbatches
@@ -55,7 +56,7 @@ class StageRunner:
             n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
             rope_base=shape.rope_base, rms_eps=shape.rms_eps,
             dtype=pm.F32 if shape.dtype == "fp32" else pm.BF16, n_microbatches=self.n,
-            max_seqs_per_mb=max(self.b_of.values()), max_ctx=max_ctx,
+            max_seqs_per_mb=max(max(self.b_of.values()), max_rows or 0), max_ctx=max_ctx,
             gpu_kv_bytes=gpu_pages * shape.page_bytes, host_kv_bytes=(host_pages + 8) * shape.page_bytes,
             device=device, flags=flags, host_reserve_tokens=(steps_per_mb + 1) if reserve else 0,
             wb_layers_per_copy=wb_layers_per_copy)

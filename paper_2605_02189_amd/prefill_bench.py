@@ -31,12 +31,12 @@ def main():
 
     base = CONFIGS[args.config]
     R, T = args.requests + 1, args.tokens                         # one extra request warms the kernels up
-    shape = base.with_(n_microbatches=1, seqs_per_mb=args.chunk)
+    shape = base.with_(n_microbatches=1, seqs_per_mb=R)
     syn = SynthInputs(shape, seed=args.seed)
-    ctx = {0: np.zeros(args.chunk, dtype=np.int32)}               # the stage's row capacity = --chunk sequences
+    ctx = {0: np.zeros(R, dtype=np.int32)}
     flags = pm.FLAG_NO_WRITEBACK if args.no_writeback else 0
     run = StageRunner(shape, syn, sigma=0.0, steps=T + 16, ctx_lens=ctx, flags=flags,
-                      gpu_pages=R * (T // 16 + 2) + 8)
+                      gpu_pages=R * (T // 16 + 2) + 8, max_rows=args.chunk)    # row capacity of a pass = --chunk
     st = run.stage
     run.load_weights()
     st.mb_define(0, ctx[0])

@@ -29,24 +29,28 @@ def _oracle_prefill(orc, syn, mb, seq, x):
     return out
 
 
-@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_long_context", "generic_fp32"])
+@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_long_context", "generic_fp32"])
 def test_prefill_matches_token_by_token_oracle(case):
     import torch
     assert torch.cuda.is_available()
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.harness import StageRunner
     from paper_2605_02189_amd.synth_inputs import CONFIGS, StageShape, SynthInputs
+    max_rows = None
     if case == "generic_fp32":
         shape = CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=6)
         tol, plan = 1e-5, [(0, 21), (1, 19), (0, 8)]
     else:
-        b = 70 if case == "mfma_wide_chunks" else 20
+        b = 70 if case == "mfma_wide_chunks" else 6 if case == "mfma_xl_chunks" else 20
+        max_rows = 600 if case == "mfma_xl_chunks" else None      # two 256-row blocks + a remainder per pass
         shape = StageShape(name=case, n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2816,
                            dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
                            decode_steps=1)
         tol = 1e-2
         # (sequence, new tokens): several chunks each; sequence 1 continues an existing prefix
         plan = [(0, 45), (1, 30), (0, 17)] if b == 20 else [(0, 150), (1, 75)]
+        if case == "mfma_xl_chunks":
+            plan = [(0, 700), (1, 300)]
         if case == "mfma_long_context":                    # beyond the chunk kernel's 256 pages: per-row kernel
             plan = [(1, 30), (0, 5)]
     syn = SynthInputs(shape, seed=31, pool_elems=1 << 23, gain_jitter=0.1)
@@ -54,7 +58,8 @@ def test_prefill_matches_token_by_token_oracle(case):
     ctx[0][0] = 0                                          # a fresh request
     ctx[0][1] = 4085 if case == "mfma_long_context" else 37    # a prefix ending inside a page
     total_new = sum(n for _, n in plan)
-    runner = StageRunner(shape, syn, sigma=0.0, steps=total_new + 4, ctx_lens=ctx, gpu_pool_all_resident=True).load()
+    runner = StageRunner(shape, syn, sigma=0.0, steps=total_new + 4, ctx_lens=ctx, gpu_pool_all_resident=True,
+                         max_rows=max_rows).load()
     st = runner.stage
     assert st.get_stats()["engine"] == (0 if case == "generic_fp32" else 1)
     orc = make_oracle(shape, syn, runner.ctx0)
@@ -69,7 +74,7 @@ def test_prefill_matches_token_by_token_oracle(case):
         st.prefill(0, seq, n_new, hin.data_ptr(), hout.data_ptr(), cur)
         ref = _oracle_prefill(orc, syn, 0, seq, x)
         got = hout.float().cpu().numpy()
-        chunk = shape.seqs_per_mb
+        chunk = max_rows or shape.seqs_per_mb
         for r0 in range(0, n_new, chunk):
             assert rel_l2(got[r0:r0 + chunk], ref[r0:r0 + chunk]) <= tol, (seq, r0)
         # a single row must also hold the bar (the last one sees the longest context)
