@@ -67,10 +67,12 @@ void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int po
 // extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
 // (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)
 // and writes the A-tiled bf16 input of the output projection.  order[z] = sequence handled by grid
-// slice z (a permutation of 0..b-1, longest context first).
+// slice z (a permutation of 0..b-1, longest context first).  ev_start / ev_stop (both or neither): events that
+// receive the start and stop time of this dispatch (for timing the kernel alone).
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q,
                const uint16_t* pool, const int* table, const int* ctx, float* part_o, float* part_ml,
-               int chunk_pages, int max_chunks, int* counters, uint16_t* out_t, const int* order);
+               int chunk_pages, int max_chunks, int* counters, uint16_t* out_t, const int* order,
+               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---- fused pipeline for b <= 64 rows -----------------------------------------------------------------
 // x = hidden_in; ssq_out[i][0] = sum of squares of row i (other nb-1 entries 0); xg_t = x * gain as

@@ -5,6 +5,9 @@
 // stored in operand-fragment order (see common.hpp), so every global load is a lane-linear 16-byte
 // load (1 KiB contiguous per wave instruction) that lands directly in an MFMA operand register.
 #include <cstdlib>
+
+#include <hip/hip_ext.h>
+
 #include "kernels.hpp"
 
 namespace pmx {
@@ -1242,11 +1245,17 @@ void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int po
 
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
-               int max_chunks, int* counters, uint16_t* out_t, const int* order) {
+               int max_chunks, int* counters, uint16_t* out_t, const int* order, hipEvent_t ev_start,
+               hipEvent_t ev_stop) {
   constexpr int NW = kAttnWaves;
   const size_t lds = (size_t)NW * D.G * kORow * sizeof(float);
-  hipLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), lds, s, D, layer, q, pool, table,
-                     ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t, order);
+  if (ev_start && ev_stop)      // the events take the start and stop times of this dispatch itself
+    hipExtLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), (uint32_t)lds, s, ev_start, ev_stop,
+                          0u, D, layer, q, pool, table, ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t,
+                          order);
+  else
+    hipLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), lds, s, D, layer, q, pool, table,
+                       ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t, order);
 }
 
 void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uint16_t* gain, uint16_t* xg_t,
