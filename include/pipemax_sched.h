@@ -120,7 +120,8 @@ int pipemax_sched_plan(pipemax_sched_t* s, int64_t t, pipemax_sched_iter_t* out,
  * requests of D_k, then pipemax_prefetch_kv of P_t into D_j.  The step is enqueued before the
  * transfers so that the host-side wait of the prefetch overlaps it.  Afterwards the mirror's free
  * page count is checked against the stage's (ERR_STATE if they differ).  Other errors: those of
- * the stage calls, passed through.                                                                */
+ * the stage calls, passed through; the mirror is then put back to its state before the call, and if the
+ * failing call was not the first of the three the stage has moved on without it: attach again.     */
 int pipemax_sched_iterate(pipemax_sched_t* s, pipemax_stage_t* stage, int64_t t, const void* hidden_in,
                           void* hidden_out, void* hip_stream, pipemax_sched_iter_t* out,
                           int32_t* exec_ids, int32_t* prefetch_ids, int32_t* evict_ids);

@@ -64,7 +64,7 @@ int pipemax_xfer_destroy(pipemax_xfer_t* x);
 int pipemax_xfer_submit(pipemax_xfer_t* x, int kind, int dir, void* dst, const void* src, size_t bytes,
                         uint64_t* ticket);
 /* Blocks the calling thread until the request has completed (its data is at dst).  ERR_ARG for a
- * ticket that was never issued.                                                                    */
+ * ticket that was never issued; ERR_HIP if any copy of the orchestrator has failed so far (sticky).  */
 int pipemax_xfer_wait(pipemax_xfer_t* x, uint64_t ticket);
 /* Returns 1 if the request has completed, 0 if not, ERR_ARG for a ticket that was never issued.      */
 int pipemax_xfer_poll(pipemax_xfer_t* x, uint64_t ticket);
@@ -72,7 +72,7 @@ int pipemax_xfer_poll(pipemax_xfer_t* x, uint64_t ticket);
  * thread until the request's last copy has been SUBMITTED, then enqueues a wait for its completion
  * event on the stream.  Not available in the host-only mode (ERR_STATE).                            */
 int pipemax_xfer_stream_wait(pipemax_xfer_t* x, uint64_t ticket, void* hip_stream);
-/* Blocks until both queues are empty and every submitted copy has finished.                        */
+/* Blocks until both queues are empty and every submitted copy has finished.  ERR_HIP as for wait.   */
 int pipemax_xfer_drain(pipemax_xfer_t* x);
 
 int pipemax_xfer_get_stats(pipemax_xfer_t* x, pipemax_xfer_stats_t* out);

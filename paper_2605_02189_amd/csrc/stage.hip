@@ -641,6 +641,21 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     st->f_o = plan_gemm_skinny(h, nq, false);
     st->f_gu = plan_gemm_skinny(2 * F, h, true);
     st->f_d = plan_gemm_skinny(h, F, false);
+    // tuning overrides "splits,waves" (waves 4 or 8), e.g. PIPEMAX_PLAN_O=2,8
+    auto override_plan = [&](const char* name, GemmPlan& p, int K) {
+      const char* e = getenv(name);
+      int sp = 0, wv = 0;
+      if (!e || sscanf(e, "%d,%d", &sp, &wv) != 2 || (wv != 4 && wv != 8) || sp < 1) return;
+      const int KT = K / 16;
+      sp = std::max(1, std::min(sp, KT / (wv * 4)));
+      const int ksp = (KT + sp - 1) / sp;
+      p.split = p.fused_swiglu ? 1 : (KT + ksp - 1) / ksp;
+      p.nwk = wv;
+    };
+    override_plan("PIPEMAX_PLAN_QKV", st->f_qkv, h);
+    override_plan("PIPEMAX_PLAN_O", st->f_o, nq);
+    override_plan("PIPEMAX_PLAN_GU", st->f_gu, h);
+    override_plan("PIPEMAX_PLAN_D", st->f_d, F);
     const int fpad = std::min(mpad, 64);
     size_t part = 0;
     part = std::max(part, (size_t)st->f_qkv.split * fpad * D.Nqkv);
@@ -1228,7 +1243,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     };
     if (b <= 64) {
       // 5 launches per layer: every element-wise consumer runs in the epilogue of the GEMM before it
-      const int nb = D.h / 64;
+      const int nb = D.h / 64;       // partial sums of squares per row: one per column block of the residual GEMMs
       st->tbegin(PIPEMAX_K_NORM, cs);
       mfma::first(cs, b, D.h, (const uint16_t*)hidden_in, st->x, (const uint16_t*)st->w[0].g1, st->m_xn_t, st->m_ssq,
                   nb, M.d_ctx, st->rope_cs, D.rope_base);

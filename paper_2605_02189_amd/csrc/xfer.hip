@@ -67,6 +67,7 @@ struct pipemax_xfer {
   uint64_t next_ticket = 1;
   int host_us_per_mib = 0;
   bool stop = false, paused = false;
+  hipError_t hip_error = hipSuccess;   // first failure of a copy or event call (sticky)
   std::thread th;
 
   hipEvent_t get_event() {
@@ -102,13 +103,16 @@ struct pipemax_xfer {
     if ((int)log.size() < cfg.log_capacity) log.push_back({r->ticket, (uint64_t)off, (uint64_t)n, r->kind, r->dir});
     if (gpu) {
       hipStream_t s = (r->kind == PIPEMAX_XFER_URGENT) ? s_urgent[r->dir] : s_bulk[r->dir];
-      (void)hipMemcpyAsync(r->dst + off, r->src + off, n,
-                           r->dir == PIPEMAX_XFER_H2D ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, s);
+      auto note = [&](hipError_t e) {
+        if (e != hipSuccess && hip_error == hipSuccess) hip_error = e;
+      };
+      note(hipMemcpyAsync(r->dst + off, r->src + off, n,
+                          r->dir == PIPEMAX_XFER_H2D ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost, s));
       Flight f{r, get_event()};
-      (void)hipEventRecord(f.ev, s);
+      note(hipEventRecord(f.ev, s));
       if (last) {
         r->ev_last = get_event();
-        (void)hipEventRecord(r->ev_last, s);
+        note(hipEventRecord(r->ev_last, s));
         r->all_submitted = true;
         cv_done.notify_all();
       }
@@ -132,7 +136,10 @@ struct pipemax_xfer {
   // retires finished copies (in submission order per stream); returns true if anything is still in flight
   bool reap() {   // mu held
     auto sweep = [&](std::deque<Flight>& d) {
-      while (!d.empty() && hipEventQuery(d.front().ev) == hipSuccess) {
+      while (!d.empty()) {
+        const hipError_t q = hipEventQuery(d.front().ev);
+        if (q == hipErrorNotReady) break;
+        if (q != hipSuccess && hip_error == hipSuccess) hip_error = q;   // retired all the same: nothing waits forever
         Flight f = d.front();
         d.pop_front();
         ev_pool.push_back(f.ev);
@@ -278,6 +285,7 @@ int pipemax_xfer_wait(pipemax_xfer_t* x, uint64_t ticket) {
   if (it == x->live.end()) return PIPEMAX_OK;
   std::shared_ptr<Request> r = it->second;
   x->cv_done.wait(lk, [&] { return r->done; });
+  if (x->hip_error != hipSuccess) XF_FAIL(PIPEMAX_ERR_HIP, "a copy failed: %s", hipGetErrorString(x->hip_error));
   return PIPEMAX_OK;
 }
 
@@ -308,6 +316,7 @@ int pipemax_xfer_drain(pipemax_xfer_t* x) {
   if (!x) XF_FAIL(PIPEMAX_ERR_ARG, "null orchestrator");
   std::unique_lock<std::mutex> lk(x->mu);
   x->cv_done.wait(lk, [&] { return x->live.empty(); });
+  if (x->hip_error != hipSuccess) XF_FAIL(PIPEMAX_ERR_HIP, "a copy failed: %s", hipGetErrorString(x->hip_error));
   return PIPEMAX_OK;
 }
 
