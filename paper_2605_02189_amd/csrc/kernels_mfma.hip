@@ -295,8 +295,9 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
         wn1[kk] = ok ? ld_stream(wp1 + (int64_t)(kn + kk) * 64) : zero4;
       }
     }
-    // (forcing the LDS reads several fragments ahead of their MFMAs with scheduling barriers was
-    // measured slower than the compiler's read-then-two-MFMAs order: the MFMAs run asynchronously)
+    // (reading the A fragments of the next k-step before the MFMAs of this one, pinned with scheduling
+    // barriers, was measured 20 % slower than the compiler's read-then-two-MFMAs order, here and in the
+    // 8-wave variant)
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
       const bf16x8 B0 = __builtin_bit_cast(bf16x8, wc0[kk]);
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 // HBM waits are covered by the other's MFMAs.  The two row halves of a column group read the same weight
 // fragments (the second read is an L1 / L2 hit).  Whole blocks of 256 rows only.
 // =================================================================================================
-template <int KC>
+template <int KC, bool WCACHED>
 __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
                                                  float* __restrict__ part, int N, int KT, int ksp,
                                                  int64_t split_stride) {
@@ -356,6 +357,9 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
   const uint4* wp0 = Wt + (int64_t)nt0 * KT * 64 + lane;
   const uint4* wp1 = wp0 + (int64_t)KT * 64;
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  // several row blocks (grid.z > 1) and the two row halves of a block read the same weight fragments: those
+  // loads should stay in the caches, a single pass over the weights should not
+  auto ldw = [](const uint4* p) { return WCACHED ? *p : ld_stream(p); };
 
   f32x16 acc[2][MTW];
 #pragma unroll
@@ -384,8 +388,8 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
       const bool ok = k0 + kk < k1;
-      wc0[kk] = ok ? ld_stream(wp0 + (int64_t)(k0 + kk) * 64) : zero4;
-      wc1[kk] = ok ? ld_stream(wp1 + (int64_t)(k0 + kk) * 64) : zero4;
+      wc0[kk] = ok ? ldw(wp0 + (int64_t)(k0 + kk) * 64) : zero4;
+      wc1[kk] = ok ? ldw(wp1 + (int64_t)(k0 + kk) * 64) : zero4;
     }
   }
   __builtin_amdgcn_s_waitcnt(0);
@@ -399,8 +403,8 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
 #pragma unroll
       for (int kk = 0; kk < KC; ++kk) {
         const bool ok = kn + kk < k1;
-        wn0[kk] = ok ? ld_stream(wp0 + (int64_t)(kn + kk) * 64) : zero4;
-        wn1[kk] = ok ? ld_stream(wp1 + (int64_t)(kn + kk) * 64) : zero4;
+        wn0[kk] = ok ? ldw(wp0 + (int64_t)(kn + kk) * 64) : zero4;
+        wn1[kk] = ok ? ldw(wp1 + (int64_t)(kn + kk) * 64) : zero4;
       }
     }
 #pragma unroll
@@ -1207,9 +1211,12 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
     if (one_wave_per_simd)
       hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
                          part, full * 256, N, KT, ksp, stride);
+    else if (getenv("PIPEMAX_GEMM_WSTREAM") != nullptr)      // tuning switch: non-temporal weight loads
+      hipLaunchKernelGGL((k_gemm_l2<4, false>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
+                         (const uint4*)Wt, part, N, KT, ksp, stride);
     else
-      hipLaunchKernelGGL((k_gemm_l2<4>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt, (const uint4*)Wt,
-                         part, N, KT, ksp, stride);
+      hipLaunchKernelGGL((k_gemm_l2<4, true>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
+                         (const uint4*)Wt, part, N, KT, ksp, stride);
   }
   if (rem) {     // the remaining rows with the smallest tile count that covers them
     const uint4* Xr = (const uint4*)Xt + (int64_t)full * 8 * KT * 64;
