@@ -113,7 +113,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
-              "(stages of a pipeline are independent processes, see DESIGN.md)", file=sys.stderr)
+              "(the stages of a pipeline are independent processes, one per GPU; nothing here runs on a second GPU)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -18,7 +18,7 @@ no residency, no streams.
 The paper inherits the transformer arithmetic from the serving system it builds
 on and never spells it out.  The readings taken here (pre-norm residual blocks,
 no biases, half-split RoPE pairs, softmax scale 1/sqrt(d), the new token attends
-to itself at position L_i) are listed in the design doc.
+to itself at position L_i) are stated where each function implements them.
 
 Pins (tests/test_oracle_pins.py): incremental-with-cache == brute-force full
 causal recompute; softmax rows sum to 1; one cached token returns its V exactly;
