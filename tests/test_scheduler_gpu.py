@@ -44,6 +44,7 @@ def test_scheduler_iterations_on_the_stage_match_both_oracles(static):
         x = syn.hidden(t, maxb)
         hin = torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).to("cuda:0")
         hout = torch.zeros_like(hin)
+        torch.cuda.synchronize()          # the fill runs on torch's stream, the step on the library's own
         got = sched.iterate(st, t, hin.data_ptr(), hout.data_ptr(), cur)
         want = sim.iterate(t)
         print(f"t {t} exec {got['exec']} prefetch {got['prefetch']} evict {got['evict']} budget "
