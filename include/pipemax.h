@@ -17,7 +17,10 @@
  *  - "host" pointers are ordinary host memory owned by the caller and are read or
  *    written before the call returns.  "device" pointers are HIP device memory
  *    owned by the caller (e.g. PyTorch tensors) on the stage's device; the work on
- *    them is enqueued on the stream given to the call.
+ *    them is enqueued on the stream given to the call and they must stay allocated, and
+ *    inputs unmodified, until that work has completed (a NULL stream means the stage's
+ *    own compute stream, which is non-blocking: it does not synchronise with the legacy
+ *    default stream).
  *  - The stage owns its weights, the GPU page pool, the pinned host page pool, the
  *    staging buffers, two side streams (host->device and device->host) and all
  *    events.  prefetch / decode_step / evict enqueue work and return; ordering
