@@ -40,6 +40,7 @@ void set_error(const char* fmt, ...) {
 
 namespace {
 
+constexpr int kFusedRows = 128;   // up to this many rows take the fused 5-launch-per-layer pipeline
 constexpr int kSlots = 4;        // depth of the write-back staging ring
 constexpr int kTableRing = 8;    // depth of the block-table upload ring
 constexpr int kMaxRunPages = 128;  // longest single prefetch copy, in pages (64 MiB at 512 KiB pages)
@@ -656,14 +657,14 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     override_plan("PIPEMAX_PLAN_O", st->f_o, nq);
     override_plan("PIPEMAX_PLAN_GU", st->f_gu, h);
     override_plan("PIPEMAX_PLAN_D", st->f_d, F);
-    const int fpad = std::min(mpad, 64);
+    const int fpad = std::min(mpad, kFusedRows);
     size_t part = 0;
     part = std::max(part, (size_t)st->f_qkv.split * fpad * D.Nqkv);
     part = std::max(part, (size_t)st->f_o.split * fpad * h);
     part = std::max(part, (size_t)st->f_gu.split * fpad * 2 * F);
     part = std::max(part, (size_t)st->f_d.split * fpad * h);
     // the un-fused path plans its split per call from the row count; the partial buffer covers every count
-    for (int rows = 96; rows <= mpad; rows += 32) {
+    for (int rows = kFusedRows + 32; rows <= mpad; rows += 32) {
       part = std::max(part, (size_t)plan_rows(D.Nqkv, h, rows).split * rows * D.Nqkv);
       part = std::max(part, (size_t)plan_rows(h, nq, rows).split * rows * h);
       part = std::max(part, (size_t)plan_rows(2 * F, h, rows).split * rows * 2 * F);
@@ -683,10 +684,10 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     const size_t n_cnt = (size_t)std::max(D.Nqkv, h) / 64 + 1;
     PMX_TRY(dev_alloc(st, &st->m_cnt_gemm, n_cnt));
     PMX_TRY(dev_alloc(st, &st->m_cnt_attn, (size_t)maxb * c.n_kv_heads));
-    PMX_TRY(dev_alloc(st, &st->m_ssq, (size_t)64 * (h / 64)));
+    PMX_TRY(dev_alloc(st, &st->m_ssq, (size_t)kFusedRows * (h / 64)));
     PMX_TRY_HIP(hipMemset(st->m_cnt_gemm, 0, n_cnt * sizeof(int)));
     PMX_TRY_HIP(hipMemset(st->m_cnt_attn, 0, (size_t)maxb * c.n_kv_heads * sizeof(int)));
-    PMX_TRY_HIP(hipMemset(st->m_ssq, 0, (size_t)64 * (h / 64) * sizeof(float)));
+    PMX_TRY_HIP(hipMemset(st->m_ssq, 0, (size_t)kFusedRows * (h / 64) * sizeof(float)));
   }
   if (c.flags & PIPEMAX_FLAG_CAPTURE_LAYERS) PMX_TRY(dev_alloc(st, &st->layer_out, (size_t)c.n_layers * maxb * h));
 
@@ -1241,7 +1242,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
                         tp ? tp->b : nullptr);
       }
     };
-    if (b <= 64) {
+    if (b <= kFusedRows) {
       // 5 launches per layer: every element-wise consumer runs in the epilogue of the GEMM before it
       const int nb = D.h / 64;       // partial sums of squares per row: one per column block of the residual GEMMs
       st->tbegin(PIPEMAX_K_NORM, cs);
@@ -1266,7 +1267,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
         mfma::gemm_swiglu(cs, b, D.h, D.F, D.eps, st->m_xn_t, (const uint16_t*)L.wgu, st->m_ssq, nb, st->m_act_t,
-                          st->f_gu.nwk);
+                          b > 64 ? 8 : st->f_gu.nwk);   // four row tiles per wave: 8 waves keep two waves per SIMD
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
         mfma::gemm_resid(cs, b, D.F, D.h, st->m_act_t, (const uint16_t*)L.wd, st->m_part, st->m_cnt_gemm, st->x,

@@ -142,13 +142,15 @@ def test_bf16_matrix_core_path_ragged():
     runner.stage.destroy()
 
 
-def test_bf16_wide_batch_uses_the_lds_staged_gemm():
-    """More than 64 rows: the GEMMs run on the LDS-staged split-K kernel (3 row tiles of 32, the last
-    one partial) with the separate SwiGLU pass."""
+@pytest.mark.parametrize("rows", [70, 150])
+def test_bf16_wide_batch(rows):
+    """More than 64 rows.  70 rows: the fused pipeline with four row tiles per wave (the last two partial
+    or empty).  150 rows: the large-tile GEMM (five row tiles, the last one partial) with the separate
+    element-wise kernels."""
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
-    shape = _mid_shape(n_layers=1, n_microbatches=2, seqs_per_mb=70, ctx_lo=3, ctx_hi=60, decode_steps=4)
+    shape = _mid_shape(n_layers=1, n_microbatches=2, seqs_per_mb=rows, ctx_lo=3, ctx_hi=60, decode_steps=4)
     syn = SynthInputs(shape, seed=8, pool_elems=1 << 23, gain_jitter=0.1)
     runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS).load()
     assert runner.stage.get_stats()["engine"] == 1
