@@ -50,8 +50,10 @@ void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, con
 // part[s][m][n] = X[m][k-range s] @ W[k-range s][n]   (X A-tiled, W B-tiled, fp32 partials)
 // Mpad = 32*MT rows are computed, rows < M are stored.  N % (32*wn) == 0, wn in {4, 8}; wn == 0 selects the
 // large-tile kernel for 65..256 rows (needs N % 256 == 0).
+// swiglu_act_t (large-tile kernel, W = interleaved gate/up matrix, one split only): instead of the partials the
+// kernel writes silu(gate) * up as the A-tiled bf16 operand of the next GEMM (K = N / 2); ignored otherwise.
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
-          int n_split, int wn);
+          int n_split, int wn, uint16_t* swiglu_act_t = nullptr);
 
 void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(WN * 64) void k_gemm(const uint4* __restrict__ Xt,
 template <int MT, int KC>
 __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
                                                 float* __restrict__ part, int M, int N, int KT, int ksp,
-                                                int64_t split_stride) {
+                                                int64_t split_stride, uint16_t* __restrict__ act_t) {
   constexpr int NF = MT * KC;            // X fragments per chunk
   constexpr int XPT = NF / 4;            // X fragments loaded per wave
   static_assert(NF % 4 == 0, "chunk must split evenly over 4 waves");
@@ -240,6 +240,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
   Xt += (int64_t)blockIdx.z * MT * KT * 64;
   part += (int64_t)blockIdx.z * MT * 32 * N;
   M -= (int)blockIdx.z * MT * 32;
+  const int row0 = (int)blockIdx.z * MT * 32;
   const int k0 = blockIdx.y * ksp;
   const int k1 = min(KT, k0 + ksp);
   const int nchunks = (k1 - k0 + KC - 1) / KC;
@@ -320,6 +321,20 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
     __syncthreads();
   }
 
+  if (act_t != nullptr) {
+    // gate/up matrix without a K split: the wave's two column tiles are a gate tile and its up tile, so
+    // silu(gate) * up is formed here and written as the A-tiled bf16 operand of the down projection
+    const int col = (nt0 >> 1) * 32 + (lane & 31);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float g = acc[0][mt][r], u = acc[1][mt][r];
+        if (m < M) act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
+      }
+    return;
+  }
   float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt0 * 32 + (lane & 31);
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt)
@@ -341,7 +356,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 template <int KC, bool WCACHED>
 __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
                                                  float* __restrict__ part, int N, int KT, int ksp,
-                                                 int64_t split_stride) {
+                                                 int64_t split_stride, uint16_t* __restrict__ act_t) {
   constexpr int MTB = 8, MTW = 4;        // row tiles per block / per wave
   constexpr int NF = MTB * KC;           // X fragments per chunk
   constexpr int XPT = NF / 8;            // X fragments loaded per wave
@@ -429,6 +444,19 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
     __syncthreads();
   }
 
+  if (act_t != nullptr) {      // gate/up without a K split: silu(gate) * up, as in the 4-wave kernel
+    const int col = (nt0 >> 1) * 32 + (lane & 31);
+    const int row0 = (int)blockIdx.z * MTB * 32;
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float g = acc[0][mt][r], u = acc[1][mt][r];
+        act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
+      }
+    return;
+  }
   float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt0 * 32 + (lane & 31);
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt)
@@ -1198,40 +1226,43 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 }
 
 static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
-                       int n_split) {
+                       int n_split, uint16_t* act_t) {
   const int KT = K / 16;
   const int ksp = (KT + n_split - 1) / n_split;
   const int S = (KT + ksp - 1) / ksp;
   const int MTall = (M + 31) / 32;
   const int64_t stride = (int64_t)MTall * 32 * N;
   const int full = M / 256, rem = M - full * 256;
+  if (S > 1) act_t = nullptr;       // the fused SwiGLU epilogue needs the whole K range in one work-group
   dim3 block(256);
   if (full) {    // whole blocks of 256 rows: one launch, row blocks along grid.z
     static const bool one_wave_per_simd = getenv("PIPEMAX_GEMM_L1") != nullptr;    // tuning switch
     if (one_wave_per_simd)
       hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
-                         part, full * 256, N, KT, ksp, stride);
+                         part, full * 256, N, KT, ksp, stride, act_t);
     else if (getenv("PIPEMAX_GEMM_WSTREAM") != nullptr)      // tuning switch: non-temporal weight loads
       hipLaunchKernelGGL((k_gemm_l2<4, false>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
-                         (const uint4*)Wt, part, N, KT, ksp, stride);
+                         (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
     else
       hipLaunchKernelGGL((k_gemm_l2<4, true>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
-                         (const uint4*)Wt, part, N, KT, ksp, stride);
+                         (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
   }
   if (rem) {     // the remaining rows with the smallest tile count that covers them
     const uint4* Xr = (const uint4*)Xt + (int64_t)full * 8 * KT * 64;
     float* pr = part + (int64_t)full * 256 * N;
+    // the A-tiled output of the remaining rows starts at row tile full * 8 of the next GEMM's operand
+    uint16_t* ar = act_t ? act_t + (int64_t)full * 8 * (N >> 5) * 512 : nullptr;
     dim3 grid(N / 256, S);
     if (rem <= 128)
-      hipLaunchKernelGGL((k_gemm_l<4, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride);
+      hipLaunchKernelGGL((k_gemm_l<4, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride, ar);
     else
-      hipLaunchKernelGGL((k_gemm_l<8, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride);
+      hipLaunchKernelGGL((k_gemm_l<8, 4>), grid, block, 0, s, Xr, (const uint4*)Wt, pr, rem, N, KT, ksp, stride, ar);
   }
 }
 
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
-          int n_split, int wn) {
-  if (wn == 0) { gemm_large(s, Xt, Wt, part, M, K, N, n_split); return; }
+          int n_split, int wn, uint16_t* swiglu_act_t) {
+  if (wn == 0) { gemm_large(s, Xt, Wt, part, M, K, N, n_split, swiglu_act_t); return; }
   if (wn == 8) gemm_wn<8>(s, Xt, Wt, part, M, K, N, n_split);
   else gemm_wn<4>(s, Xt, Wt, part, M, K, N, n_split);
 }

@@ -1314,11 +1314,15 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
                          st->m_xn_t, nullptr);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
-        run_gemm(p_gu, st->m_xn_t, L.wgu, D.h, 2 * D.F);
+        const bool gu_fused = (p_gu.wn == 0 && p_gu.split == 1);     // SwiGLU in the GEMM's epilogue
+        mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wgu, st->m_part, b, D.h, 2 * D.F, p_gu.split, p_gu.wn,
+                   gu_fused ? st->m_act_t : nullptr);
         st->tend(cs);
-        st->tbegin(PIPEMAX_K_SWIGLU, cs);
-        mfma::swiglu(cs, b, D.F, st->m_part, p_gu.split, s_gu, st->m_act_t);
-        st->tend(cs);
+        if (!gu_fused) {
+          st->tbegin(PIPEMAX_K_SWIGLU, cs);
+          mfma::swiglu(cs, b, D.F, st->m_part, p_gu.split, s_gu, st->m_act_t);
+          st->tend(cs);
+        }
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
         run_gemm(p_d, st->m_act_t, L.wd, D.F, D.h);
         st->tend(cs);

@@ -29,7 +29,8 @@ def _oracle_prefill(orc, syn, mb, seq, x):
     return out
 
 
-@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_long_context", "generic_fp32"])
+@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_xl_wide_ffn", "mfma_long_context",
+                                  "generic_fp32"])
 def test_prefill_matches_token_by_token_oracle(case):
     import torch
     assert torch.cuda.is_available()
@@ -41,15 +42,18 @@ def test_prefill_matches_token_by_token_oracle(case):
         shape = CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=6)
         tol, plan = 1e-5, [(0, 21), (1, 19), (0, 8)]
     else:
-        b = 70 if case == "mfma_wide_chunks" else 6 if case == "mfma_xl_chunks" else 20
-        max_rows = 600 if case == "mfma_xl_chunks" else None      # two 256-row blocks + a remainder per pass
-        shape = StageShape(name=case, n_layers=2, hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=2816,
+        xl = case in ("mfma_xl_chunks", "mfma_xl_wide_ffn")
+        b = 70 if case == "mfma_wide_chunks" else 6 if xl else 20
+        max_rows = 600 if xl else None                            # two 256-row blocks + a remainder per pass
+        # the wide FFN makes the gate/up GEMM of a 600-row pass un-split: SwiGLU runs in its epilogue
+        shape = StageShape(name=case, n_layers=1 if case == "mfma_xl_wide_ffn" else 2, hidden=1024, n_q_heads=8,
+                           n_kv_heads=2, head_dim=128, ffn=16384 if case == "mfma_xl_wide_ffn" else 2816,
                            dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
                            decode_steps=1)
         tol = 1e-2
         # (sequence, new tokens): several chunks each; sequence 1 continues an existing prefix
         plan = [(0, 45), (1, 30), (0, 17)] if b == 20 else [(0, 150), (1, 75)]
-        if case == "mfma_xl_chunks":
+        if xl:
             plan = [(0, 700), (1, 300)]
         if case == "mfma_long_context":                    # beyond the chunk kernel's 256 pages: per-row kernel
             plan = [(1, 30), (0, 5)]
