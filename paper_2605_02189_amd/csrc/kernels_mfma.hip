@@ -353,7 +353,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 // HBM waits are covered by the other's MFMAs.  The two row halves of a column group read the same weight
 // fragments (the second read is an L1 / L2 hit).  Whole blocks of 256 rows only.
 // =================================================================================================
-template <int KC, bool WCACHED>
+template <int KC>
 __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
                                                  float* __restrict__ part, int N, int KT, int ksp,
                                                  int64_t split_stride, uint16_t* __restrict__ act_t) {
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
   // several row blocks (grid.z > 1) and the two row halves of a block read the same weight fragments: those
   // loads should stay in the caches, a single pass over the weights should not
-  auto ldw = [](const uint4* p) { return WCACHED ? *p : ld_stream(p); };
+  auto ldw = [](const uint4* p) { return *p; };
 
   f32x16 acc[2][MTW];
 #pragma unroll
@@ -445,6 +445,155 @@ __global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, c
   }
 
   if (act_t != nullptr) {      // gate/up without a K split: silu(gate) * up, as in the 4-wave kernel
+    const int col = (nt0 >> 1) * 32 + (lane & 31);
+    const int row0 = (int)blockIdx.z * MTB * 32;
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float g = acc[0][mt][r], u = acc[1][mt][r];
+        act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
+      }
+    return;
+  }
+  float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt0 * 32 + (lane & 31);
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        out[(int64_t)m * N + nt * 32] = acc[nt][mt][r];
+      }
+}
+
+// =================================================================================================
+// 256 x 256 tile, 8 waves, both operands through an LDS ring of R slots of TWO k-steps each, loads spread out.
+// Cycle counters inside the two-chunk kernel show where its time goes: a wave spends about 40 % of a chunk
+// ISSUING its twelve 1 KiB loads.  The vector memory path of a compute unit accepts 64 bytes per cycle, so the
+// 96 KiB a work-group pulls per chunk keep it busy for 1500 cycles -- three quarters of the chunk's MFMA time
+// -- and because a wave issues in order, a wave queued behind that burst issues no MFMA either.  So:
+//   * every fragment is fetched once per work-group (no second fetch of the weights by the other row half):
+//     16 KiB per k-step, half of the MFMA time at full rate;
+//   * the four loads a wave owes per slot are placed between groups of four MFMAs, never in a burst behind
+//     the barrier;
+//   * one barrier per two k-steps (16 MFMAs per wave), and the fragments of the slot's second k-step are read
+//     from LDS while the first is multiplied.
+//   A load issued during step s fills the slot read in step s + R - 1: it has R - 2 whole steps to land.
+//   Whole blocks of 256 rows, k ranges of an even number of k-steps.
+// =================================================================================================
+template <int R>
+__global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
+                                                 float* __restrict__ part, int N, int KT, int ksp,
+                                                 int64_t split_stride, uint16_t* __restrict__ act_t) {
+  constexpr int MTB = 8, MTW = 4;
+  constexpr int kSlot = 2048;                       // uint4 per slot: [X | W][k-step 0 | 1][tile 0..7][64]
+  extern __shared__ uint4 ring[];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, rh = w >> 2, wc = w & 3;
+  const int nt0 = (blockIdx.x * 4 + wc) * 2;
+  Xt += (int64_t)blockIdx.z * MTB * KT * 64;
+  part += (int64_t)blockIdx.z * MTB * 32 * N;
+  const int k0 = blockIdx.y * ksp;
+  const int ns = (min(KT, k0 + ksp) - k0) >> 1;     // steps of two k-steps
+  const uint4* xp = Xt + ((int64_t)w * KT + k0) * 64 + lane;                          // row tile w
+  const uint4* wp = Wt + ((int64_t)(blockIdx.x * 8 + w) * KT + k0) * 64 + lane;       // column tile w of the block
+
+  f32x16 acc[2][MTW];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
+
+  // load i (0..3) of step s into slot `slot`: X k-step 0, X k-step 1, W k-step 0, W k-step 1 of tile w
+  auto issue = [&](int s, int slot, int i) {
+    const uint4* src = ((i & 2) ? wp : xp) + (int64_t)(2 * s + (i & 1)) * 64;
+    uint4* dst = ring + (size_t)slot * kSlot + ((i & 2) ? 1024 : 0) + (i & 1) * 512 + w * 64;
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                     (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+  };
+  // Every step issues exactly four loads, so "at most 4 (R - 2) outstanding" always means that the next
+  // step's slot has landed; past the end of the k range the loads re-fetch the last step into a slot that is
+  // not read again (no branch in the loop body, and the counter arithmetic stays uniform).
+  constexpr int kAhead = 4 * (R - 2);
+  constexpr int kWaitAhead = (kAhead & 0xF) | ((kAhead >> 4) << 14) | (0x7 << 4) | (0xF << 8);   // vmcnt(kAhead) only
+  if (ns > 0) {
+#pragma unroll
+    for (int r = 0; r < R - 1; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) issue(min(r, ns - 1), r, i);
+    __builtin_amdgcn_s_waitcnt(kWaitAhead);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  for (int s0 = 0; s0 < ns; s0 += R) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int s = s0 + r;
+      if (s < ns) {
+        const int sn = min(s + R - 1, ns - 1);
+        const int nslot = (r + R - 1) % R;
+        const uint4* base = ring + (size_t)r * kSlot;
+        // (the reads are typed as MFMA operands at the load: the compiler makes a wave wait for ALL its
+        // outstanding direct-to-LDS loads before an LDS read typed as an integer vector, which would drain
+        // the ring every step; the slot read here is covered by the counted wait and the barrier below)
+        bf16x8 a0[MTW], a1[MTW], b0[2], b1[2];
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) a0[mt] = __builtin_bit_cast(bf16x8, base[(rh * MTW + mt) * 64 + lane]);
+        b0[0] = __builtin_bit_cast(bf16x8, base[1024 + (wc * 2) * 64 + lane]);
+        b0[1] = __builtin_bit_cast(bf16x8, base[1024 + (wc * 2 + 1) * 64 + lane]);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(sn, nslot, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[0], acc[0][mt], 0, 0, 0);
+          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[1], acc[1][mt], 0, 0, 0);
+        }
+        // the second k-step's fragments are read behind the first four MFMAs (while direct-to-LDS loads are
+        // in flight every compiler-placed LDS wait is a full one, so reads issued earlier would not overlap)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) a1[mt] = __builtin_bit_cast(bf16x8, base[512 + (rh * MTW + mt) * 64 + lane]);
+        b1[0] = __builtin_bit_cast(bf16x8, base[1024 + 512 + (wc * 2) * 64 + lane]);
+        b1[1] = __builtin_bit_cast(bf16x8, base[1024 + 512 + (wc * 2 + 1) * 64 + lane]);
+        issue(sn, nslot, 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 2; mt < MTW; ++mt) {
+          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[0], acc[0][mt], 0, 0, 0);
+          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[1], acc[1][mt], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        issue(sn, nslot, 2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[0], acc[0][mt], 0, 0, 0);
+          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[1], acc[1][mt], 0, 0, 0);
+          if (mt == 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue(sn, nslot, 3);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        // bare barrier (no fence): this step's LDS reads have been consumed by its MFMAs, and the counted
+        // wait is what makes the next slot's direct-to-LDS data visible
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWaitAhead);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0);      // the re-fetches past the end are still writing LDS
+
+  if (act_t != nullptr) {      // gate/up without a K split: silu(gate) * up
     const int col = (nt0 >> 1) * 32 + (lane & 31);
     const int row0 = (int)blockIdx.z * MTB * 32;
 #pragma unroll
@@ -1228,23 +1377,35 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
                        int n_split, uint16_t* act_t) {
   const int KT = K / 16;
-  const int ksp = (KT + n_split - 1) / n_split;
+  int ksp = (KT + n_split - 1) / n_split;
   const int S = (KT + ksp - 1) / ksp;
+  // k ranges of an even number of k-steps (what the ring kernel needs) when that keeps the number of splits
+  if (KT % 2 == 0 && (ksp & 1) && (KT + ksp) / (ksp + 1) == S) ksp += 1;
   const int MTall = (M + 31) / 32;
   const int64_t stride = (int64_t)MTall * 32 * N;
   const int full = M / 256, rem = M - full * 256;
   if (S > 1) act_t = nullptr;       // the fused SwiGLU epilogue needs the whole K range in one work-group
   dim3 block(256);
   if (full) {    // whole blocks of 256 rows: one launch, row blocks along grid.z
-    static const bool one_wave_per_simd = getenv("PIPEMAX_GEMM_L1") != nullptr;    // tuning switch
-    if (one_wave_per_simd)
+    // tuning switches: the 4-wave tile, or the two-chunk 8-wave kernel, instead of the ring kernel
+    static const bool four_waves = getenv("PIPEMAX_GEMM_L1") != nullptr;
+    static const bool two_chunk = getenv("PIPEMAX_GEMM_TWO_CHUNK") != nullptr;
+    const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);      // the ring kernel's slots hold two k-steps
+    if (four_waves)
       hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
                          part, full * 256, N, KT, ksp, stride, act_t);
-    else if (getenv("PIPEMAX_GEMM_WSTREAM") != nullptr)      // tuning switch: non-temporal weight loads
-      hipLaunchKernelGGL((k_gemm_l2<4, false>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
+    else if (even && !two_chunk) {
+      constexpr int R = 4;
+      constexpr int lds = R * 2048 * 16;
+      static bool attr_set = false;
+      if (!attr_set) {
+        (void)hipFuncSetAttribute((const void*)k_gemm_l5<R>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+      }
+      hipLaunchKernelGGL((k_gemm_l5<R>), dim3(N / 256, S, full), dim3(512), lds, s, (const uint4*)Xt,
                          (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
-    else
-      hipLaunchKernelGGL((k_gemm_l2<4, true>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
+    } else
+      hipLaunchKernelGGL((k_gemm_l2<4>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
                          (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
   }
   if (rem) {     // the remaining rows with the smallest tile count that covers them

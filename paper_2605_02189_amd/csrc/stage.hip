@@ -387,7 +387,8 @@ GemmPlan plan_gemm_large(int N, int K, int M) {
   const int bn = (N / 256) * ((M + 255) / 256), KT = K / 16;
   int S = std::max(1, (256 + bn / 2) / bn);
   S = std::max(1, std::min(S, KT / 16));
-  const int ksp = (KT + S - 1) / S;
+  int ksp = (KT + S - 1) / S;
+  if (KT % 2 == 0) ksp += ksp & 1;      // the ring kernel works on pairs of k-steps
   p.split = (KT + ksp - 1) / ksp;
   return p;
 }
