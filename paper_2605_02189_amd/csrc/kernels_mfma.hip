@@ -297,8 +297,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
       }
     }
     // (reading the A fragments of the next k-step before the MFMAs of this one, pinned with scheduling
-    // barriers, was measured 20 % slower than the compiler's read-then-two-MFMAs order, here and in the
-    // 8-wave variant)
+    // barriers, was measured 20 % slower here than the compiler's read-then-two-MFMAs order)
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
       const bf16x8 B0 = __builtin_bit_cast(bf16x8, wc0[kk]);
@@ -348,133 +347,13 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 }
 
 // =================================================================================================
-// The same 256 x 256 tile with 8 waves: wave (rh, wc) owns row half rh (4 row tiles) of column group wc
-// (2 column tiles), i.e. 8 accumulator tiles, so two waves share a SIMD and one wave's LDS / barrier /
-// HBM waits are covered by the other's MFMAs.  The two row halves of a column group read the same weight
-// fragments (the second read is an L1 / L2 hit).  Whole blocks of 256 rows only.
-// =================================================================================================
-template <int KC>
-__global__ __launch_bounds__(512) void k_gemm_l2(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
-                                                 float* __restrict__ part, int N, int KT, int ksp,
-                                                 int64_t split_stride, uint16_t* __restrict__ act_t) {
-  constexpr int MTB = 8, MTW = 4;        // row tiles per block / per wave
-  constexpr int NF = MTB * KC;           // X fragments per chunk
-  constexpr int XPT = NF / 8;            // X fragments loaded per wave
-  static_assert(NF % 8 == 0, "chunk must split evenly over 8 waves");
-  __shared__ uint4 xs[2][NF * 64];
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, rh = w >> 2, wc = w & 3;
-  const int nt0 = (blockIdx.x * 4 + wc) * 2;
-  Xt += (int64_t)blockIdx.z * MTB * KT * 64;
-  part += (int64_t)blockIdx.z * MTB * 32 * N;
-  const int k0 = blockIdx.y * ksp;
-  const int k1 = min(KT, k0 + ksp);
-  const int nchunks = (k1 - k0 + KC - 1) / KC;
-  const uint4* wp0 = Wt + (int64_t)nt0 * KT * 64 + lane;
-  const uint4* wp1 = wp0 + (int64_t)KT * 64;
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  // several row blocks (grid.z > 1) and the two row halves of a block read the same weight fragments: those
-  // loads should stay in the caches, a single pass over the weights should not
-  auto ldw = [](const uint4* p) { return *p; };
-
-  f32x16 acc[2][MTW];
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-    for (int mt = 0; mt < MTW; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
-
-  uint4 wc0[KC], wc1[KC], wn0[KC], wn1[KC];
-  auto load_x = [&](int kc0, int buf) {
-#pragma unroll
-    for (int t = 0; t < XPT; ++t) {
-      const int f = w + t * 8, mt = f / KC, kk = f - mt * KC;
-      if (kc0 + kk < k1)
-        __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)(Xt + ((int64_t)mt * KT + kc0 + kk) * 64 + lane),
-            (void __attribute__((address_space(3)))*)(&xs[buf][f * 64]), 16, 0, 0);
-      else
-        xs[buf][f * 64 + lane] = zero4;
-    }
-  };
-
-  if (nchunks > 0) {
-    load_x(k0, 0);
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      const bool ok = k0 + kk < k1;
-      wc0[kk] = ok ? ldw(wp0 + (int64_t)(k0 + kk) * 64) : zero4;
-      wc1[kk] = ok ? ldw(wp1 + (int64_t)(k0 + kk) * 64) : zero4;
-    }
-  }
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    const int buf = c & 1;
-    const bool more = (c + 1 < nchunks);
-    if (more) {
-      const int kn = k0 + (c + 1) * KC;
-      load_x(kn, buf ^ 1);
-#pragma unroll
-      for (int kk = 0; kk < KC; ++kk) {
-        const bool ok = kn + kk < k1;
-        wn0[kk] = ok ? ldw(wp0 + (int64_t)(kn + kk) * 64) : zero4;
-        wn1[kk] = ok ? ldw(wp1 + (int64_t)(kn + kk) * 64) : zero4;
-      }
-    }
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      const bf16x8 B0 = __builtin_bit_cast(bf16x8, wc0[kk]);
-      const bf16x8 B1 = __builtin_bit_cast(bf16x8, wc1[kk]);
-#pragma unroll
-      for (int mt = 0; mt < MTW; ++mt) {
-        const bf16x8 A = __builtin_bit_cast(bf16x8, xs[buf][((rh * MTW + mt) * KC + kk) * 64 + lane]);
-        acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B0, acc[0][mt], 0, 0, 0);
-        acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B1, acc[1][mt], 0, 0, 0);
-      }
-    }
-    if (more) {
-#pragma unroll
-      for (int kk = 0; kk < KC; ++kk) {
-        wc0[kk] = wn0[kk];
-        wc1[kk] = wn1[kk];
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(0);      // the next chunk's direct-to-LDS loads have landed
-    __syncthreads();
-  }
-
-  if (act_t != nullptr) {      // gate/up without a K split: silu(gate) * up, as in the 4-wave kernel
-    const int col = (nt0 >> 1) * 32 + (lane & 31);
-    const int row0 = (int)blockIdx.z * MTB * 32;
-#pragma unroll
-    for (int mt = 0; mt < MTW; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float g = acc[0][mt][r], u = acc[1][mt][r];
-        act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
-      }
-    return;
-  }
-  float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)nt0 * 32 + (lane & 31);
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-    for (int mt = 0; mt < MTW; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        out[(int64_t)m * N + nt * 32] = acc[nt][mt][r];
-      }
-}
-
-// =================================================================================================
 // 256 x 256 tile, 8 waves, both operands through an LDS ring of R slots of TWO k-steps each, loads spread out.
-// Cycle counters inside the two-chunk kernel show where its time goes: a wave spends about 40 % of a chunk
-// ISSUING its twelve 1 KiB loads.  The vector memory path of a compute unit accepts 64 bytes per cycle, so the
-// 96 KiB a work-group pulls per chunk keep it busy for 1500 cycles -- three quarters of the chunk's MFMA time
-// -- and because a wave issues in order, a wave queued behind that burst issues no MFMA either.  So:
+// Cycle counters inside an 8-wave kernel that, like the 4-wave one above, issued all loads of the next chunk of
+// four k-steps at once (weights into registers, every row half its own copy) showed a wave spending about 40 %
+// of a chunk ISSUING its twelve 1 KiB loads.  The vector memory path of a compute unit accepts 64 bytes per
+// cycle, so the 96 KiB that work-group pulled per chunk kept it busy for 1500 cycles -- three quarters of the
+// chunk's MFMA time -- and because a wave issues in order, a wave queued behind that burst issues no MFMA
+// either.  So here:
 //   * every fragment is fetched once per work-group (no second fetch of the weights by the other row half):
 //     16 KiB per k-step, half of the MFMA time at full rate;
 //   * the four loads a wave owes per slot are placed between groups of four MFMAs, never in a burst behind
@@ -1387,14 +1266,10 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
   if (S > 1) act_t = nullptr;       // the fused SwiGLU epilogue needs the whole K range in one work-group
   dim3 block(256);
   if (full) {    // whole blocks of 256 rows: one launch, row blocks along grid.z
-    // tuning switches: the 4-wave tile, or the two-chunk 8-wave kernel, instead of the ring kernel
+    // the ring kernel's slots hold two k-steps; odd k ranges (or the tuning switch) take the 4-wave tile
     static const bool four_waves = getenv("PIPEMAX_GEMM_L1") != nullptr;
-    static const bool two_chunk = getenv("PIPEMAX_GEMM_TWO_CHUNK") != nullptr;
-    const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);      // the ring kernel's slots hold two k-steps
-    if (four_waves)
-      hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
-                         part, full * 256, N, KT, ksp, stride, act_t);
-    else if (even && !two_chunk) {
+    const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);
+    if (even && !four_waves) {
       constexpr int R = 4;
       constexpr int lds = R * 2048 * 16;
       static bool attr_set = false;
@@ -1405,8 +1280,8 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
       hipLaunchKernelGGL((k_gemm_l5<R>), dim3(N / 256, S, full), dim3(512), lds, s, (const uint4*)Xt,
                          (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
     } else
-      hipLaunchKernelGGL((k_gemm_l2<4>), dim3(N / 256, S, full), dim3(512), 0, s, (const uint4*)Xt,
-                         (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
+      hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
+                         part, full * 256, N, KT, ksp, stride, act_t);
   }
   if (rem) {     // the remaining rows with the smallest tile count that covers them
     const uint4* Xr = (const uint4*)Xt + (int64_t)full * 8 * KT * 64;
