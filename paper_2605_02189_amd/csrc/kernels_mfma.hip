@@ -4,6 +4,8 @@
 // Data reaches the matrix instructions without any shuffle: KV pages, weights and activations are
 // stored in operand-fragment order (see common.hpp), so every global load is a lane-linear 16-byte
 // load (1 KiB contiguous per wave instruction) that lands directly in an MFMA operand register.
+#include <algorithm>
+#include <atomic>
 #include <cstdlib>
 
 #include <hip/hip_ext.h>
@@ -1272,13 +1274,24 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
     if (even && !four_waves) {
       constexpr int R = 4;
       constexpr int lds = R * 2048 * 16;
-      static bool attr_set = false;
-      if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)k_gemm_l5<R>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
+      // 128 KiB of dynamic LDS must be allowed once per device (0 = not asked yet, 1 = granted, 2 = refused)
+      static std::atomic<int> ring_state[64];
+      int dev = 0;
+      (void)hipGetDevice(&dev);
+      dev = std::min(std::max(dev, 0), 63);
+      int st = ring_state[dev].load(std::memory_order_acquire);
+      if (st == 0) {
+        st = hipFuncSetAttribute((const void*)k_gemm_l5<R>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) ==
+                     hipSuccess ? 1 : 2;
+        if (st == 2) (void)hipGetLastError();
+        ring_state[dev].store(st, std::memory_order_release);
       }
-      hipLaunchKernelGGL((k_gemm_l5<R>), dim3(N / 256, S, full), dim3(512), lds, s, (const uint4*)Xt,
-                         (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
+      if (st == 1)
+        hipLaunchKernelGGL((k_gemm_l5<R>), dim3(N / 256, S, full), dim3(512), lds, s, (const uint4*)Xt,
+                           (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
+      else
+        hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt,
+                           (const uint4*)Wt, part, full * 256, N, KT, ksp, stride, act_t);
     } else
       hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
                          part, full * 256, N, KT, ksp, stride, act_t);
