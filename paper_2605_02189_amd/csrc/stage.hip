@@ -275,6 +275,41 @@ void scatter_token(const pipemax_stage* st, T* page, int layer, int slot, const 
     }
   }
 }
+// n consecutive tokens of one sequence (slots slot0 .. slot0 + n - 1 of one page; their staging rows lie
+// `stride` elements apart): in the page the 8-element K pieces of consecutive tokens are adjacent, and so are
+// the V elements of four consecutive tokens, so a run is written in 16-byte / 4-element pieces instead of
+// element by element (a prefill chunk hands over thousands of rows per layer).
+template <typename T>
+void scatter_run(const pipemax_stage* st, T* page, int layer, int slot0, int n, const T* k_rows, const T* v_rows,
+                 size_t stride) {
+  const int Hkv = st->D.Hkv, d = st->D.d;
+  for (int head = 0; head < Hkv; ++head) {
+    T* ks = page + sub_block_off(Hkv, d, layer, head, 0);
+    T* vs = page + sub_block_off(Hkv, d, layer, head, 1);
+    for (int dd = 0; dd < d; dd += 8) {
+      T* dst = ks + k_sub_idx(slot0, dd);
+      const T* src = k_rows + (size_t)head * d + dd;
+      for (int t = 0; t < n; ++t) memcpy(dst + (size_t)t * 8, src + (size_t)t * stride, 8 * sizeof(T));
+    }
+    int t = 0;
+    for (; t < n && ((slot0 + t) & 3); ++t) {          // tokens in front of the first aligned group of four
+      const T* vr = v_rows + (size_t)t * stride + (size_t)head * d;
+      for (int dd = 0; dd < d; ++dd) vs[v_sub_idx(slot0 + t, dd)] = vr[dd];
+    }
+    for (; t + 4 <= n; t += 4) {
+      const T* v0 = v_rows + (size_t)t * stride + (size_t)head * d;
+      const T *v1 = v0 + stride, *v2 = v1 + stride, *v3 = v2 + stride;
+      for (int dd = 0; dd < d; ++dd) {
+        const T quad[4] = {v0[dd], v1[dd], v2[dd], v3[dd]};
+        memcpy(vs + v_sub_idx(slot0 + t, dd), quad, sizeof(quad));
+      }
+    }
+    for (; t < n; ++t) {
+      const T* vr = v_rows + (size_t)t * stride + (size_t)head * d;
+      for (int dd = 0; dd < d; ++dd) vs[v_sub_idx(slot0 + t, dd)] = vr[dd];
+    }
+  }
+}
 template <typename T>
 void gather_token(const pipemax_stage* st, const T* page, int layer, int slot, T* k_row, T* v_row) {
   const int Hkv = st->D.Hkv, d = st->D.d;
@@ -303,24 +338,33 @@ void worker_main(pipemax_stage* st) {
     if (int us = st->dly_worker.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
     const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
-    // rows write disjoint token slots, so a prefill chunk (hundreds of rows) is spread over the host cores
-    const int n_items = job.n_layers * job.b;
-#pragma omp parallel for schedule(static) if (n_items >= 1024)
+    // rows write disjoint token slots, so a prefill chunk (hundreds of rows) is spread over the host cores;
+    // its rows are consecutive tokens, which are written run by run (rows of one page, consecutive slots)
+    std::vector<std::pair<int, int>> runs;      // (first row, length)
+    for (int i = 0; i < job.b;) {
+      int n = 1;
+      while (i + n < job.b && (*job.where)[i + n].first == (*job.where)[i].first &&
+             (*job.where)[i + n].second == (*job.where)[i].second + n)
+        ++n;
+      runs.emplace_back(i, n);
+      i += n;
+    }
+    const int n_runs = (int)runs.size();
+    const int n_items = job.n_layers * n_runs;
+#pragma omp parallel for schedule(static) if (job.n_layers * job.b >= 1024)
     for (int item = 0; item < n_items; ++item) {
-      const int layer = job.layer + item / job.b;
+      const int layer = job.layer + item / n_runs;
       const char* src = (const char*)st->h_stage[job.slot] + (size_t)layer * layer_elems * st->esz;
-      {
-        const int i = item % job.b;
-        const auto& wh = (*job.where)[i];
-        char* page = st->host_page_ptr(wh.first);
-        const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
-        const char* vr = src + ((size_t)i * 2 + 1) * row * st->esz;
-        if (st->esz == 4)
-          scatter_token<float>(st, (float*)page, layer, wh.second, (const float*)kr, (const float*)vr);
-        else
-          scatter_token<uint16_t>(st, (uint16_t*)page, layer, wh.second, (const uint16_t*)kr,
-                                  (const uint16_t*)vr);
-      }
+      const int i = runs[item % n_runs].first, n = runs[item % n_runs].second;
+      const auto& wh = (*job.where)[i];
+      char* page = st->host_page_ptr(wh.first);
+      const char* kr = src + ((size_t)i * 2 + 0) * row * st->esz;
+      const char* vr = src + ((size_t)i * 2 + 1) * row * st->esz;
+      if (st->esz == 4)
+        scatter_run<float>(st, (float*)page, layer, wh.second, n, (const float*)kr, (const float*)vr, 2 * row);
+      else
+        scatter_run<uint16_t>(st, (uint16_t*)page, layer, wh.second, n, (const uint16_t*)kr, (const uint16_t*)vr,
+                              2 * row);
     }
     {
       std::lock_guard<std::mutex> lk(st->mu);
@@ -379,17 +423,31 @@ GemmPlan plan_gemm_skinny(int N, int K, bool swiglu) {
   return p;
 }
 
-// more than 64 rows: large-tile kernel, one work-group (4 waves, 256 rows x 256 columns) per CU and about
-// 256 work-groups in total: column blocks x row blocks x K splits
+// More than 128 rows: large-tile kernel, one work-group (256 rows x 256 columns) per CU.  The K split is the
+// one with the lowest modelled time: work-groups run in rounds of 256 (one per compute unit), a work-group takes
+// a fixed start / store cost plus its share of the k-steps, and every split adds one fp32 partial of the output
+// that is written here and read by the consumer.  (Constants measured on the ring kernel: 0.42 us per k-step
+// and work-group, 4.5 us per work-group, partials at an effective 4 TB/s.)  A plain "about 256 work-groups" rule
+// picks 3 splits for 96 column-row blocks -- 288 work-groups, i.e. two rounds -- where 2 splits are 25 % faster.
 GemmPlan plan_gemm_large(int N, int K, int M) {
   GemmPlan p;
   p.wn = 0;
-  const int bn = (N / 256) * ((M + 255) / 256), KT = K / 16;
-  int S = std::max(1, (256 + bn / 2) / bn);
-  S = std::max(1, std::min(S, KT / 16));
-  int ksp = (KT + S - 1) / S;
-  if (KT % 2 == 0) ksp += ksp & 1;      // the ring kernel works on pairs of k-steps
-  p.split = (KT + ksp - 1) / ksp;
+  const int rb = (M + 255) / 256, bn = (N / 256) * rb, KT = K / 16;
+  const double part_us = (double)rb * 256 * N * 8.0 / 4.0e6;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int S = 1; S <= std::max(1, std::min(16, KT / 16)); ++S) {
+    int ksp = (KT + S - 1) / S;
+    if (KT % 2 == 0) ksp += ksp & 1;      // the ring kernel works on pairs of k-steps
+    const int split = (KT + ksp - 1) / ksp;
+    const int rounds = (bn * split + 255) / 256;
+    const double cost = rounds * (0.42 * ksp + 4.5) + (split > 1 ? split * part_us : 0.0);
+    if (S == 1 || cost < best_cost) {
+      best = split;
+      best_cost = cost;
+    }
+  }
+  p.split = best;
   return p;
 }
 
