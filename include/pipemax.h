@@ -295,6 +295,13 @@ int pipemax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_strea
 int64_t pipemax_page_elem_offset(int n_layers, int n_kv_heads, int head_dim,
                                  int layer, int kv, int head, int tok, int dd);
 
+/* Split-K plan of the large-tile GEMM (more than 128 rows; n_cols a multiple of 256, k of 16): the number
+ * of K splits the stage plans for a rows x k x n_cols product (*plan_splits: the partials its consumers sum),
+ * the number the launch geometry derives from it (*launch_splits; the two must agree) and the 16-wide
+ * k-steps per split.  Pure host arithmetic.  Errors: ERR_ARG.                                          */
+int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, int32_t* launch_splits,
+                             int32_t* k_steps_per_split);
+
 /* Merges n (src_page, dst_page) pairs, in the given order, into runs of consecutive pages,
  * each at most max_run_pages long.  Writes (src_first, dst_first, count) triples to runs
  * (room for 3*n int32) and returns the number of runs, or a negative status.               */

@@ -55,6 +55,17 @@ void resid_norm(hipStream_t s, int b, int h, float eps, const uint16_t* hin, con
 void gemm(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
           int n_split, int wn, uint16_t* swiglu_act_t = nullptr);
 
+// K ranges of the large-tile kernel for a requested number of splits: k-steps per split (*ksp) and the number
+// of splits the grid really has (the return value; the consumers of the partials must use the same number).
+// Ranges of an even number of k-steps -- what the ring kernel needs -- are taken when that keeps the count.
+inline int large_gemm_splits(int KT, int n_split, int* ksp_out) {
+  int ksp = (KT + n_split - 1) / n_split;
+  const int S = (KT + ksp - 1) / ksp;
+  if (KT % 2 == 0 && (ksp & 1) && (KT + ksp) / (ksp + 1) == S) ksp += 1;
+  *ksp_out = ksp;
+  return S;
+}
+
 void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* part, int n_split,
                  int64_t split_stride, const float2* cs, const int* ctx, const int* table,
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);

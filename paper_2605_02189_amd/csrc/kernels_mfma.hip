@@ -1258,10 +1258,8 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
                        int n_split, uint16_t* act_t) {
   const int KT = K / 16;
-  int ksp = (KT + n_split - 1) / n_split;
-  const int S = (KT + ksp - 1) / ksp;
-  // k ranges of an even number of k-steps (what the ring kernel needs) when that keeps the number of splits
-  if (KT % 2 == 0 && (ksp & 1) && (KT + ksp) / (ksp + 1) == S) ksp += 1;
+  int ksp = 0;
+  const int S = large_gemm_splits(KT, n_split, &ksp);
   const int MTall = (M + 31) / 32;
   const int64_t stride = (int64_t)MTall * 32 * N;
   const int full = M / 256, rem = M - full * 256;

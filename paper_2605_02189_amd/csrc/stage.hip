@@ -1659,6 +1659,19 @@ int64_t pipemax_page_elem_offset(int n_layers, int n_kv_heads, int head_dim, int
   return sub_block_off(n_kv_heads, head_dim, layer, head, kv) + (kv ? v_sub_idx(tok, dd) : k_sub_idx(tok, dd));
 }
 
+int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, int32_t* launch_splits,
+                             int32_t* k_steps_per_split) {
+  if (!plan_splits || !launch_splits || !k_steps_per_split || rows < 1 || n_cols < 256 || n_cols % 256 != 0 ||
+      k < 16 || k % 16 != 0)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "plan_gemm_splits: rows >= 1, columns a multiple of 256, k a multiple of 16");
+  const GemmPlan p = plan_gemm_large(n_cols, k, rows);
+  int ksp = 0;
+  *plan_splits = p.split;
+  *launch_splits = pmx::mfma::large_gemm_splits(k / 16, p.split, &ksp);
+  *k_steps_per_split = ksp;
+  return PIPEMAX_OK;
+}
+
 int pipemax_plan_copy_runs(const int32_t* src_pages, const int32_t* dst_pages, int n, int max_run_pages,
                            int32_t* runs) {
   if (n < 0 || max_run_pages < 1 || (n > 0 && (!src_pages || !dst_pages || !runs)))

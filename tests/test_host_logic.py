@@ -132,3 +132,26 @@ def test_page_layout_is_a_bijection_with_the_documented_order(lib, d):
     assert lib.page_elem_offset(nl, hkv, d, nl, 0, 0, 0, 0) == -1
     assert lib.page_elem_offset(nl, hkv, d, 0, 0, 0, 16, 0) == -1
     assert lib.page_elem_offset(nl, hkv, 48, 0, 0, 0, 0, 0) == -1
+
+
+def test_gemm_split_plan_and_launch_geometry_agree(lib):
+    """The consumers of the split-K partials sum `planned` slices while the GEMM's grid has `launched` splits: the
+    two must be the same number for every shape, the splits must cover K, and k ranges come in pairs of k-steps
+    (the ring kernel's slots) whenever K allows it."""
+    for rows in (129, 150, 256, 257, 512, 600, 768, 1024):
+        for n_cols in (256, 1024, 4096, 6144, 10240, 28672, 57344):
+            for k in (512, 1024, 2816, 4096, 8192, 14336, 16384, 28672, 4112):
+                planned, launched, ksp = lib.plan_gemm_splits(rows, n_cols, k)
+                kt = k // 16
+                assert planned == launched >= 1, (rows, n_cols, k)
+                assert ksp * launched >= kt > ksp * (launched - 1), (rows, n_cols, k)
+                assert launched <= max(1, kt // 16)
+                if kt % 2 == 0 and launched > 1:
+                    assert ksp % 2 == 0, (rows, n_cols, k)
+    # 96 column-row blocks (the 8B stage's QKV matrix at 1024 rows): three splits would be 288 work-groups, i.e.
+    # two rounds on 256 compute units; the plan takes two
+    assert lib.plan_gemm_splits(1024, 6144, 4096)[0] == 2
+    # a matrix with more blocks than compute units is not split at all
+    assert lib.plan_gemm_splits(1024, 28672, 4096)[0] == 1
+    with pytest.raises(lib.PipemaxError):
+        lib.plan_gemm_splits(256, 300, 4096)
