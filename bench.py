@@ -41,12 +41,13 @@ def attn_bytes(shape, lens_before):
     return sum(2 * shape.n_kv_heads * shape.head_dim * shape.elem_bytes * (int(L) + 1) for L in lens_before)
 
 
-def measured_traffic(config_name):
-    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload."""
+def measured_traffic(config_name, key="traffic_bytes_per_launch"):
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload (and, with
+    key="algorithmic_bytes_per_launch", the algorithmic bytes of the launches those counters were read on)."""
     path = os.path.join(ROOT, "profiles", f"attn_{config_name}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
+            if line.startswith(key):
                 return int(line.split()[1])
     except OSError:
         pass
@@ -216,6 +217,7 @@ def main():
         roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(shape.name),
+                    "traffic_measured_on_algorithmic_bytes": measured_traffic(shape.name, "algorithmic_bytes_per_launch"),
                     "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_launches,
                     "bytes_per_launch": int(bytes_attn / max(attn_launches, 1))}
         hbm_bytes_step = shape.weight_bytes + bytes_attn / Kc
