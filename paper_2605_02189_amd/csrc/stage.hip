@@ -21,6 +21,7 @@
 #include <memory>
 #include <mutex>
 #include <new>
+#include <omp.h>
 #include <thread>
 #include <vector>
 
@@ -323,8 +324,23 @@ void gather_token(const pipemax_stage* st, const T* page, int layer, int slot, T
   }
 }
 
+// Threads of the re-layout team.  They must not saturate the host: the HIP runtime resolves cross-stream event
+// waits in host threads of its own, and with every core spinning in OpenMP the compute stream was seen to stall
+// for 1-2 ms per prefill pass behind the write-back copy.  So: at most half of the available threads (8 at most;
+// PIPEMAX_RELAYOUT_THREADS overrides), and the team sleeps as soon as a job is done instead of spinning for the
+// runtime's default 200 ms.
+int relayout_threads() {
+  static const int n = [] {
+    int t = std::max(1, std::min(8, omp_get_max_threads() / 2));
+    if (const char* e = getenv("PIPEMAX_RELAYOUT_THREADS")) t = std::max(1, std::min(64, atoi(e)));
+    return t;
+  }();
+  return n;
+}
+
 void worker_main(pipemax_stage* st) {
   (void)hipSetDevice(st->dev);
+  kmp_set_blocktime(0);
   for (;;) {
     WbJob job;
     {
@@ -351,7 +367,7 @@ void worker_main(pipemax_stage* st) {
     }
     const int n_runs = (int)runs.size();
     const int n_items = job.n_layers * n_runs;
-#pragma omp parallel for schedule(static) if (job.n_layers * job.b >= 1024)
+#pragma omp parallel for schedule(static) num_threads(relayout_threads()) if (job.n_layers * job.b >= 1024)
     for (int item = 0; item < n_items; ++item) {
       const int layer = job.layer + item / n_runs;
       const char* src = (const char*)st->h_stage[job.slot] + (size_t)layer * layer_elems * st->esz;
@@ -822,6 +838,7 @@ int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* ho
   const int KT = K / 16;
   const int F = D.F;
   const int NT = N / 32;
+  kmp_set_blocktime(0);      // the helper threads sleep after the loop instead of spinning beside the first steps
 #pragma omp parallel for schedule(static)
   for (int nt = 0; nt < NT; ++nt) {
     int src_col0;
