@@ -129,7 +129,8 @@ typedef struct {
   double   host_enqueue_s;        /* host time spent inside decode_step                      */
   double   host_wait_s;           /* host time blocked on the write-back worker              */
   double   h2d_ms;                /* busy time of prefetch copies   (FLAG_TIME_KERNELS)      */
-  double   d2h_ms;                /* busy time of write-back copies (FLAG_TIME_KERNELS)      */
+  double   d2h_ms;                /* write-back copies, issue to completion as seen by the   */
+                                  /* worker thread that issues them (FLAG_TIME_KERNELS)      */
   double   kernel_ms[PIPEMAX_N_KCLASS];        /* summed kernel durations per class          */
   uint64_t kernel_launches[PIPEMAX_N_KCLASS];
   int32_t  engine;                /* 0 = shape-generic kernels, 1 = matrix-core (bf16) kernels */
@@ -273,8 +274,9 @@ int pipemax_get_layer_outputs(pipemax_stage_t* st, float* out, size_t bytes);
  * synchronising the stage: any read of a page that no live sequence owns then poisons the output. */
 int pipemax_debug_fill_free_gpu_pages(pipemax_stage_t* st, uint16_t pattern);
 /* Delays, in microseconds, injected from now on before every prefetch batch (on the host->device
- * stream), before every write-back copy (on the device->host stream) and before every re-layout job
- * (in the worker thread).  Results must not depend on them: they only move work in time.         */
+ * stream), before every write-back copy and before every re-layout job (both in the worker thread,
+ * which issues the copy once the step's K,V rows are in the staging buffer).  Results must not
+ * depend on them: they only move work in time.                                                    */
 int pipemax_debug_set_delays(pipemax_stage_t* st, int h2d_us, int d2h_us, int worker_us);
 
 const char* pipemax_last_error(void);

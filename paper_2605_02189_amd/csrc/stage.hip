@@ -3,9 +3,10 @@
 //
 // Streams.  compute = the caller's stream (or the stage's own); h2d = KV prefetch; d2h = KV
 // write-back.  All at default priority.
-//   decode_step(mb): compute waits for mb's prefetch event; per layer, after the kernel that appends
-//     the new K,V, an event releases the d2h copy of that layer's contiguous staging to pinned host
-//     memory; the worker thread waits for that copy and scatters the rows into the host pages.
+//   decode_step(mb): compute waits for mb's prefetch event; after the kernel that appends the new K,V
+//     of a layer (or of the last layer of a group) an event is recorded; the worker thread waits for it,
+//     issues the d2h copy of the contiguous staging rows to pinned host memory, waits for the copy and
+//     scatters the rows into the host pages.
 //   prefetch(mb):   host waits until mb's pending write-back has landed in the host replica, then
 //     page runs are copied on h2d, which is ordered (see evict) after the last reader of any page
 //     it overwrites.
@@ -79,6 +80,10 @@ struct WbJob {
   hipEvent_t ev = nullptr;
   int mb = 0, layer = 0, n_layers = 1, slot = 0, b = 0;
   std::shared_ptr<std::vector<std::pair<int32_t, int>>> where;   // per sequence: host page, slot
+  // ev marks the staging rows as written; the worker then issues the device -> host copy itself
+  void* copy_dst = nullptr;
+  const void* copy_src = nullptr;
+  size_t copy_bytes = 0;
   bool stop = false;
 };
 
@@ -140,7 +145,7 @@ struct pipemax_stage {
   // write-back ring
   void* d_stage[kSlots] = {};
   void* h_stage[kSlots] = {};
-  std::vector<hipEvent_t> ev_ready[kSlots], ev_copied[kSlots];
+  std::vector<hipEvent_t> ev_ready[kSlots];
   int slot_pending[kSlots] = {};   // guarded by mu
   uint64_t step_no = 0;
   // table upload ring
@@ -161,6 +166,7 @@ struct pipemax_stage {
   bool worker_started = false;
   // test hooks
   std::atomic<int> dly_h2d{0}, dly_d2h{0}, dly_worker{0};
+  int worker_hip_error = 0;        // guarded by mu: first failure of a copy the worker issued
   // stats / timing
   pipemax_stats_t st{};
   std::vector<Timed> timed;
@@ -351,6 +357,15 @@ void worker_main(pipemax_stage* st) {
     }
     if (job.stop) return;
     (void)hipEventSynchronize(job.ev);
+    {
+      if (int us = st->dly_d2h.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
+      const double t0 = now_s();
+      hipError_t e = hipMemcpyAsync(job.copy_dst, job.copy_src, job.copy_bytes, hipMemcpyDeviceToHost, st->s_d2h);
+      if (e == hipSuccess) e = hipStreamSynchronize(st->s_d2h);
+      std::lock_guard<std::mutex> lk(st->mu);
+      if (e != hipSuccess && !st->worker_hip_error) st->worker_hip_error = (int)e;
+      if (st->timing()) st->st.d2h_ms += (now_s() - t0) * 1e3;
+    }
     if (int us = st->dly_worker.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
     const size_t layer_elems = (size_t)st->cfg.max_seqs_per_mb * 2 * row;  // staging of one layer
@@ -514,7 +529,6 @@ void destroy_impl(pipemax_stage* st) {
   }
   for (int s = 0; s < kSlots; ++s) {
     for (auto e : st->ev_ready[s]) (void)hipEventDestroy(e);
-    for (auto e : st->ev_copied[s]) (void)hipEventDestroy(e);
   }
   for (int r = 0; r < kTableRing; ++r)
     if (st->ev_table[r]) (void)hipEventDestroy(st->ev_table[r]);
@@ -773,10 +787,8 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     PMX_TRY(dev_alloc(st, &p, stage_bytes)); st->d_stage[s] = p;
     PMX_TRY(host_alloc(st, &p, stage_bytes)); st->h_stage[s] = p;
     st->ev_ready[s].resize(c.n_layers, nullptr);
-    st->ev_copied[s].resize(c.n_layers, nullptr);
     for (int l = 0; l < c.n_layers; ++l) {
       PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_ready[s][l], hipEventDisableTiming));
-      PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_copied[s][l], hipEventDisableTiming));
     }
   }
   for (int r = 0; r < kTableRing; ++r) {
@@ -1210,18 +1222,17 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     if ((l + 1) % wb_group != 0 && l != nl - 1) return PIPEMAX_OK;
     const int l0 = (l / wb_group) * wb_group, nlay = l - l0 + 1;
     PMX_HIP(hipEventRecord(st->ev_ready[slot][l], cs));
-    PMX_HIP(hipStreamWaitEvent(st->s_d2h, st->ev_ready[slot][l], 0));
-    if (int us = st->dly_d2h.load()) PMX_HIP(hipLaunchHostFunc(st->s_d2h, host_sleep_cb, (void*)(intptr_t)us));
-    st->tbegin(TC_D2H, st->s_d2h);
     // one layer's rows are contiguous for b sequences; a group spans whole layer slots
     const size_t group_bytes = (size_t)(nlay - 1) * layer_elems * st->esz + copy_bytes;
-    PMX_HIP(hipMemcpyAsync((char*)st->h_stage[slot] + (size_t)l0 * layer_elems * st->esz,
-                           (char*)st->d_stage[slot] + (size_t)l0 * layer_elems * st->esz, group_bytes,
-                           hipMemcpyDeviceToHost, st->s_d2h));
-    st->tend(st->s_d2h);
-    PMX_HIP(hipEventRecord(st->ev_copied[slot][l], st->s_d2h));
+    char* h_dst = (char*)st->h_stage[slot] + (size_t)l0 * layer_elems * st->esz;
+    const char* d_src = (const char*)st->d_stage[slot] + (size_t)l0 * layer_elems * st->esz;
+    // The worker thread issues the copy once the event has completed.  Enqueued here, behind a cross-stream
+    // wait, the runtime's device-to-host copy (a shader copy with a full-size grid) was measured to hold this
+    // thread up and to run beside the next kernels of the compute stream, which take several times longer next
+    // to it; issued from the worker it costs a prefill pass of 1024 rows 0.25 ms instead of 0.65 ms.
     WbJob job;
-    job.ev = st->ev_copied[slot][l];
+    job.ev = st->ev_ready[slot][l];
+    job.copy_dst = h_dst; job.copy_src = d_src; job.copy_bytes = group_bytes;
     job.mb = mb; job.layer = l0; job.n_layers = nlay; job.slot = slot; job.b = b; job.where = where;
     {
       std::lock_guard<std::mutex> lk(st->mu);
@@ -1509,6 +1520,11 @@ int pipemax_sync(pipemax_stage_t* st) {
   PMX_HIP(hipStreamSynchronize(st->s_h2d));
   PMX_HIP(hipStreamSynchronize(st->s_d2h));
   st->wait_all_writeback();
+  {
+    std::lock_guard<std::mutex> lk(st->mu);
+    if (st->worker_hip_error)
+      PMX_FAIL(PIPEMAX_ERR_HIP, "a write-back copy failed: %s", hipGetErrorString((hipError_t)st->worker_hip_error));
+  }
   for (auto& M : st->mbs) {
     if (!M.defined) continue;
     M.prefetch_pending = false;
