@@ -84,6 +84,7 @@ struct WbJob {
   void* copy_dst = nullptr;
   const void* copy_src = nullptr;
   size_t copy_bytes = 0;
+  bool timed = false;              // accumulate the copy's duration (the timing flag when the job was queued)
   bool stop = false;
 };
 
@@ -364,7 +365,7 @@ void worker_main(pipemax_stage* st) {
       if (e == hipSuccess) e = hipStreamSynchronize(st->s_d2h);
       std::lock_guard<std::mutex> lk(st->mu);
       if (e != hipSuccess && !st->worker_hip_error) st->worker_hip_error = (int)e;
-      if (st->timing()) st->st.d2h_ms += (now_s() - t0) * 1e3;
+      if (job.timed) st->st.d2h_ms += (now_s() - t0) * 1e3;
     }
     if (int us = st->dly_worker.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
     const size_t row = (size_t)st->D.Hkv * st->D.d;                       // elements of one K (or V) row
@@ -1233,6 +1234,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     WbJob job;
     job.ev = st->ev_ready[slot][l];
     job.copy_dst = h_dst; job.copy_src = d_src; job.copy_bytes = group_bytes;
+    job.timed = st->timing();
     job.mb = mb; job.layer = l0; job.n_layers = nlay; job.slot = slot; job.b = b; job.where = where;
     {
       std::lock_guard<std::mutex> lk(st->mu);
