@@ -789,7 +789,8 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
     PMX_TRY(host_alloc(st, &p, stage_bytes)); st->h_stage[s] = p;
     st->ev_ready[s].resize(c.n_layers, nullptr);
     for (int l = 0; l < c.n_layers; ++l) {
-      PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_ready[s][l], hipEventDisableTiming));
+      // the worker sleeps in hipEventSynchronize instead of spinning on a core for a whole step
+      PMX_TRY_HIP(hipEventCreateWithFlags(&st->ev_ready[s][l], hipEventDisableTiming | hipEventBlockingSync));
     }
   }
   for (int r = 0; r < kTableRing; ++r) {
