@@ -1062,7 +1062,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
 //   Column n sees tokens <= pos0 + r0 + n.  At most 64 * NW pages (the host checks).
 // =================================================================================================
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_prefill(Dims D, int layer, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_prefill(Dims D, int layer, const uint16_t* __restrict__ q,
                                                           const uint16_t* __restrict__ pool,
                                                           const int* __restrict__ table, int pos0, int R,
                                                           uint16_t* __restrict__ out_t) {
@@ -1095,63 +1095,90 @@ __global__ __launch_bounds__(NW * 64) void k_attn_prefill(Dims D, int layer, con
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 kf[2][4], vf[2][4];
+  // The softmax bookkeeping of an update (maximum and sum across the wave, the rescale of 32 accumulator
+  // registers) costs more vector instructions than the scores themselves, so an update covers TWO pages
+  // (32 tokens): the kernel is bound by that arithmetic, not by memory.  Groups of two pages are
+  // double-buffered; a missing second page (odd count) re-reads the wave's first page and is masked out.
+  uint4 kf[2][2][4], vf[2][2][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
-    const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
+    const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t < npw ? t : 0));
     const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
   };
-  if (npw > 0) load_page(0, kf[0], vf[0]);
-  for (int t0 = 0; t0 < npw; t0 += 2) {
+  const int ngr = (npw + 1) / 2;
+  if (ngr > 0) {
+    load_page(0, kf[0][0], vf[0][0]);
+    load_page(1, kf[0][1], vf[0][1]);
+  }
+  for (int g0 = 0; g0 < ngr; g0 += 2) {
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-      const int t = t0 + r;
-      if (t < npw) {
-        if (t + 1 < npw) load_page(t + 1, kf[r ^ 1], vf[r ^ 1]);
-        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+      const int gi = g0 + r;
+      if (gi < ngr) {
+        if (gi + 1 < ngr) {
+          load_page(2 * gi + 2, kf[r ^ 1][0], vf[r ^ 1][0]);
+          load_page(2 * gi + 3, kf[r ^ 1][1], vf[r ^ 1][1]);
+        }
+        f32x4 sacc[2];
+        float sv[2][4];
+        int tok0[2];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[r][kk]), qf[kk],
-                                                         sacc, 0, 0, 0);
-        const int tok0 = ((w + NW * t) << 4) + 4 * g;
-        float sv[4];
+        for (int p = 0; p < 2; ++p) {
+          sacc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) sv[e] = (tok0 + e < n_vis) ? sacc[e] * scale_log2 : -INFINITY;
-        float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+          for (int kk = 0; kk < 4; ++kk)
+            sacc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[r][p][kk]), qf[kk],
+                                                              sacc[p], 0, 0, 0);
+          const int t = 2 * gi + p;
+          tok0[p] = ((w + NW * t) << 4) + 4 * g;
+          const bool have = t < npw;                     // wave-uniform: the second page of the last group
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            sv[p][e] = (have && tok0[p] + e < n_vis) ? sacc[p][e] * scale_log2 : -INFINITY;
+        }
+        float mloc = fmaxf(fmaxf(fmaxf(sv[0][0], sv[0][1]), fmaxf(sv[0][2], sv[0][3])),
+                           fmaxf(fmaxf(sv[1][0], sv[1][1]), fmaxf(sv[1][2], sv[1][3])));
         mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
         const float m_new = fmaxf(m_run, mloc);
         // a column may see nothing of this wave's pages so far: keep the exponents finite
         const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = exp2f(m_run - m_ref);
-        float pr[4];
+        float pr[2][4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pr[e] = exp2f(sv[e] - m_ref);
-        float lsum = (pr[0] + pr[1]) + (pr[2] + pr[3]);
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pr[p][e] = exp2f(sv[p][e] - m_ref);
+        float lsum = ((pr[0][0] + pr[0][1]) + (pr[0][2] + pr[0][3])) + ((pr[1][0] + pr[1][1]) + (pr[1][2] + pr[1][3]));
         lsum += __shfl_xor(lsum, 16);
         lsum += __shfl_xor(lsum, 32);
         l_run = l_run * alpha + lsum;
         m_run = m_new;
-        const uint2 pp = make_uint2(pack2(pr[0], pr[1]), pack2(pr[2], pr[3]));
-        const s16x4 pf = __builtin_bit_cast(s16x4, pp);
-        // slots past the last appended token hold whatever the page held before (0 * NaN is NaN)
-        uint32_t vm0 = 0xffffffffu, vm1 = 0xffffffffu;
-        if (tok0 + 3 >= n_total) {
-          const int valid = n_total - tok0;
-          vm0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
-          vm1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
-        }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].x & vm0, vf[r][jj].y & vm1));
-          const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][jj].z & vm0, vf[r][jj].w & vm1));
-          oacc[2 * jj] = oacc[2 * jj] * alpha;
-          oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
-          oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
-          oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+        for (int dt = 0; dt < 8; ++dt) oacc[dt] = oacc[dt] * alpha;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          const uint2 pp = make_uint2(pack2(pr[p][0], pr[p][1]), pack2(pr[p][2], pr[p][3]));
+          const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+          // slots past the last appended token hold whatever the page held before (0 * NaN is NaN)
+          uint32_t vm0 = 0xffffffffu, vm1 = 0xffffffffu;
+          if (2 * gi + p >= npw) {
+            vm0 = vm1 = 0u;                              // the stand-in for a missing second page: V = 0
+          } else if (tok0[p] + 3 >= n_total) {
+            const int valid = n_total - tok0[p];
+            vm0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+            vm1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+          }
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vf[r][p][jj].x & vm0, vf[r][p][jj].y & vm1));
+            const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vf[r][p][jj].z & vm0, vf[r][p][jj].w & vm1));
+            oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
+            oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+          }
         }
       }
     }
