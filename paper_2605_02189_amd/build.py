@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipemax.so")
-SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip", "xfer.hip", "scheduler.cpp"]
+SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip", "xfer.hip", "scheduler.cpp", "dma_copy.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 FLAGS = ["--offload-arch=gfx950", "-fopenmp", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *COMMON]
@@ -40,7 +40,7 @@ def build(verbose: bool = False) -> str:
             print(f"--- {src} ---\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fopenmp", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fopenmp", *objs, "-lhsa-runtime64", "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -26,6 +26,7 @@
 #include <thread>
 #include <vector>
 
+#include "dma_copy.hpp"
 #include "kernels.hpp"
 #include "pipemax_xfer.h"
 #include "kv_pool.hpp"
@@ -168,6 +169,7 @@ struct pipemax_stage {
   // test hooks
   std::atomic<int> dly_h2d{0}, dly_d2h{0}, dly_worker{0};
   int worker_hip_error = 0;        // guarded by mu: first failure of a copy the worker issued
+  DmaCopy* dma = nullptr;          // write-back copies on the DMA engines (nullptr: the runtime's own copies)
   // stats / timing
   pipemax_stats_t st{};
   std::vector<Timed> timed;
@@ -361,8 +363,13 @@ void worker_main(pipemax_stage* st) {
     {
       if (int us = st->dly_d2h.load()) std::this_thread::sleep_for(std::chrono::microseconds(us));
       const double t0 = now_s();
-      hipError_t e = hipMemcpyAsync(job.copy_dst, job.copy_src, job.copy_bytes, hipMemcpyDeviceToHost, st->s_d2h);
-      if (e == hipSuccess) e = hipStreamSynchronize(st->s_d2h);
+      hipError_t e = hipSuccess;
+      if (st->dma) {
+        if (dma_copy_d2h(st->dma, job.copy_dst, job.copy_src, job.copy_bytes) != 0) e = hipErrorUnknown;
+      } else {
+        e = hipMemcpyAsync(job.copy_dst, job.copy_src, job.copy_bytes, hipMemcpyDeviceToHost, st->s_d2h);
+        if (e == hipSuccess) e = hipStreamSynchronize(st->s_d2h);
+      }
       std::lock_guard<std::mutex> lk(st->mu);
       if (e != hipSuccess && !st->worker_hip_error) st->worker_hip_error = (int)e;
       if (job.timed) st->st.d2h_ms += (now_s() - t0) * 1e3;
@@ -520,6 +527,8 @@ void destroy_impl(pipemax_stage* st) {
     }
     st->cv_job.notify_all();
     st->worker.join();
+    dma_copy_destroy(st->dma);
+    st->dma = nullptr;
   }
   (void)hipDeviceSynchronize();
   st->timed.clear();
@@ -802,6 +811,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
 #undef PMX_TRY_HIP
 
   if (const char* e = getenv("PIPEMAX_ATTN_CHUNK_PAGES")) st->attn_cp_override = atoi(e);
+  st->dma = dma_copy_create(st->d_stage[0], st->h_stage[0]);
   st->worker = std::thread(worker_main, st);
   st->worker_started = true;
   st->st.engine = st->engine;
