@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <cmath>
 #include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
@@ -1128,6 +1129,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
   const int b = (int)sel.size(), nl = st->cfg.n_layers;
   if (b == 0) return PIPEMAX_OK;
   int grow = 0, grow_host = 0, max_len = 0;
+  int64_t sum_pages = 0;      // pages the attention of this step reads per KV head and layer
   for (int i : sel)
     if (M.seq[i].state == ST_HOST)
       PMX_FAIL(PIPEMAX_ERR_NOT_RESIDENT, "sequence %d of micro-batch %d is host-resident; prefetch it first", i, mb);
@@ -1143,6 +1145,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
       if (before >= (int)S.host_reserved.size()) ++grow_host;
     }
     max_len = std::max(max_len, pos0[r]);
+    sum_pages += (pos0[r] + 1 + kPageTokens - 1) / kPageTokens;
   }
   if (grow > st->gpu_pages->free_count() || grow_host > st->host_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", grow,
@@ -1318,6 +1321,18 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     const int per_chunk_waves = b * D.Hkv * mfma::kAttnWaves;
     const int nch_target = std::max(1, (1024 + per_chunk_waves / 2) / per_chunk_waves);
     int CP = (npages_max + nch_target - 1) / nch_target;
+    // Ragged batches: a work-group streams about 1.3 pages per microsecond whatever else runs (its four waves
+    // wait for one page each), the whole chip about 650 (8 KiB pages at 5.3 TB/s).  When the longest sequence
+    // alone would take longer than all pages take at the chip's rate, it -- and every sequence longer than the
+    // resulting chunk -- is split evenly, so that the tail of the launch is not one work-group.  Uniform
+    // batches (longest = mean) and batches with enough sequences to hide a long one keep a single chunk
+    // (measured: 64 ragged sequences of 512..4100 tokens -4 % per step; 128 of them no gain from splitting).
+    {
+      const double chip_bound = (double)D.Hkv * (double)sum_pages / 650.0 * 1.3;      // pages one work-group may own
+      const double target = std::max(chip_bound, (double)sum_pages / b);
+      const int nch_long = std::max(1, (int)std::ceil(npages_max / std::max(target, 1.0) - 1e-9));
+      CP = std::min(CP, (npages_max + nch_long - 1) / nch_long);
+    }
     CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
     if (st->attn_cp_override > 0) CP = std::max(8, std::min(64 * mfma::kAttnWaves, st->attn_cp_override));
     const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
