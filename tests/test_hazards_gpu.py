@@ -77,6 +77,21 @@ def test_nan_canary_in_free_pages_never_reaches_the_output(dtype):
         np.testing.assert_array_equal(Va, Vb)
 
 
+def test_write_back_through_the_runtime_copy_equals_the_dma_engine_path(monkeypatch):
+    """The worker thread copies a step's staged K,V rows to the host on a DMA engine (HSA runtime); when that path
+    is refused -- forced here by the switch -- it falls back to the runtime's own copy.  Same bytes either way."""
+    shape = _shape("bf16")
+    base_out, base_rep, base_stats = _run(shape, wb=1)
+    monkeypatch.setenv("PIPEMAX_NO_DMA_WRITEBACK", "1")
+    out, rep, stats = _run(shape, wb=1)
+    assert stats["d2h_bytes"] == base_stats["d2h_bytes"] > 0
+    for t, (a, b) in enumerate(zip(out, base_out)):
+        np.testing.assert_array_equal(a, b, err_msg=f"step {t}")
+    for (Ka, Va), (Kb, Vb) in zip(rep, base_rep):
+        np.testing.assert_array_equal(Ka, Kb)
+        np.testing.assert_array_equal(Va, Vb)
+
+
 def _run_scheduled(delays=None, canary=False):
     """Alg. 1 driving the stage (decode of a chosen part, releases, per-request prefetch) for 24 iterations."""
     import torch
