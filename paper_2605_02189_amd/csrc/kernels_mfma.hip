@@ -365,21 +365,29 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 //   A load issued during step s fills the slot read in step s + R - 1: it has R - 2 whole steps to land.
 //   Whole blocks of 256 rows, k ranges of an even number of k-steps.
 // =================================================================================================
-template <int R>
-__global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
-                                                 float* __restrict__ part, int N, int KT, int ksp,
-                                                 int64_t split_stride, uint16_t* __restrict__ act_t) {
-  constexpr int MTB = 8, MTW = 4;
-  constexpr int kSlot = 2048;                       // uint4 per slot: [X | W][k-step 0 | 1][tile 0..7][64]
+template <int R, int RH>
+__global__ __launch_bounds__(256 * RH, 3 - RH) void k_gemm_l5(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
+                                                         float* __restrict__ part, int M, int N, int KT, int ksp,
+                                                         int64_t split_stride, uint16_t* __restrict__ act_t) {
+  // RH row halves of 128 rows per work-group: 2 = the 256 x 256 tile with 8 waves described above; 1 = a
+  // 128 x 256 tile with 4 waves and 3 slots of 24 KiB, so that two work-groups share a compute unit (65..128
+  // rows, and the last rows of a taller operand).  Rows >= M of the last row block are computed on whatever the
+  // padded X operand holds (finite) and not stored.
+  constexpr int NWV = 4 * RH, MTB = 4 * RH, MTW = 4;
+  constexpr int kXs = 2 * MTB * 64;                 // uint4 of a slot's X part: [k-step 0 | 1][row tile][64]
+  constexpr int kSlot = kXs + 1024;                 // then W: [k-step 0 | 1][column tile 0..7][64]
+  constexpr int LPS = (2 * MTB + 16) / NWV;         // loads per wave and step: 2 of X, LPS - 2 of W
   extern __shared__ uint4 ring[];
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, rh = w >> 2, wc = w & 3;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, rh = (RH == 2) ? (w >> 2) : 0, wc = w & 3;
   const int nt0 = (blockIdx.x * 4 + wc) * 2;
   Xt += (int64_t)blockIdx.z * MTB * KT * 64;
   part += (int64_t)blockIdx.z * MTB * 32 * N;
+  const int row0 = (int)blockIdx.z * MTB * 32;
+  const int mrows = M - row0;                       // valid rows of this row block
   const int k0 = blockIdx.y * ksp;
   const int ns = (min(KT, k0 + ksp) - k0) >> 1;     // steps of two k-steps
-  const uint4* xp = Xt + ((int64_t)w * KT + k0) * 64 + lane;                          // row tile w
-  const uint4* wp = Wt + ((int64_t)(blockIdx.x * 8 + w) * KT + k0) * 64 + lane;       // column tile w of the block
+  const uint4* xp = Xt + (int64_t)k0 * 64 + lane;
+  const uint4* wp = Wt + ((int64_t)blockIdx.x * 8 * KT + k0) * 64 + lane;
 
   f32x16 acc[2][MTW];
 #pragma unroll
@@ -389,23 +397,32 @@ __global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, c
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
 
-  // load i (0..3) of step s into slot `slot`: X k-step 0, X k-step 1, W k-step 0, W k-step 1 of tile w
+  // load i (0 .. LPS - 1) of step s into slot `slot`: i < 2: X k-step i, row tile w; else fragment
+  // (i - 2) * NWV + w of the 16 weight fragments [k-step][column tile]
   auto issue = [&](int s, int slot, int i) {
-    const uint4* src = ((i & 2) ? wp : xp) + (int64_t)(2 * s + (i & 1)) * 64;
-    uint4* dst = ring + (size_t)slot * kSlot + ((i & 2) ? 1024 : 0) + (i & 1) * 512 + w * 64;
+    const uint4* src;
+    uint4* dst = ring + (size_t)slot * kSlot;
+    if (i < 2) {
+      src = xp + ((int64_t)w * KT + 2 * s + i) * 64;
+      dst += (i * MTB + w) * 64;
+    } else {
+      const int g = (i - 2) * NWV + w, kk = g >> 3, tile = g & 7;
+      src = wp + ((int64_t)tile * KT + 2 * s + kk) * 64;
+      dst += kXs + g * 64;
+    }
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                      (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
   };
-  // Every step issues exactly four loads, so "at most 4 (R - 2) outstanding" always means that the next
+  // Every step issues exactly LPS loads, so "at most LPS (R - 2) outstanding" always means that the next
   // step's slot has landed; past the end of the k range the loads re-fetch the last step into a slot that is
   // not read again (no branch in the loop body, and the counter arithmetic stays uniform).
-  constexpr int kAhead = 4 * (R - 2);
+  constexpr int kAhead = LPS * (R - 2);
   constexpr int kWaitAhead = (kAhead & 0xF) | ((kAhead >> 4) << 14) | (0x7 << 4) | (0xF << 8);   // vmcnt(kAhead) only
   if (ns > 0) {
 #pragma unroll
     for (int r = 0; r < R - 1; ++r)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) issue(min(r, ns - 1), r, i);
+      for (int i = 0; i < LPS; ++i) issue(min(r, ns - 1), r, i);
     __builtin_amdgcn_s_waitcnt(kWaitAhead);
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
@@ -426,40 +443,36 @@ __global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, c
         bf16x8 a0[MTW], a1[MTW], b0[2], b1[2];
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) a0[mt] = __builtin_bit_cast(bf16x8, base[(rh * MTW + mt) * 64 + lane]);
-        b0[0] = __builtin_bit_cast(bf16x8, base[1024 + (wc * 2) * 64 + lane]);
-        b0[1] = __builtin_bit_cast(bf16x8, base[1024 + (wc * 2 + 1) * 64 + lane]);
+        b0[0] = __builtin_bit_cast(bf16x8, base[kXs + (wc * 2) * 64 + lane]);
+        b0[1] = __builtin_bit_cast(bf16x8, base[kXs + (wc * 2 + 1) * 64 + lane]);
         __builtin_amdgcn_sched_barrier(0);
         issue(sn, nslot, 0);
         __builtin_amdgcn_sched_barrier(0);
+        // eight pairs of MFMAs (pair q: k-step q / 4, row tile q % 4); loads 1 .. LPS - 1 are spread over the
+        // three points behind pairs 1, 3 and 5, and the second k-step's fragments are read behind pair 1 (while direct-to-LDS loads
+        // are in flight every compiler-placed LDS wait is a full one, so reads issued earlier would not overlap)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[0], acc[0][mt], 0, 0, 0);
-          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[1], acc[1][mt], 0, 0, 0);
-        }
-        // the second k-step's fragments are read behind the first four MFMAs (while direct-to-LDS loads are
-        // in flight every compiler-placed LDS wait is a full one, so reads issued earlier would not overlap)
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) a1[mt] = __builtin_bit_cast(bf16x8, base[512 + (rh * MTW + mt) * 64 + lane]);
-        b1[0] = __builtin_bit_cast(bf16x8, base[1024 + 512 + (wc * 2) * 64 + lane]);
-        b1[1] = __builtin_bit_cast(bf16x8, base[1024 + 512 + (wc * 2 + 1) * 64 + lane]);
-        issue(sn, nslot, 1);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 2; mt < MTW; ++mt) {
-          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[0], acc[0][mt], 0, 0, 0);
-          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[1], acc[1][mt], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        issue(sn, nslot, 2);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) {
-          acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[0], acc[0][mt], 0, 0, 0);
-          acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[1], acc[1][mt], 0, 0, 0);
-          if (mt == 1) {
+        for (int q = 0; q < 8; ++q) {
+          const int mt = q & 3;
+          if (q < 4) {
+            acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[0], acc[0][mt], 0, 0, 0);
+            acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[1], acc[1][mt], 0, 0, 0);
+          } else {
+            acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[0], acc[0][mt], 0, 0, 0);
+            acc[1][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mt], b1[1], acc[1][mt], 0, 0, 0);
+          }
+          if ((q & 1) && q < 7) {
             __builtin_amdgcn_sched_barrier(0);
-            issue(sn, nslot, 3);
+            if (q == 1) {
+#pragma unroll
+              for (int m2 = 0; m2 < MTW; ++m2)
+                a1[m2] = __builtin_bit_cast(bf16x8, base[(MTB + rh * MTW + m2) * 64 + lane]);
+              b1[0] = __builtin_bit_cast(bf16x8, base[kXs + 512 + (wc * 2) * 64 + lane]);
+              b1[1] = __builtin_bit_cast(bf16x8, base[kXs + 512 + (wc * 2 + 1) * 64 + lane]);
+            }
+#pragma unroll
+            for (int i = 1; i < LPS; ++i)
+              if ((i - 1) * 3 / (LPS - 1) == (q - 1) / 2) issue(sn, nslot, i);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -476,14 +489,13 @@ __global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, c
 
   if (act_t != nullptr) {      // gate/up without a K split: silu(gate) * up
     const int col = (nt0 >> 1) * 32 + (lane & 31);
-    const int row0 = (int)blockIdx.z * MTB * 32;
 #pragma unroll
     for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         const float g = acc[0][mt][r], u = acc[1][mt][r];
-        act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
+        if (m < mrows) act_t[a_tiled_idx(N >> 5, row0 + m, col)] = f2bf(g / (1.0f + expf(-g)) * u);
       }
     return;
   }
@@ -495,7 +507,7 @@ __global__ __launch_bounds__(512) void k_gemm_l5(const uint4* __restrict__ Xt, c
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = (rh * MTW + mt) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        out[(int64_t)m * N + nt * 32] = acc[nt][mt][r];
+        if (m < mrows) out[(int64_t)m * N + nt * 32] = acc[nt][mt][r];
       }
 }
 
@@ -1282,6 +1294,25 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 #undef PMX_GEMM_CASE
 }
 
+// 0 = not asked yet, 1 = granted, 2 = refused: more than 64 KiB of dynamic LDS must be allowed once per device
+// and kernel
+template <int R, int RH>
+static bool ring_allowed(int lds) {
+  static std::atomic<int> state[64];
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  dev = std::min(std::max(dev, 0), 63);
+  int st = state[dev].load(std::memory_order_acquire);
+  if (st == 0) {
+    st = hipFuncSetAttribute((const void*)k_gemm_l5<R, RH>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) ==
+                 hipSuccess ? 1 : 2;
+    if (st == 2) (void)hipGetLastError();
+    state[dev].store(st, std::memory_order_release);
+  }
+  return st == 1;
+}
+
+// The X operand must be readable up to the next multiple of 256 rows (128 when M <= 128); rows >= M are not stored.
 static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, int M, int K, int N,
                        int n_split, uint16_t* act_t) {
   const int KT = K / 16;
@@ -1289,42 +1320,37 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
   const int S = large_gemm_splits(KT, n_split, &ksp);
   const int MTall = (M + 31) / 32;
   const int64_t stride = (int64_t)MTall * 32 * N;
-  const int full = M / 256, rem = M - full * 256;
   if (S > 1) act_t = nullptr;       // the fused SwiGLU epilogue needs the whole K range in one work-group
-  dim3 block(256);
-  if (full) {    // whole blocks of 256 rows: one launch, row blocks along grid.z
-    // the ring kernel's slots hold two k-steps; odd k ranges (or the tuning switch) take the 4-wave tile
-    static const bool four_waves = getenv("PIPEMAX_GEMM_L1") != nullptr;
-    const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);
-    if (even && !four_waves) {
-      constexpr int R = 4;
-      constexpr int lds = R * 2048 * 16;
-      // 128 KiB of dynamic LDS must be allowed once per device (0 = not asked yet, 1 = granted, 2 = refused)
-      static std::atomic<int> ring_state[64];
-      int dev = 0;
-      (void)hipGetDevice(&dev);
-      dev = std::min(std::max(dev, 0), 63);
-      int st = ring_state[dev].load(std::memory_order_acquire);
-      if (st == 0) {
-        st = hipFuncSetAttribute((const void*)k_gemm_l5<R>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) ==
-                     hipSuccess ? 1 : 2;
-        if (st == 2) (void)hipGetLastError();
-        ring_state[dev].store(st, std::memory_order_release);
-      }
-      if (st == 1)
-        hipLaunchKernelGGL((k_gemm_l5<R>), dim3(N / 256, S, full), dim3(512), lds, s, (const uint4*)Xt,
-                           (const uint4*)Wt, part, N, KT, ksp, stride, act_t);
-      else
-        hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt,
-                           (const uint4*)Wt, part, full * 256, N, KT, ksp, stride, act_t);
-    } else
-      hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
-                         part, full * 256, N, KT, ksp, stride, act_t);
+  // the ring kernel's slots hold two k-steps; odd k ranges (or the tuning switch) take the 4-wave tile
+  static const bool four_waves = getenv("PIPEMAX_GEMM_L1") != nullptr;
+  const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);
+  constexpr int R2 = 4, kLds2 = R2 * 2048 * 16;       // 256-row blocks: 4 slots of 32 KiB
+  constexpr int R1 = 3, kLds1 = R1 * 1536 * 16;       // 128-row block: 3 slots of 24 KiB, two work-groups per CU
+  if (even && !four_waves && ring_allowed<R2, 2>(kLds2) && ring_allowed<R1, 1>(kLds1)) {
+    // blocks of 256 rows along grid.z; a last block of at most 128 rows takes the 128-row tile
+    const int rem = M % 256;
+    const int tall = (rem == 0 || rem > 128) ? (M + 255) / 256 : M / 256;
+    if (tall)
+      hipLaunchKernelGGL((k_gemm_l5<R2, 2>), dim3(N / 256, S, tall), dim3(512), kLds2, s, (const uint4*)Xt,
+                         (const uint4*)Wt, part, M, N, KT, ksp, stride, act_t);
+    if (tall * 256 < M) {
+      const uint4* Xr = (const uint4*)Xt + (int64_t)tall * 8 * KT * 64;
+      float* pr = part + (int64_t)tall * 256 * N;
+      // the A-tiled output of these rows starts at row tile tall * 8 of the next GEMM's operand
+      uint16_t* ar = act_t ? act_t + (int64_t)tall * 8 * (N >> 5) * 512 : nullptr;
+      hipLaunchKernelGGL((k_gemm_l5<R1, 1>), dim3(N / 256, S, 1), dim3(256), kLds1, s, Xr, (const uint4*)Wt, pr,
+                         M - tall * 256, N, KT, ksp, stride, ar);
+    }
+    return;
   }
+  const int full = M / 256, rem = M - full * 256;
+  dim3 block(256);
+  if (full)      // whole blocks of 256 rows: one launch, row blocks along grid.z
+    hipLaunchKernelGGL((k_gemm_l<8, 4>), dim3(N / 256, S, full), block, 0, s, (const uint4*)Xt, (const uint4*)Wt,
+                       part, full * 256, N, KT, ksp, stride, act_t);
   if (rem) {     // the remaining rows with the smallest tile count that covers them
     const uint4* Xr = (const uint4*)Xt + (int64_t)full * 8 * KT * 64;
     float* pr = part + (int64_t)full * 256 * N;
-    // the A-tiled output of the remaining rows starts at row tile full * 8 of the next GEMM's operand
     uint16_t* ar = act_t ? act_t + (int64_t)full * 8 * (N >> 5) * 512 : nullptr;
     dim3 grid(N / 256, S);
     if (rem <= 128)
