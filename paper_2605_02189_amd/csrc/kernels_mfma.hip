@@ -530,6 +530,7 @@ __global__ __launch_bounds__(256 * RH, 3 - RH) void k_gemm_l5(const uint4* __res
 // =================================================================================================
 enum { EPI_SWIGLU = 1, EPI_RESID = 2, EPI_QKV = 3 };
 
+
 struct FusedArgs {
   int* counters;          // one per 64-column block; zero at launch, reset by the last arriver
   const float* ssq_in;    // [64][n_ssq_in] partial sums of squares of A's rows, or null (no row factor)
@@ -559,7 +560,10 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
                                                      float* __restrict__ part, FusedArgs A, int M, int N,
                                                      int KT, int ksp, int64_t split_stride) {
   constexpr int NT = 2;
-  __shared__ float red[NWK][NT * 16][64];
+  // cross-wave reduction buffer: MP row tiles per pass, [wave][(row tile * NT + column tile) * 4 + g][lane] holds
+  // accumulator registers 4 g .. 4 g + 3 (rows 8 g + 4 (lane >> 5) + 0 .. 3 of the tile) as one 16-byte word
+  constexpr int MP = (MT == 1) ? 1 : (NWK == 4 || MT == 4) ? 2 : 1;
+  __shared__ float4 red[NWK][MP * NT * 4][64];
   __shared__ float rs[MT * 32];
   __shared__ int s_last;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
@@ -625,9 +629,44 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
     }
   }
 
-  // the epilogue of output element pair (row m; columns c and c + 32 of the block), c = lane & 31.
-  // All 64 lanes call it together (it contains wave shuffles); the 32 lanes of a half-wave share m.
-  auto epi = [&](int m, int c, float lo, float hi) {
+  // The epilogue of output element pair (row m; columns c and c + 32 of the block), c = lane & 31, in two
+  // parts: `pre` requests what the epilogue reads from memory besides the sums, `epi` computes and stores.
+  // A thread that owns several pairs calls `pre` for all of them first: its stores may alias its loads as
+  // far as the compiler can tell, so loads left inside `epi` would each wait behind the previous pair's
+  // stores -- one exposed memory latency per pair.
+  struct Pre {
+    float xl, xh;      // EPI_RESID: the residual stream
+    float2 cs;         // EPI_QKV: RoPE factors; position and physical page of the row's new token
+    int pos, phys;
+  };
+  float gain_lo = 1.f, gain_hi = 1.f;      // EPI_RESID: the next norm's gain of this thread's two columns
+  if (EPI == EPI_RESID && A.hout == nullptr) {
+    gain_lo = bf2f(A.gain_next[blockIdx.x * 64 + (lane & 31)]);
+    gain_hi = bf2f(A.gain_next[blockIdx.x * 64 + (lane & 31) + 32]);
+  }
+  auto pre = [&](int m, int c) {
+    Pre P;
+    P.xl = P.xh = 0.f;
+    P.cs = make_float2(0.f, 0.f);
+    P.pos = P.phys = 0;
+    if (m < M) {
+      if (EPI == EPI_RESID) {
+        const int64_t o = (int64_t)m * N + (int64_t)blockIdx.x * 64 + c;
+        P.xl = A.x[o];
+        P.xh = A.x[o + 32];
+      } else if (EPI == EPI_QKV) {
+        const int hd = blockIdx.x >> 1, j = ((blockIdx.x & 1) << 5) + c;
+        if (hd < A.Hq + A.Hkv) P.cs = A.cs[m * 64 + j];
+        if (hd >= A.Hq) {
+          P.pos = A.ctx[m];
+          P.phys = A.table[(int64_t)m * A.max_pages + (P.pos >> 4)];
+        }
+      }
+    }
+    return P;
+  };
+  // All 64 lanes call `epi` together (it contains wave shuffles); the 32 lanes of a half-wave share m.
+  auto epi = [&](int m, int c, float lo, float hi, const Pre& P) {
     const bool ok = m < M;
     if (EPI == EPI_SWIGLU) {
       if (ok) {
@@ -639,8 +678,8 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
       const int64_t o = (int64_t)m * N + (int64_t)blockIdx.x * 64 + c;
       float xl = 0.f, xh = 0.f;
       if (ok) {
-        xl = A.x[o] + lo;
-        xh = A.x[o + 32] + hi;
+        xl = P.xl + lo;
+        xh = P.xh + hi;
         A.x[o] = xl;
         A.x[o + 32] = xh;
         if (A.hout) {
@@ -648,8 +687,8 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
           A.hout[o + 32] = f2bf(xh);
         } else {
           const int n = blockIdx.x * 64 + c;
-          A.xg_t[a_tiled_idx(N >> 4, m, n)] = f2bf(xl * bf2f(A.gain_next[n]));
-          A.xg_t[a_tiled_idx(N >> 4, m, n + 32)] = f2bf(xh * bf2f(A.gain_next[n + 32]));
+          A.xg_t[a_tiled_idx(N >> 4, m, n)] = f2bf(xl * gain_lo);
+          A.xg_t[a_tiled_idx(N >> 4, m, n + 32)] = f2bf(xh * gain_hi);
         }
       }
       float ss = xl * xl + xh * xh;
@@ -663,23 +702,19 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
         hi *= r;
         const int hd = blockIdx.x >> 1, j = ((blockIdx.x & 1) << 5) + c;
         if (hd < A.Hq) {
-          const float2 cs = A.cs[m * 64 + j];
           uint16_t* q = A.q_out + ((int64_t)m * A.Hq + hd) * 128;
-          q[j] = f2bf(lo * cs.x - hi * cs.y);
-          q[j + 64] = f2bf(hi * cs.x + lo * cs.y);
+          q[j] = f2bf(lo * P.cs.x - hi * P.cs.y);
+          q[j + 64] = f2bf(hi * P.cs.x + lo * P.cs.y);
         } else {
           const int kv = (hd < A.Hq + A.Hkv) ? 0 : 1;
           const int head = hd - A.Hq - kv * A.Hkv;
           if (kv == 0) {
-            const float2 cs = A.cs[m * 64 + j];
-            const float a = lo * cs.x - hi * cs.y, b2 = hi * cs.x + lo * cs.y;
+            const float a = lo * P.cs.x - hi * P.cs.y, b2 = hi * P.cs.x + lo * P.cs.y;
             lo = a;
             hi = b2;
           }
-          const int pos = A.ctx[m];
-          const int phys = A.table[(int64_t)m * A.max_pages + (pos >> 4)];
-          const int slot = pos & 15;
-          uint16_t* sub = A.pool + (int64_t)phys * A.page_elems + sub_block_off(A.Hkv, 128, A.layer, head, kv);
+          const int slot = P.pos & 15;
+          uint16_t* sub = A.pool + (int64_t)P.phys * A.page_elems + sub_block_off(A.Hkv, 128, A.layer, head, kv);
           const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
           if (kv == 0) {
             sub[k_sub_idx(slot, j)] = blo;
@@ -698,31 +733,44 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
 
   const bool split = gridDim.y > 1;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    if (mt) __syncthreads();
+  for (int mt0 = 0; mt0 < MT; mt0 += MP) {
+    if (mt0) __syncthreads();
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int mtl = 0; mtl < MP; ++mtl)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) red[w][nt * 16 + r][lane] = acc[nt * MT + mt][r];
-    __syncthreads();            // also orders the rs[] writes before their use
-    for (int r = w; r < 16; r += NWK) {
-      float v[NT];
+      for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        float a = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < NWK; ++ww) a += red[ww][nt * 16 + r][lane];
-        v[nt] = a;
-      }
-      const int m = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      if (split) {
-        if (m < M) {
-          float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + (lane & 31);
-          st_agent(out, v[0]);
-          st_agent(out + 32, v[1]);
+        for (int g = 0; g < 4; ++g) {
+          const f32x16& a = acc[nt * MT + mt0 + mtl];
+          red[w][(mtl * NT + nt) * 4 + g][lane] = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
         }
+    __syncthreads();            // also orders the rs[] writes before their use
+    // a wave sums, over the waves in order, four rows of both column tiles
+    for (int combo = w; combo < MP * 4; combo += NWK) {
+      const int mtl = combo >> 2, g = combo & 3;
+      float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+#pragma unroll
+      for (int ww = 0; ww < NWK; ++ww) {
+        const float4 a = red[ww][(mtl * NT) * 4 + g][lane], c2 = red[ww][(mtl * NT + 1) * 4 + g][lane];
+        v0.x += a.x; v0.y += a.y; v0.z += a.z; v0.w += a.w;
+        v1.x += c2.x; v1.y += c2.y; v1.z += c2.z; v1.w += c2.w;
+      }
+      const float lo4[4] = {v0.x, v0.y, v0.z, v0.w}, hi4[4] = {v1.x, v1.y, v1.z, v1.w};
+      const int m0 = (mt0 + mtl) * 32 + 8 * g + 4 * (lane >> 5);
+      if (split) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (m0 + i < M) {
+            float* out = part + (int64_t)blockIdx.y * split_stride + (int64_t)(m0 + i) * N + (int64_t)nt0 * 32 + (lane & 31);
+            st_agent(out, lo4[i]);
+            st_agent(out + 32, hi4[i]);
+          }
       } else {
-        epi(m, lane & 31, v[0], v[1]);
+        Pre P[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) P[i] = pre(m0 + i, lane & 31);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) epi(m0 + i, lane & 31, lo4[i], hi4[i], P[i]);
       }
     }
   }
@@ -737,31 +785,40 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
     constexpr int NE = (MT * 1024) / (NWK * 64);       // output pairs per thread
     const int S = (int)gridDim.y;
     float lo[NE], hi[NE];
+    Pre P[NE];
 #pragma unroll
     for (int q = 0; q < NE; ++q) {
+      const int e = tid + q * NWK * 64;
       lo[q] = 0.f;
       hi[q] = 0.f;
+      P[q] = pre(e >> 5, e & 31);
     }
-    // all loads of a split are issued together; the sums run in split order
-    for (int s = 0; s < S; ++s) {
-      float tl[NE], th[NE];
+    // the loads of UD splits are in flight together; the sums run in split order (an absent split adds 0)
+    constexpr int UD = (NE <= 8) ? 4 : 2;
+    for (int s0 = 0; s0 < S; s0 += UD) {
+      float tl[UD][NE], th[UD][NE];
 #pragma unroll
-      for (int q = 0; q < NE; ++q) {
-        const int e = tid + q * NWK * 64, m = e >> 5, c = e & 31;
-        const float* p = part + (int64_t)s * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + c;
-        tl[q] = (m < M) ? ld_agent(p) : 0.f;
-        th[q] = (m < M) ? ld_agent(p + 32) : 0.f;
-      }
+      for (int u = 0; u < UD; ++u)
 #pragma unroll
-      for (int q = 0; q < NE; ++q) {
-        lo[q] += tl[q];
-        hi[q] += th[q];
-      }
+        for (int q = 0; q < NE; ++q) {
+          const int e = tid + q * NWK * 64, m = e >> 5, c = e & 31;
+          const float* p = part + (int64_t)(s0 + u) * split_stride + (int64_t)m * N + (int64_t)nt0 * 32 + c;
+          const bool ok = m < M && s0 + u < S;
+          tl[u][q] = ok ? ld_agent(p) : 0.f;
+          th[u][q] = ok ? ld_agent(p + 32) : 0.f;
+        }
+#pragma unroll
+      for (int u = 0; u < UD; ++u)
+#pragma unroll
+        for (int q = 0; q < NE; ++q) {
+          lo[q] += tl[u][q];
+          hi[q] += th[u][q];
+        }
     }
 #pragma unroll
     for (int q = 0; q < NE; ++q) {
       const int e = tid + q * NWK * 64;
-      epi(e >> 5, e & 31, lo[q], hi[q]);
+      epi(e >> 5, e & 31, lo[q], hi[q], P[q]);
     }
   }
   if (EPI == EPI_RESID && A.ctx_advance != nullptr && blockIdx.x == 0 && tid < M) A.ctx_advance[tid] += 1;
