@@ -142,11 +142,12 @@ def test_bf16_matrix_core_path_ragged():
     runner.stage.destroy()
 
 
-@pytest.mark.parametrize("rows", [70, 150])
+@pytest.mark.parametrize("rows", [70, 128, 150, 300])
 def test_bf16_wide_batch(rows):
-    """More than 64 rows.  70 rows: the fused pipeline with four row tiles per wave (the last two partial
-    or empty).  150 rows: the large-tile GEMM (five row tiles, the last one partial) with the separate
-    element-wise kernels."""
+    """More than 64 rows.  70 and 128 rows: the fused pipeline with four row tiles per wave (at 70 the last
+    two partial or empty).  150 rows: the large-tile GEMM (one 256-row block, its rows past 150 not stored)
+    with the separate element-wise kernels.  300 rows: a 256-row block plus the 128-row tile for the
+    remaining 44."""
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
