@@ -363,7 +363,8 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 //   * one barrier per two k-steps (16 MFMAs per wave), and the fragments of the slot's second k-step are read
 //     from LDS while the first is multiplied.
 //   A load issued during step s fills the slot read in step s + R - 1: it has R - 2 whole steps to land.
-//   Whole blocks of 256 rows, k ranges of an even number of k-steps.
+//   k ranges of an even number of k-steps; the X operand is readable up to the end of the last row block, whose
+//   rows >= M are computed and not stored.
 // =================================================================================================
 template <int R, int RH>
 __global__ __launch_bounds__(256 * RH, 3 - RH) void k_gemm_l5(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
