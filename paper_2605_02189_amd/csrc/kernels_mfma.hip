@@ -938,7 +938,12 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
   __shared__ int s_last;
   // work-groups are dispatched in grid order: `order` lists the sequences longest first, so that the
   // long ones start early and the kernel's tail consists of short ones
-  const int chunk = blockIdx.x, c = blockIdx.y, i = order[blockIdx.z];
+  // Work-groups go to the 8 XCDs round-robin in grid order; with the KV head taken from blockIdx.y alone every XCD
+  // would read one fixed 4 KiB slot of each page's 64 KiB layer block for the whole launch.  Wave times differ
+  // between slots and between XCDs (cycle counters: up to 40 %), and a slow slot that stays on a slow XCD sets the
+  // launch time; rotating the head by the sequence index gives every XCD all slots (-6 % on a one-layer stage,
+  // whose pages are 64 KiB apart; -1 % with eight layers per page).
+  const int chunk = blockIdx.x, c = (blockIdx.y + blockIdx.z) % gridDim.y, i = order[blockIdx.z];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
   const int G = D.G;
   // issue the three independent first loads together: length, this wave's page ids, Q
