@@ -939,7 +939,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
   // work-groups are dispatched in grid order: `order` lists the sequences longest first, so that the
   // long ones start early and the kernel's tail consists of short ones
   // Work-groups go to the 8 XCDs round-robin in grid order; with the KV head taken from blockIdx.y alone every XCD
-  // would read one fixed 4 KiB slot of each page's 64 KiB layer block for the whole launch.  Wave times differ
+  // would read one fixed 8 KiB slot (K and V of its head) of each page's 64 KiB layer block for the whole launch.  Wave times differ
   // between slots and between XCDs (cycle counters: up to 40 %), and a slow slot that stays on a slow XCD sets the
   // launch time; rotating the head by the sequence index gives every XCD all slots (-6 % on a one-layer stage,
   // whose pages are 64 KiB apart; -1 % with eight layers per page).
