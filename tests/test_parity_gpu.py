@@ -438,3 +438,45 @@ def test_config2_full_size_sampled_rows():
     # every step streamed one whole micro-batch in (64 prefix pages + grown pages per sequence)
     assert st["h2d_bytes"] >= steps * 64 * 64 * shape.page_bytes
     runner.stage.destroy()
+
+
+def test_config3_ragged_full_shape_sampled_rows():
+    """configs[2] at its full layer shapes and batch (128 ragged sequences of 512..4096 tokens per
+    micro-batch, 8 layers, sigma = 1), two of its six micro-batches for two cycles: the fused path with
+    four row tiles per wave, attention over up to 257 pages per sequence with the long sequences split.
+    The oracle follows the longest, the shortest and two other sequences of each micro-batch."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = CONFIGS["C3"].with_(n_microbatches=2)
+    syn = SynthInputs(shape, seed=0, gain_jitter=0.1)
+    steps = 2 * shape.n_microbatches
+    runner = StageRunner(shape, syn, steps=steps, flags=pm.FLAG_CAPTURE_LAYERS).load()
+    assert runner.stage.get_stats()["engine"] == 1
+    sample = {}
+    for mb in range(shape.n_microbatches):
+        lens = np.asarray(runner.ctx0[mb])
+        sample[mb] = sorted({int(lens.argmax()), int(lens.argmin()), 5 + mb, 127})
+    orc = _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer=1e-2, tol_delta=3e-2, oracle_seqs=sample)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs=sample)
+    runner.stage.destroy()
+
+
+def test_config4_layer_shapes_sampled_rows():
+    """configs[3]'s layer shapes and batch (hidden 8192, 64/8 heads, ffn 28672, 256 sequences of 2048
+    tokens) on two of its ten layers and two micro-batches: the large-tile GEMMs at 256 rows with the
+    separate element-wise kernels, at the sizes bench.py --config C4 launches them."""
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = CONFIGS["C4"].with_(n_microbatches=2, n_layers=2)
+    syn = SynthInputs(shape, seed=0, gain_jitter=0.1)
+    steps = 2 * shape.n_microbatches
+    runner = StageRunner(shape, syn, steps=steps, flags=pm.FLAG_CAPTURE_LAYERS).load()
+    assert runner.stage.get_stats()["engine"] == 1
+    sample = {mb: [0, 100 + mb, 255] for mb in range(shape.n_microbatches)}
+    orc = _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer=1e-2, tol_delta=3e-2, oracle_seqs=sample)
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs=sample)
+    runner.stage.destroy()
