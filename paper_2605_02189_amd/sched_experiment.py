@@ -47,9 +47,9 @@ def main():
     ap.add_argument("--pool-frac", type=float, default=0.75)
     ap.add_argument("--seed", type=int, default=0)
     # Eq. 2 parameters and B as fitted / measured by fit_estimator on this GPU for the C2 stage
-    ap.add_argument("--alpha-us", type=float, default=3.0)
+    ap.add_argument("--alpha-us", type=float, default=2.7)
     ap.add_argument("--beta-ns", type=float, default=6.3)
-    ap.add_argument("--delta-ms", type=float, default=0.88)
+    ap.add_argument("--delta-ms", type=float, default=0.87)
     ap.add_argument("--link-gbs", type=float, default=56.66)
     ap.add_argument("--static", default="0.005,0.01,0.025,0.05,0.10,0.15,0.20,0.25")
     ap.add_argument("--verbose", action="store_true")
