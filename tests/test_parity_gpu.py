@@ -142,12 +142,13 @@ def test_bf16_matrix_core_path_ragged():
     runner.stage.destroy()
 
 
-@pytest.mark.parametrize("rows", [70, 128, 150, 300])
+@pytest.mark.parametrize("rows", [70, 128, 150, 257, 300, 384, 385])
 def test_bf16_wide_batch(rows):
     """More than 64 rows.  70 and 128 rows: the fused pipeline with four row tiles per wave (at 70 the last
     two partial or empty).  150 rows: the large-tile GEMM (one 256-row block, its rows past 150 not stored)
     with the separate element-wise kernels.  300 rows: a 256-row block plus the 128-row tile for the
-    remaining 44."""
+    remaining 44; 257, 384 and 385 rows are the edges of that choice (1 and 128 rows in the 128-row tile,
+    129 rows in a second 256-row block)."""
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
