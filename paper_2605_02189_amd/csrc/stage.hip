@@ -512,7 +512,7 @@ bool mfma_shape_ok(const pipemax_config_t& c) {
          nq % 16 == 0 && c.n_q_heads / c.n_kv_heads <= 16 &&
          // more than 256 rows per pass (prefill chunks) need the large-tile GEMM for every matrix
          (c.max_seqs_per_mb <= 256 ||
-          (c.max_seqs_per_mb <= 1024 && (nq + 2 * c.n_kv_heads * c.head_dim) % 256 == 0 && c.hidden % 256 == 0 &&
+          (c.max_seqs_per_mb <= 4096 && (nq + 2 * c.n_kv_heads * c.head_dim) % 256 == 0 && c.hidden % 256 == 0 &&
            (2 * c.ffn) % 256 == 0));
 }
 

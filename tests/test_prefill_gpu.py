@@ -29,7 +29,8 @@ def _oracle_prefill(orc, syn, mb, seq, x):
     return out
 
 
-@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_xl_wide_ffn", "mfma_long_context",
+@pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_xxl_chunks", "mfma_xl_wide_ffn",
+                                  "mfma_long_context",
                                   "generic_fp32"])
 def test_prefill_matches_token_by_token_oracle(case):
     import torch
@@ -42,9 +43,11 @@ def test_prefill_matches_token_by_token_oracle(case):
         shape = CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=6)
         tol, plan = 1e-5, [(0, 21), (1, 19), (0, 8)]
     else:
-        xl = case in ("mfma_xl_chunks", "mfma_xl_wide_ffn")
+        xl = case in ("mfma_xl_chunks", "mfma_xxl_chunks", "mfma_xl_wide_ffn")
         b = 70 if case == "mfma_wide_chunks" else 6 if xl else 20
         max_rows = 600 if xl else None                            # two 256-row blocks + a remainder per pass
+        if case == "mfma_xxl_chunks":
+            max_rows = 1300                                       # five 256-row blocks + 20 rows: beyond 1024 rows per pass
         # the wide FFN makes the gate/up GEMM of a 600-row pass un-split: SwiGLU runs in its epilogue
         shape = StageShape(name=case, n_layers=1 if case == "mfma_xl_wide_ffn" else 2, hidden=1024, n_q_heads=8,
                            n_kv_heads=2, head_dim=128, ffn=16384 if case == "mfma_xl_wide_ffn" else 2816,
@@ -55,6 +58,8 @@ def test_prefill_matches_token_by_token_oracle(case):
         plan = [(0, 45), (1, 30), (0, 17)] if b == 20 else [(0, 150), (1, 75)]
         if xl:
             plan = [(0, 700), (1, 300)]
+        if case == "mfma_xxl_chunks":
+            plan = [(0, 1400), (1, 100)]
         if case == "mfma_long_context":                    # beyond the chunk kernel's 256 pages: per-row kernel
             plan = [(1, 30), (0, 5)]
     syn = SynthInputs(shape, seed=31, pool_elems=1 << 23, gain_jitter=0.1)
