@@ -133,7 +133,12 @@ typedef struct {
                                   /* worker thread that issues them (FLAG_TIME_KERNELS)      */
   double   kernel_ms[PIPEMAX_N_KCLASS];        /* summed kernel durations per class          */
   uint64_t kernel_launches[PIPEMAX_N_KCLASS];
-  int32_t  engine;                /* 0 = shape-generic kernels, 1 = matrix-core (bf16) kernels */
+  int32_t  engine;                /* 0 = shape-generic kernels, 1 = matrix-core (bf16) kernels.
+                                     The matrix-core kernels serve bf16 stages with head_dim 128,
+                                     hidden % 128 == 0, ffn % 64 == 0, at most 16 query heads per KV
+                                     head and max_seqs_per_mb <= 256 -- or <= 4096 when hidden,
+                                     (n_q_heads + 2 n_kv_heads) * head_dim and 2 * ffn are multiples
+                                     of 256; every other stage runs on the generic kernels.        */
   int32_t  gpu_pages_total, gpu_pages_free, host_pages_total, host_pages_free;
   uint64_t page_bytes;
 } pipemax_stats_t;
