@@ -555,15 +555,15 @@ struct FusedArgs {
   int64_t page_elems;
 };
 
-template <int MT, int NWK, int U, int EPI>
+template <int MT, int NWK, int U, int EPI, int MP>
 __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ Xt,
                                                      const uint4* __restrict__ Wt,
                                                      float* __restrict__ part, FusedArgs A, int M, int N,
                                                      int KT, int ksp, int64_t split_stride) {
   constexpr int NT = 2;
-  // cross-wave reduction buffer: MP row tiles per pass, [wave][(row tile * NT + column tile) * 4 + g][lane] holds
-  // accumulator registers 4 g .. 4 g + 3 (rows 8 g + 4 (lane >> 5) + 0 .. 3 of the tile) as one 16-byte word
-  constexpr int MP = (MT == 1) ? 1 : (NWK == 4 || MT == 4) ? 2 : 1;
+  // cross-wave reduction buffer: MP row tiles per pass (NWK * MP * 8 KiB), [wave][(row tile * NT + column tile) * 4 + g]
+  // [lane] holds accumulator registers 4 g .. 4 g + 3 (rows 8 g + 4 (lane >> 5) + 0 .. 3 of the tile) as one 16-byte word
+  static_assert(MT % MP == 0, "whole passes");
   __shared__ float4 red[NWK][MP * NT * 4][64];
   __shared__ float rs[MT * 32];
   __shared__ int s_last;
@@ -1465,6 +1465,22 @@ void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uin
                      (double)rope_base);
 }
 
+static int compute_units() {      // of the current device (cached per device)
+  static std::atomic<int> cus[64];
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  dev = std::min(std::max(dev, 0), 63);
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    cus[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
 template <int NWK, int EPI>
 static void gemm_fused_t(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float* part, const FusedArgs& A,
                          int M, int K, int N, int n_split) {
@@ -1475,13 +1491,19 @@ static void gemm_fused_t(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, 
   const int64_t stride = (int64_t)MT * 32 * N;
   dim3 grid(N / 64, S), block(NWK * 64);
   if (MT <= 1)
-    hipLaunchKernelGGL((k_gemm_f<1, NWK, 4, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
+    hipLaunchKernelGGL((k_gemm_f<1, NWK, 4, EPI, 1>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
                        N, KT, ksp, stride);
-  else if (MT <= 2)     // two k-steps in flight measured 1-4 % faster than four, six or eight (fewer registers)
-    hipLaunchKernelGGL((k_gemm_f<2, NWK, 2, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
-                       N, KT, ksp, stride);
-  else     // up to 128 rows: 8 accumulator tiles per wave, two k-steps in flight as well
-    hipLaunchKernelGGL((k_gemm_f<4, NWK, 2, EPI>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
+  else if (MT <= 2) {   // two k-steps in flight measured 1-4 % faster than four, six or eight (fewer registers)
+    // Both row tiles in one reduction pass keep all eight waves busy in it (-0.5 .. -1.3 us per launch), but 128 KiB
+    // of LDS leave room for one work-group per compute unit: only where the grid does not ask for a second one.
+    if (NWK == 4 || (int)(grid.x * grid.y) <= compute_units())
+      hipLaunchKernelGGL((k_gemm_f<2, NWK, 2, EPI, 2>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A,
+                         M, N, KT, ksp, stride);
+    else
+      hipLaunchKernelGGL((k_gemm_f<2, NWK, 2, EPI, 1>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A,
+                         M, N, KT, ksp, stride);
+  } else     // up to 128 rows: 8 accumulator tiles per wave, two k-steps in flight as well
+    hipLaunchKernelGGL((k_gemm_f<4, NWK, 2, EPI, 2>), grid, block, 0, s, (const uint4*)Xt, (const uint4*)Wt, part, A, M,
                        N, KT, ksp, stride);
 }
 
