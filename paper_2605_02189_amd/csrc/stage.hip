@@ -481,7 +481,12 @@ GemmPlan plan_gemm_large(int N, int K, int M) {
     if (KT % 2 == 0) ksp += ksp & 1;      // the ring kernel works on pairs of k-steps
     const int split = (KT + ksp - 1) / ksp;
     const int rounds = (bn * split + 255) / 256;
-    const double cost = rounds * (0.42 * ksp + 4.5) + (split > 1 ? split * part_us : 0.0);
+    double cost = rounds * (0.42 * ksp + 4.5) + (split > 1 ? split * part_us : 0.0);
+    // One row block: every work-group streams weights of its own, and at the ring kernel's rate 256 of them ask for
+    // about 5 TB/s.  A round that needs (nearly) every compute unit then runs 10-25 % longer than one that leaves an
+    // eighth of them free (256 rows, 32 tiles x 6 / 7 / 8 splits of k = 8192: 46.7 / 49.7 / 57.8 us).  With several
+    // row blocks the weight tiles are shared through L2 and the full round is the faster one (1024 rows: 0.68 vs 0.72 ms).
+    if (rb == 1 && bn * split - (rounds - 1) * 256 > 224) cost += 0.25 * (0.42 * ksp + 4.5);
     if (S == 1 || cost < best_cost) {
       best = split;
       best_cost = cost;
