@@ -30,6 +30,7 @@ def _oracle_prefill(orc, syn, mb, seq, x):
 
 
 @pytest.mark.parametrize("case", ["mfma_fused_chunks", "mfma_wide_chunks", "mfma_xl_chunks", "mfma_xxl_chunks", "mfma_xl_wide_ffn",
+                                  "mfma_xl_grouped",
                                   "mfma_long_context",
                                   "generic_fp32"])
 def test_prefill_matches_token_by_token_oracle(case):
@@ -43,16 +44,22 @@ def test_prefill_matches_token_by_token_oracle(case):
         shape = CONFIGS["C1"].with_(n_microbatches=1, seqs_per_mb=6)
         tol, plan = 1e-5, [(0, 21), (1, 19), (0, 8)]
     else:
-        xl = case in ("mfma_xl_chunks", "mfma_xxl_chunks", "mfma_xl_wide_ffn")
+        xl = case in ("mfma_xl_chunks", "mfma_xxl_chunks", "mfma_xl_wide_ffn", "mfma_xl_grouped")
         b = 70 if case == "mfma_wide_chunks" else 6 if xl else 20
         max_rows = 600 if xl else None                            # two 256-row blocks + a remainder per pass
         if case == "mfma_xxl_chunks":
             max_rows = 1300                                       # five 256-row blocks + 20 rows: beyond 1024 rows per pass
         # the wide FFN makes the gate/up GEMM of a 600-row pass un-split: SwiGLU runs in its epilogue
-        shape = StageShape(name=case, n_layers=1 if case == "mfma_xl_wide_ffn" else 2, hidden=1024, n_q_heads=8,
-                           n_kv_heads=2, head_dim=128, ffn=16384 if case == "mfma_xl_wide_ffn" else 2816,
-                           dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
-                           decode_steps=1)
+        if case == "mfma_xl_grouped":
+            # every matrix has a multiple of 8 column blocks of 256: the large GEMM walks its tiles XCD by XCD
+            shape = StageShape(name=case, n_layers=2, hidden=2048, n_q_heads=12, n_kv_heads=2, head_dim=128, ffn=2048,
+                               dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
+                               decode_steps=1)
+        else:
+            shape = StageShape(name=case, n_layers=1 if case == "mfma_xl_wide_ffn" else 2, hidden=1024, n_q_heads=8,
+                               n_kv_heads=2, head_dim=128, ffn=16384 if case == "mfma_xl_wide_ffn" else 2816,
+                               dtype="bf16", rope_base=500000.0, n_microbatches=1, seqs_per_mb=b, ctx_lo=1, ctx_hi=60,
+                               decode_steps=1)
         tol = 1e-2
         # (sequence, new tokens): several chunks each; sequence 1 continues an existing prefix
         plan = [(0, 45), (1, 30), (0, 17)] if b == 20 else [(0, 150), (1, 75)]
