@@ -119,6 +119,8 @@ def main():
 
     import numpy as np
     import torch
+    from paper_2605_02189_amd.build import ensure_built
+    ensure_built()      # loads what is built; builds only if nothing is
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.harness import StageRunner
     from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs

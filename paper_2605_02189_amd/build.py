@@ -50,5 +50,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """For the harness entry points (tests, smoke, bench): builds the library only if there is none.
+    The binding itself never builds and never falls back: it raises when the library is missing."""
+    return LIB if os.path.exists(LIB) else build(verbose=False)
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

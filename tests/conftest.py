@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load what is built; only if nothing is built yet they build it (hipcc cross-compiles without a GPU)
+    from paper_2605_02189_amd.build import ensure_built
+    ensure_built()
 
 
 def rel_l2(a, b):
