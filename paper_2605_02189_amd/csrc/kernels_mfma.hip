@@ -654,7 +654,7 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
     int pos, phys;
   };
   float gain_lo = 1.f, gain_hi = 1.f;      // EPI_RESID: the next norm's gain of this thread's two columns
-  if (EPI == EPI_RESID && A.hout == nullptr) {
+  if (EPI == EPI_RESID && A.hout == nullptr && A.gain_next != nullptr) {
     gain_lo = bf2f(A.gain_next[blockIdx.x * 64 + (lane & 31)]);
     gain_hi = bf2f(A.gain_next[blockIdx.x * 64 + (lane & 31) + 32]);
   }
