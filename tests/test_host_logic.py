@@ -153,5 +153,11 @@ def test_gemm_split_plan_and_launch_geometry_agree(lib):
     assert lib.plan_gemm_splits(1024, 6144, 4096)[0] == 2
     # a matrix with more blocks than compute units is not split at all
     assert lib.plan_gemm_splits(1024, 28672, 4096)[0] == 1
+    # a single row block streams every weight tile once: its splits leave an eighth of the 256 compute units free
+    # (the 70B-sized stage's 256-row GEMMs), while several row blocks, which share tiles, may fill the chip
+    for n_cols, k in ((8192, 8192), (8192, 28672), (10240, 8192)):
+        splits = lib.plan_gemm_splits(256, n_cols, k)[0]
+        assert 1 < splits and (n_cols // 256) * splits <= 224, (n_cols, k, splits)
+    assert lib.plan_gemm_splits(1024, 4096, 4096)[0] * 4 * (4096 // 256) == 256
     with pytest.raises(lib.PipemaxError):
         lib.plan_gemm_splits(256, 300, 4096)
