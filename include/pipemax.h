@@ -81,7 +81,7 @@ enum {
                                        the other launches' event records do not perturb it       */
   PIPEMAX_FLAG_STREAM_ORDERED_EVICT = 32  /* order a prefetch after the last reader of the pages it
                                        re-uses with a stream-side event wait instead of the default
-                                       host-side wait inside pipemax_prefetch_kv (see there)      */
+                                       host-side wait of the prefetch worker (see pipemax_prefetch_kv) */
 };
 
 typedef struct {
@@ -167,6 +167,21 @@ int pipemax_set_weight(pipemax_stage_t* st, int layer, int which, const void* ho
  * All sequences start HOST-resident.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED.                */
 int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ctx_lens);
 
+/* Measurement aid for hosts that cannot pin the KV of a whole configuration (a process here pins at most
+ * about 64 GiB; the 70B-shaped configurations need 172 and 344 GB): defines micro-batch `mb` (not yet
+ * defined) as an ALIAS of the defined, non-alias micro-batch `src_mb`.  The alias has as many sequences,
+ * with the lengths src_mb's have now, and its block tables name the SAME host pages (reserved growth pages
+ * included); nothing is taken from the host pool.  GPU pages, prefetch, decode and evict work as for any
+ * micro-batch, so its transfers move the same bytes along the same access pattern and its steps run the same
+ * kernels.  Its write-back lands in the shared pages: once an alias has decoded, the tokens appended to the
+ * alias AND to its source are unspecified in the host replica (whichever wrote last), while every token that
+ * existed when the alias was defined stays intact as long as both advance by the same number of steps.
+ * For timing only: parity is checked on micro-batches that are neither aliases nor sources of a stepped alias.
+ * pipemax_kv_host_write on an alias fails with ERR_STATE.  Errors: ERR_ARG.                                  */
+int pipemax_mb_define_alias(pipemax_stage_t* st, int mb, int src_mb);
+/* *src_mb (host pointer) receives the micro-batch `mb` is an alias of, or -1.                              */
+int pipemax_mb_alias_of(pipemax_stage_t* st, int mb, int32_t* src_mb);
+
 /* Writes / reads tokens [tok0, tok0+ntok) of one layer of one sequence in the HOST replica.
  * K and V are host pointers, canonical layout [ntok][Hkv][d].  Both calls first wait until
  * all pending write-back of that micro-batch has landed.  Range must lie within the
@@ -183,18 +198,20 @@ int pipemax_kv_dev_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok
 
 /* ---- the hot path ---------------------------------------------------------------------- */
 
-/* Prefetch (Sec. 3.3.2, "prefetching KV cache from CPU memory to update D_j"; Sec. 3.4.2,
- * block-first layout): for every named sequence of `mb` that is HOST-resident, allocates GPU
- * pages (lowest free index first) and enqueues host->device copies of its pages on the
+/* Prefetch (Sec. 3.3.2: the KV cache of the next batch D_j is brought from CPU memory while D_i
+ * executes; Sec. 3.4.2, block-first layout): for every named sequence of `mb` that is HOST-resident,
+ * allocates GPU pages (lowest free index first) and arranges host->device copies of its pages on the
  * library's prefetch stream, adjacent (host, GPU) page pairs merged into single copies.
  * seq_ids: host pointer to n sequence indices, or NULL for all sequences of mb.  Sequences that
- * already have GPU pages are skipped.  Waits on the host for pending write-back of `mb`
- * (so that the host replica is complete) and, on the stream, for the last reader of any page
- * it re-uses.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED (nothing applied), ERR_HIP.
- * By default the wait for the last reader of re-used pages is taken on the host (the call blocks
- * until the decode step that last read the evicted pages has finished): a copy stream that waits on
- * a not-yet-signalled event of another stream was measured to leave gaps of 150-350 us between its
- * copies on this platform.  PIPEMAX_FLAG_STREAM_ORDERED_EVICT selects the stream-side wait.       */
+ * already have GPU pages are skipped.  Errors: ERR_ARG, ERR_POOL_EXHAUSTED (nothing applied), ERR_HIP
+ * (also when an earlier prefetch failed after its call had returned).
+ * The call does the bookkeeping and returns at once.  A worker thread of the stage issues the copies
+ * as soon as (1) the write-back of `mb` that was pending at the time of the call has landed in the
+ * host replica and (2) the decode steps that last read the pages being re-used (those of the
+ * micro-batches evicted since the previous prefetch) have finished.  (2) is a host-side wait in that
+ * thread: a copy stream that waits on a not-yet-signalled event of another stream was measured to
+ * leave gaps of 150-350 us between its copies on this platform.  PIPEMAX_FLAG_STREAM_ORDERED_EVICT
+ * selects the stream-side wait instead.  A decode step of `mb` is ordered after the copies.        */
 int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n);
 
 /* One decode step of the stage on micro-batch `mb` (the op list of the benchmark spec; cost
@@ -239,8 +256,8 @@ int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids
 int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const void* hidden_in,
                     void* hidden_out, void* hip_stream);
 
-/* Evict (Sec. 3.3.2, "overwriting KV cache blocks associated with the inactive batch D_k"):
- * releases the GPU pages of the named sequences (NULL = all of mb).  No bulk copy is made: the
+/* Evict (Sec. 3.3.2: the GPU blocks of the batch D_k that has just executed are the ones a prefetch
+ * may overwrite): releases the GPU pages of the named sequences (NULL = all of mb).  No bulk copy is made: the
  * host replica is kept current by the per-layer write-back.  Later prefetches into the freed
  * pages are ordered after the last decode step that read them.  Returns without blocking.  */
 int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n);

@@ -50,6 +50,7 @@ HOST, INFLIGHT, GPU = 0, 1, 2
 # every symbol include/pipemax.h declares
 SYMBOLS = [
     "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
+    "pipemax_mb_define_alias", "pipemax_mb_alias_of",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
     "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_config", "pipemax_mb_size",
@@ -176,6 +177,8 @@ _sig = {
     "pipemax_stage_destroy": (C.c_int, [_vp]),
     "pipemax_set_weight": (C.c_int, [_vp, C.c_int, C.c_int, _vp, C.c_size_t]),
     "pipemax_mb_define": (C.c_int, [_vp, C.c_int, C.c_int, _i32p]),
+    "pipemax_mb_define_alias": (C.c_int, [_vp, C.c_int, C.c_int]),
+    "pipemax_mb_alias_of": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_kv_host_write": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
     "pipemax_kv_host_read": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
     "pipemax_kv_dev_read": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
@@ -277,6 +280,15 @@ class Stage:
         a = np.ascontiguousarray(ctx_lens, dtype=np.int32)
         _check(_lib.pipemax_mb_define(self._h, mb, int(a.size), a.ctypes.data_as(_i32p)))
         self._nseq[mb] = int(a.size)
+
+    def mb_define_alias(self, mb: int, src_mb: int):
+        _check(_lib.pipemax_mb_define_alias(self._h, mb, src_mb))
+        self._nseq[mb] = self._nseq[src_mb]
+
+    def mb_alias_of(self, mb: int) -> int:
+        out = C.c_int32(0)
+        _check(_lib.pipemax_mb_alias_of(self._h, mb, C.byref(out)))
+        return int(out.value)
 
     def kv_host_write(self, mb, seq, layer, tok0, K: np.ndarray, V: np.ndarray):
         K = np.ascontiguousarray(K, dtype=self.np_dtype)

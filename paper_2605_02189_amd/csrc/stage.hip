@@ -7,10 +7,13 @@
 //     of a layer (or of the last layer of a group) an event is recorded; the worker thread waits for it,
 //     issues the d2h copy of the contiguous staging rows to pinned host memory, waits for the copy and
 //     scatters the rows into the host pages.
-//   prefetch(mb):   host waits until mb's pending write-back has landed in the host replica, then
-//     page runs are copied on h2d, which is ordered (see evict) after the last reader of any page
-//     it overwrites.
-//   evict(mb):      h2d waits for mb's last step event; the GPU pages go back to the free list.
+//   prefetch(mb):   the caller's thread does the bookkeeping (GPU pages, copy runs) and returns; a second
+//     worker thread waits until mb's pending write-back has landed in the host replica and until the
+//     last reader of every page about to be overwritten has finished (see evict), then issues the page
+//     runs on h2d and records mb's prefetch event.  A decode step of mb waits (host side) for that issue
+//     before it makes its stream wait for the event.
+//   evict(mb):      the GPU pages go back to the free list; the next prefetch is ordered after mb's
+//     last step event.
 #include <algorithm>
 #include <atomic>
 #include <chrono>
@@ -64,6 +67,7 @@ struct SeqState {
 
 struct MicroBatch {
   bool defined = false;
+  int alias_of = -1;    // >= 0: shares the host pages of that micro-batch (timing aid, see pipemax_mb_define_alias)
   int b = 0;
   std::vector<SeqState> seq;
   int* d_ctx = nullptr;
@@ -76,6 +80,8 @@ struct MicroBatch {
   hipEvent_t ev_step = nullptr;
   bool stepped = false;
   int wb_pending = 0;   // guarded by Stage::mu
+  uint64_t wb_queued = 0, wb_done = 0;   // write-back jobs of this micro-batch ever queued / finished (guarded by mu)
+  uint64_t pf_ticket = 0;   // number of the last prefetch job of this micro-batch
 };
 
 struct WbJob {
@@ -93,6 +99,18 @@ struct WbJob {
 struct Timed {
   int cls;
   hipEvent_t a, b;
+};
+
+// One prefetch_kv call, handed to the prefetch worker: the copies and what they must wait for.
+struct PfJob {
+  uint64_t no = 0;                 // running number of the job (MicroBatch::pf_ticket)
+  int mb = 0;
+  std::vector<CopyRun> runs;
+  std::vector<int> release;        // micro-batches evicted since the last prefetch: their last step read the pages
+  uint64_t wb_target = 0;          // write-back jobs of mb that must have landed in the host replica first
+  bool stream_ordered = false;     // wait for the last readers on the stream instead of on the host
+  bool timed = false;
+  bool stop = false;
 };
 
 struct LayerW {
@@ -167,6 +185,15 @@ struct pipemax_stage {
   std::condition_variable cv_job, cv_done;
   std::deque<WbJob> jobs;
   bool worker_started = false;
+  // prefetch worker: issues the copies of prefetch_kv once their conditions hold
+  std::thread pf_worker;
+  std::condition_variable cv_pf, cv_pf_done;
+  std::deque<PfJob> pf_jobs;            // guarded by mu
+  uint64_t pf_queued = 0, pf_issued = 0;   // jobs handed over / issued on the stream (guarded by mu)
+  int pf_error = 0;                     // guarded by mu: status of the first failing job
+  char pf_error_text[256] = "";
+  std::vector<Timed> pf_timed;          // guarded by mu: event pairs the prefetch worker recorded
+  std::vector<hipEvent_t> pf_ev_free;   // guarded by mu
   // test hooks
   std::atomic<int> dly_h2d{0}, dly_d2h{0}, dly_worker{0};
   int worker_hip_error = 0;        // guarded by mu: first failure of a copy the worker issued
@@ -218,7 +245,26 @@ struct pipemax_stage {
   }
   // only_ready: keep the pairs whose second event has not completed yet
   void resolve_timers(bool only_ready = false) {
-    std::vector<Timed> keep;
+    std::vector<Timed> keep, from_pf, back_pf;
+    {
+      std::lock_guard<std::mutex> lk(mu);
+      from_pf.swap(pf_timed);
+    }
+    for (auto& t : from_pf) {          // pairs of the prefetch worker; their events go back to its own free list
+      float ms = 0.f;
+      if (hipEventQuery(t.b) != hipSuccess) {
+        back_pf.push_back(t);
+        continue;
+      }
+      if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) st.h2d_ms += ms;
+      std::lock_guard<std::mutex> lk(mu);
+      pf_ev_free.push_back(t.a);
+      pf_ev_free.push_back(t.b);
+    }
+    if (!back_pf.empty()) {
+      std::lock_guard<std::mutex> lk(mu);
+      pf_timed.insert(pf_timed.begin(), back_pf.begin(), back_pf.end());
+    }
     for (auto& t : timed) {
       float ms = 0.f;
       if (only_ready && hipEventQuery(t.b) != hipSuccess) {
@@ -247,6 +293,14 @@ struct pipemax_stage {
     if (mbs[mb].wb_pending == 0) return;
     double t0 = now_s();
     cv_done.wait(lk, [&] { return mbs[mb].wb_pending == 0; });
+    st.host_wait_s += now_s() - t0;
+  }
+  // blocks until the prefetch worker has issued job `no` (0 = nothing to wait for)
+  void wait_pf(uint64_t no) {
+    std::unique_lock<std::mutex> lk(mu);
+    if (pf_issued >= no) return;
+    double t0 = now_s();
+    cv_pf_done.wait(lk, [&] { return pf_issued >= no; });
     st.host_wait_s += now_s() - t0;
   }
   void wait_slot(int slot) {
@@ -409,6 +463,7 @@ void worker_main(pipemax_stage* st) {
     {
       std::lock_guard<std::mutex> lk(st->mu);
       st->mbs[job.mb].wb_pending -= 1;
+      st->mbs[job.mb].wb_done += 1;
       st->slot_pending[job.slot] -= 1;
       st->st.relayout_jobs += job.n_layers;
     }
@@ -418,6 +473,83 @@ void worker_main(pipemax_stage* st) {
 
 void host_sleep_cb(void* arg) {
   std::this_thread::sleep_for(std::chrono::microseconds((intptr_t)arg));
+}
+
+// The prefetch worker.  A job's copies may start once (1) the write-back of its micro-batch that was pending when
+// prefetch_kv was called has landed in the host replica and (2) the last decode step of every micro-batch evicted
+// since the previous prefetch has finished reading the pages that are handed out again.  Both waits used to be
+// taken by the caller inside prefetch_kv, which kept it from enqueuing the next decode step meanwhile.
+void pf_worker_main(pipemax_stage* st) {
+  (void)hipSetDevice(st->dev);
+  for (;;) {
+    PfJob job;
+    {
+      std::unique_lock<std::mutex> lk(st->mu);
+      st->cv_pf.wait(lk, [&] { return !st->pf_jobs.empty(); });
+      job = std::move(st->pf_jobs.front());
+      st->pf_jobs.pop_front();
+      if (job.stop) return;
+      st->cv_done.wait(lk, [&] { return st->mbs[job.mb].wb_done >= job.wb_target; });
+    }
+    MicroBatch& M = st->mbs[job.mb];
+    int status = PIPEMAX_OK;
+    char text[256] = "";
+    auto fail_hip = [&](hipError_t e, const char* what) {
+      if (e == hipSuccess || status != PIPEMAX_OK) return;
+      status = PIPEMAX_ERR_HIP;
+      snprintf(text, sizeof(text), "prefetch worker: %s failed: %s", what, hipGetErrorString(e));
+    };
+    for (int k : job.release) {
+      if (job.stream_ordered) fail_hip(hipStreamWaitEvent(st->s_h2d, st->mbs[k].ev_step, 0), "hipStreamWaitEvent");
+      else fail_hip(hipEventSynchronize(st->mbs[k].ev_step), "hipEventSynchronize");
+    }
+    if (int us = st->dly_h2d.load())
+      fail_hip(hipLaunchHostFunc(st->s_h2d, host_sleep_cb, (void*)(intptr_t)us), "hipLaunchHostFunc");
+    uint64_t ticket = 0;
+    if (st->xfer) {
+      // the orchestrator cuts the runs into chunks and feeds them to the link behind any urgent copy; bulk
+      // requests of one direction complete in order, so the last ticket stands for the whole prefetch
+      for (const CopyRun& r : job.runs) {
+        if (status != PIPEMAX_OK) break;
+        int rc = pipemax_xfer_submit(st->xfer, PIPEMAX_XFER_BULK, PIPEMAX_XFER_H2D, st->gpu_page_ptr(r.dst),
+                                     st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes, &ticket);
+        if (rc != PIPEMAX_OK) {
+          status = rc;
+          snprintf(text, sizeof(text), "prefetch worker: the transfer orchestrator refused a copy (%d)", rc);
+        }
+      }
+    } else {
+      Timed t{TC_H2D, nullptr, nullptr};
+      if (job.timed) {
+        std::lock_guard<std::mutex> lk(st->mu);
+        if (st->pf_ev_free.size() >= 2) {
+          t.a = st->pf_ev_free.back(); st->pf_ev_free.pop_back();
+          t.b = st->pf_ev_free.back(); st->pf_ev_free.pop_back();
+        }
+      }
+      if (job.timed && !t.a && (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess)) t.a = t.b = nullptr;
+      if (t.a) fail_hip(hipEventRecord(t.a, st->s_h2d), "hipEventRecord");
+      for (const CopyRun& r : job.runs)
+        fail_hip(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
+                                hipMemcpyHostToDevice, st->s_h2d), "hipMemcpyAsync");
+      if (t.a) {
+        fail_hip(hipEventRecord(t.b, st->s_h2d), "hipEventRecord");
+        std::lock_guard<std::mutex> lk(st->mu);
+        st->pf_timed.push_back(t);
+      }
+      fail_hip(hipEventRecord(M.ev_prefetch, st->s_h2d), "hipEventRecord");
+    }
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      M.prefetch_ticket = ticket;
+      st->pf_issued = job.no;
+      if (status != PIPEMAX_OK && st->pf_error == PIPEMAX_OK) {
+        st->pf_error = status;
+        snprintf(st->pf_error_text, sizeof(st->pf_error_text), "%s", text);
+      }
+    }
+    st->cv_pf_done.notify_all();
+  }
 }
 
 template <typename T>
@@ -533,11 +665,24 @@ void destroy_impl(pipemax_stage* st) {
     }
     st->cv_job.notify_all();
     st->worker.join();
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      PfJob stop;
+      stop.stop = true;
+      st->pf_jobs.push_back(stop);
+    }
+    st->cv_pf.notify_all();
+    st->pf_worker.join();
     dma_copy_destroy(st->dma);
     st->dma = nullptr;
   }
   (void)hipDeviceSynchronize();
   st->timed.clear();
+  for (auto& t : st->pf_timed) {
+    (void)hipEventDestroy(t.a);
+    (void)hipEventDestroy(t.b);
+  }
+  for (auto e : st->pf_ev_free) (void)hipEventDestroy(e);
   for (auto e : st->ev_free) (void)hipEventDestroy(e);
   for (auto& mb : st->mbs) {
     if (mb.ev_prefetch) (void)hipEventDestroy(mb.ev_prefetch);
@@ -819,6 +964,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   if (const char* e = getenv("PIPEMAX_ATTN_CHUNK_PAGES")) st->attn_cp_override = atoi(e);
   st->dma = dma_copy_create(st->d_stage[0], st->h_stage[0]);
   st->worker = std::thread(worker_main, st);
+  st->pf_worker = std::thread(pf_worker_main, st);
   st->worker_started = true;
   st->st.engine = st->engine;
   *out = st;
@@ -932,11 +1078,45 @@ int pipemax_mb_define(pipemax_stage_t* st, int mb, int n_seqs, const int32_t* ct
   return PIPEMAX_OK;
 }
 
+int pipemax_mb_define_alias(pipemax_stage_t* st, int mb, int src_mb) {
+  int rc = check_mb(st, mb, false);
+  if (rc) return rc;
+  rc = check_mb(st, src_mb, true);
+  if (rc) return rc;
+  MicroBatch& M = st->mbs[mb];
+  const MicroBatch& S = st->mbs[src_mb];
+  if (M.defined) PMX_FAIL(PIPEMAX_ERR_ARG, "micro-batch %d is already defined", mb);
+  if (S.alias_of >= 0) PMX_FAIL(PIPEMAX_ERR_ARG, "micro-batch %d is itself an alias", src_mb);
+  st->wait_mb_writeback(src_mb);
+  M.seq.assign(S.b, SeqState());
+  for (int i = 0; i < S.b; ++i) {
+    M.seq[i].len = S.seq[i].len;
+    M.seq[i].state = ST_HOST;
+    M.seq[i].host = S.seq[i].host;                     // the same page ids: nothing is taken from the pool
+    M.seq[i].host_reserved = S.seq[i].host_reserved;   // growth lands in the source's reserved pages as well
+  }
+  M.b = S.b;
+  M.alias_of = src_mb;
+  M.defined = true;
+  M.table_dirty = true;
+  return PIPEMAX_OK;
+}
+
+int pipemax_mb_alias_of(pipemax_stage_t* st, int mb, int32_t* src_mb) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  if (!src_mb) PMX_FAIL(PIPEMAX_ERR_ARG, "null argument");
+  *src_mb = st->mbs[mb].alias_of;
+  return PIPEMAX_OK;
+}
+
 int pipemax_kv_host_write(pipemax_stage_t* st, int mb, int seq, int layer, int tok0, int ntok,
                           const void* K, const void* V) {
   int rc = kv_rw_check(st, mb, seq, layer, tok0, ntok);
   if (rc) return rc;
   if (!K || !V) PMX_FAIL(PIPEMAX_ERR_ARG, "null K/V");
+  if (st->mbs[mb].alias_of >= 0)
+    PMX_FAIL(PIPEMAX_ERR_STATE, "micro-batch %d is an alias: it has no host pages of its own to write", mb);
   SeqState& S = st->mbs[mb].seq[seq];
   if (S.state != ST_HOST) PMX_FAIL(PIPEMAX_ERR_STATE, "kv_host_write needs a HOST-resident sequence");
   st->wait_mb_writeback(mb);
@@ -1024,13 +1204,12 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
   if (need > st->gpu_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "GPU pool has %d free pages, %lld needed", st->gpu_pages->free_count(),
              (long long)need);
-  PMX_HIP(hipSetDevice(st->dev));
-  st->wait_mb_writeback(mb);     // the host replica of mb must be complete before it is read
-  if (!st->release_wait.empty()) {     // the pages freed by earlier evictions are no longer being read
-    const double t0 = now_s();
-    for (int k : st->release_wait) PMX_HIP(hipEventSynchronize(st->mbs[k].ev_step));
-    st->release_wait.clear();
-    st->st.host_wait_s += now_s() - t0;
+  {
+    std::lock_guard<std::mutex> lk(st->mu);
+    if (st->pf_error != PIPEMAX_OK) {
+      set_error("%s", st->pf_error_text);
+      return st->pf_error;
+    }
   }
   std::vector<int32_t> src, dst;
   src.reserve(need);
@@ -1044,33 +1223,26 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
     dst.insert(dst.end(), S.gpu.begin(), S.gpu.end());
   }
   M.table_dirty = true;
-  std::vector<CopyRun> runs;
-  plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, runs);
-  if (int us = st->dly_h2d.load()) PMX_HIP(hipLaunchHostFunc(st->s_h2d, host_sleep_cb, (void*)(intptr_t)us));
-  if (st->xfer) {
-    // the orchestrator cuts the runs into chunks and feeds them to the link behind any urgent copy; bulk
-    // requests of one direction complete in order, so the last ticket stands for the whole prefetch
-    for (const CopyRun& r : runs) {
-      rc = pipemax_xfer_submit(st->xfer, PIPEMAX_XFER_BULK, PIPEMAX_XFER_H2D, st->gpu_page_ptr(r.dst),
-                               st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes, &M.prefetch_ticket);
-      if (rc) return rc;
-      st->st.h2d_bytes += (uint64_t)r.count * st->page_bytes;
-      st->st.h2d_copies += 1;
-    }
-    M.prefetch_pending = true;
-    return PIPEMAX_OK;
-  }
-  st->tbegin(TC_H2D, st->s_h2d);
-  for (const CopyRun& r : runs) {
-    PMX_HIP(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
-                           hipMemcpyHostToDevice, st->s_h2d));
+  PfJob job;
+  job.mb = mb;
+  plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, job.runs);
+  for (const CopyRun& r : job.runs) {
     st->st.h2d_bytes += (uint64_t)r.count * st->page_bytes;
     st->st.h2d_copies += 1;
   }
-  st->tend(st->s_h2d);
-  PMX_HIP(hipEventRecord(M.ev_prefetch, st->s_h2d));
+  // the pages freed by earlier evictions may still be read by the evicted micro-batches' last steps
+  job.release.swap(st->release_wait);
+  job.stream_ordered = (st->cfg.flags & PIPEMAX_FLAG_STREAM_ORDERED_EVICT) && !st->xfer;
+  job.timed = st->timing();
+  {
+    std::lock_guard<std::mutex> lk(st->mu);
+    job.no = ++st->pf_queued;
+    job.wb_target = M.wb_queued;     // the host replica of mb must be complete before it is read
+    M.pf_ticket = job.no;
+    st->pf_jobs.push_back(std::move(job));
+  }
+  st->cv_pf.notify_one();
   M.prefetch_pending = true;
-  M.prefetch_ticket = 0;
   return PIPEMAX_OK;
 }
 
@@ -1089,13 +1261,11 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
     }
   if (!any) return PIPEMAX_OK;
   PMX_HIP(hipSetDevice(st->dev));
-  // later prefetches into these pages must come after the last step that read them
-  if (M.stepped) {
-    if ((st->cfg.flags & PIPEMAX_FLAG_STREAM_ORDERED_EVICT) && !st->xfer)
-      PMX_HIP(hipStreamWaitEvent(st->s_h2d, M.ev_step, 0));
-    else st->release_wait.push_back(mb);
-  }
+  // later prefetches into these pages must come after the last step that read them (the prefetch worker waits)
+  if (M.stepped && std::find(st->release_wait.begin(), st->release_wait.end(), mb) == st->release_wait.end())
+    st->release_wait.push_back(mb);
   // pages of a cancelled prefetch may be handed to a decode step's growth: fence the compute stream
+  if (any_inflight) st->wait_pf(M.pf_ticket);     // its copies are on the stream (or with the orchestrator)
   if (any_inflight && st->xfer && M.prefetch_ticket) {
     rc = pipemax_xfer_wait(st->xfer, M.prefetch_ticket);     // the copies into these pages have landed
     if (rc) return rc;
@@ -1182,6 +1352,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
 
   // ---- stream dependencies -----------------------------------------------------------------------
   if (M.prefetch_pending) {
+    st->wait_pf(M.pf_ticket);      // the event below exists only once the worker has issued the copies
     if (st->xfer && M.prefetch_ticket) {
       rc = pipemax_xfer_stream_wait(st->xfer, M.prefetch_ticket, cs);
       if (rc) return rc;
@@ -1258,6 +1429,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     {
       std::lock_guard<std::mutex> lk(st->mu);
       M.wb_pending += 1;
+      M.wb_queued += 1;
       st->slot_pending[slot] += 1;
       st->jobs.push_back(job);
     }
@@ -1544,6 +1716,14 @@ int pipemax_prefill(pipemax_stage_t* st, int mb, int seq, int n_tokens, const vo
 int pipemax_sync(pipemax_stage_t* st) {
   if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
   PMX_HIP(hipSetDevice(st->dev));
+  {
+    uint64_t last;
+    {
+      std::lock_guard<std::mutex> lk(st->mu);
+      last = st->pf_queued;
+    }
+    st->wait_pf(last);
+  }
   if (st->xfer) {
     int rcx = pipemax_xfer_drain(st->xfer);
     if (rcx) return rcx;
@@ -1557,6 +1737,10 @@ int pipemax_sync(pipemax_stage_t* st) {
     std::lock_guard<std::mutex> lk(st->mu);
     if (st->worker_hip_error)
       PMX_FAIL(PIPEMAX_ERR_HIP, "a write-back copy failed: %s", hipGetErrorString((hipError_t)st->worker_hip_error));
+    if (st->pf_error != PIPEMAX_OK) {
+      set_error("%s", st->pf_error_text);
+      return st->pf_error;
+    }
   }
   for (auto& M : st->mbs) {
     if (!M.defined) continue;

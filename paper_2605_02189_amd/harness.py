@@ -27,30 +27,44 @@ class StageRunner:
                  flags: int = 0, device: int = 0, n_microbatches: int | None = None,
                  ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False,
                  wb_layers_per_copy: int = 0, reserve: bool = True, gpu_pages: int | None = None,
-                 max_rows: int | None = None):
+                 max_rows: int | None = None, real_microbatches: int | None = None,
+                 gpu_resident_microbatches: int | None = None):
+        """real_microbatches = r < n: only micro-batches 0..r-1 get host pages and KV of their own; micro-batch
+        m >= r is an alias of m mod r (same lengths, same host pages; hosts that cannot pin the whole
+        configuration; timing only).  gpu_resident_microbatches: size the GPU pool for that many whole
+        micro-batches (compute-only legs of configurations whose KV exceeds the HBM)."""
         self.shape, self.syn = shape, syn
         pool_override = gpu_pages
         self.n = n_microbatches or shape.n_microbatches
+        self.n_real = min(self.n, real_microbatches or self.n)
         self.b = shape.seqs_per_mb
         self.steps = steps if steps is not None else shape.decode_steps
         self.device = device
         self.ctx0 = {mb: np.asarray(ctx_lens[mb] if ctx_lens else syn.ctx_lens(mb), dtype=np.int32)
-                     for mb in range(self.n)}
+                     for mb in range(self.n_real)}
+        for mb in range(self.n_real, self.n):
+            self.ctx0[mb] = self.ctx0[mb % self.n_real]
         self.b_of = {mb: len(self.ctx0[mb]) for mb in range(self.n)}
         steps_per_mb = -(-self.steps // self.n)
         grow = pages_for(steps_per_mb) + 1
         self._set_sigma(sigma)
         full = {mb: [pages_for(l) + grow for l in self.ctx0[mb]] for mb in range(self.n)}
-        host_pages = sum(sum(v) for v in full.values())
+        host_pages = sum(sum(full[mb]) for mb in range(self.n_real))
+        all_pages = sum(sum(v) for v in full.values())
         resident_pages = sum(sum(full[mb][: self.b_of[mb] - self.n_stream[mb]]) for mb in range(self.n))
         stream_pages = sorted((sum(full[mb][self.b_of[mb] - self.n_stream[mb]:]) for mb in range(self.n)),
                               reverse=True)
         gpu_pages = resident_pages + sum(stream_pages[:2]) + 8          # two arenas for the streamed part
         if gpu_pool_all_resident:                                       # room to keep everything on the GPU
-            gpu_pages = host_pages + 8
+            gpu_pages = all_pages + 8
+        if gpu_resident_microbatches is not None:
+            gpu_pages = max(gpu_pages, sum(sorted((sum(v) for v in full.values()), reverse=True)
+                                           [:gpu_resident_microbatches]) + 8)
         if pool_override is not None:                                   # caller-chosen GPU pool (scheduler runs)
             gpu_pages = int(pool_override)
         max_ctx = int(max(int(c.max()) for c in self.ctx0.values())) + steps_per_mb + 1
+        self.max_ctx = max_ctx
+        self.reserve_tokens = (steps_per_mb + 1) if reserve else 0
         self.stage = pm.Stage(
             n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
             n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
@@ -58,7 +72,7 @@ class StageRunner:
             dtype=pm.F32 if shape.dtype == "fp32" else pm.BF16, n_microbatches=self.n,
             max_seqs_per_mb=max(max(self.b_of.values()), max_rows or 0), max_ctx=max_ctx,
             gpu_kv_bytes=gpu_pages * shape.page_bytes, host_kv_bytes=(host_pages + 8) * shape.page_bytes,
-            device=device, flags=flags, host_reserve_tokens=(steps_per_mb + 1) if reserve else 0,
+            device=device, flags=flags, host_reserve_tokens=self.reserve_tokens,
             wb_layers_per_copy=wb_layers_per_copy)
         self.torch_dtype = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
         self.t = 0
@@ -92,7 +106,7 @@ class StageRunner:
             self.stage.set_weight(l, pm.G_FFN, w["g2"])
 
     def load_kv(self):
-        for mb in range(self.n):
+        for mb in range(self.n_real):
             self.stage.mb_define(mb, self.ctx0[mb])
             for s, L in enumerate(self.ctx0[mb]):
                 if L == 0:
@@ -100,6 +114,8 @@ class StageRunner:
                 for l in range(self.shape.n_layers):
                     K, V = self.syn.kv_prefix(mb, s, l, int(L))
                     self.stage.kv_host_write(mb, s, l, 0, K, V)
+        for mb in range(self.n_real, self.n):
+            self.stage.mb_define_alias(mb, mb % self.n_real)
 
     def load(self):
         self.load_weights()
@@ -129,18 +145,20 @@ class StageRunner:
 
     def step(self, hidden_in: torch.Tensor | None, hidden_out: torch.Tensor | None,
              stream: torch.cuda.Stream | None = None, transfers: bool = True, compute: bool = True):
-        """Iteration t of the cyclic schedule: overwrite D_k, prefetch D_j, execute D_i (Eq. 3).
+        """Iteration t of the cyclic schedule: execute D_i, overwrite D_k, prefetch D_j (Eq. 3).  The step is
+        enqueued first, so that the GPU already has it while the host arranges the iteration's transfers
+        (none of the three calls blocks on the GPU).
         transfers=False keeps everything where it is (all micro-batches must be resident);
         compute=False issues only the evict / prefetch traffic of the iteration."""
         n, t = self.n, self.t
         i, j, k = t % n, (t + 1) % n, (t - 1) % n
+        if compute:
+            sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+            self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         if transfers:
             if t > 0 and self.n_stream[k] and k != i and k != j:
                 self.stage.evict_kv(k, self.stream_ids[k])
             if j != i and self.n_stream[j]:
                 self.stage.prefetch_kv(j, self.stream_ids[j])
-        if compute:
-            sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
-            self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         self.t += 1
         return i

@@ -14,12 +14,12 @@ def _shape(dtype):
     return StageShape("hz", 2, 512, 8, 2, 128, 1024, "bf16", 500000.0, 4, 6, 5, 90, 12)
 
 
-def _run(shape, delays=None, canary=False, wb=0):
+def _run(shape, delays=None, canary=False, wb=0, flags=0):
     import torch
     from paper_2605_02189_amd.harness import StageRunner
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     syn = SynthInputs(shape, seed=21, pool_elems=1 << 22, gain_jitter=0.1)
-    run = StageRunner(shape, syn, wb_layers_per_copy=wb).load()
+    run = StageRunner(shape, syn, wb_layers_per_copy=wb, flags=flags).load()
     st = run.stage
     if delays:
         st.debug_set_delays(*delays)
@@ -75,6 +75,26 @@ def test_nan_canary_in_free_pages_never_reaches_the_output(dtype):
     for (Ka, Va), (Kb, Vb) in zip(rep, base_rep):
         np.testing.assert_array_equal(Ka, Kb)
         np.testing.assert_array_equal(Va, Vb)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_stream_ordered_evict_gives_the_same_results(dtype):
+    """PIPEMAX_FLAG_STREAM_ORDERED_EVICT: the prefetch stream itself waits for the last reader of the pages it
+    overwrites instead of the prefetch worker waiting on the host.  Same outputs and replica, also with every
+    side path delayed and with the free pages poisoned (a copy that overtook its last reader, or a step that
+    overtook its copy, would read the canary or stale bytes)."""
+    from paper_2605_02189_amd import binding as pm
+    shape = _shape(dtype)
+    base_out, base_rep, _ = _run(shape)
+    for delays, canary in ((None, False), ((6000, 3000, 3000), False), ((0, 0, 0), True), ((20000, 0, 0), True)):
+        print("stream-ordered evict: delays", delays, "canary", canary, flush=True)
+        out, rep, stats = _run(shape, delays=delays, canary=canary, flags=pm.FLAG_STREAM_ORDERED_EVICT)
+        for t, (a, b) in enumerate(zip(out, base_out)):
+            np.testing.assert_array_equal(a, b, err_msg=f"step {t} differs (delays {delays}, canary {canary})")
+        for (Ka, Va), (Kb, Vb) in zip(rep, base_rep):
+            np.testing.assert_array_equal(Ka, Kb)
+            np.testing.assert_array_equal(Va, Vb)
+        assert stats["steps"] == shape.decode_steps
 
 
 def test_write_back_through_the_runtime_copy_equals_the_dma_engine_path(monkeypatch):

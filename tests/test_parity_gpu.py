@@ -4,7 +4,7 @@ seeded inputs.  Bars: bit-exact for KV paging / indexing / bookkeeping; relative
 import numpy as np
 import pytest
 
-from conftest import rel_l2
+from conftest import max_row_rel_l2, rel_l2
 from helpers import check_tables, make_oracle
 
 pytestmark = pytest.mark.gpu
@@ -29,7 +29,7 @@ def _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer, tol_delta, ora
     from paper_2605_02189_amd import binding as pm
     orc = make_oracle(shape, syn, runner.ctx0, oracle_seqs)
     runner.warm_start()
-    worst_layer = worst_delta = 0.0
+    worst_layer = worst_delta = worst_row = worst_row_delta = 0.0
     for t in range(steps):
         mb = t % runner.n
         b = runner.b_of[mb]
@@ -46,20 +46,28 @@ def _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer, tol_delta, ora
         for l in range(shape.n_layers):
             e = rel_l2(got_layers[l], ref_layers[l])
             d = rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref)
+            # the same two bars for every row on its own: a single wrong row (a tile edge) must not hide in the batch
+            er = max_row_rel_l2(got_layers[l], ref_layers[l])
+            dr = max_row_rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref)
             worst_layer, worst_delta = max(worst_layer, e), max(worst_delta, d)
+            worst_row, worst_row_delta = max(worst_row, er), max(worst_row_delta, dr)
             assert e <= tol_layer, f"step {t} layer {l}: rel L2 {e:.3e} > {tol_layer}"
             assert d <= tol_delta, f"step {t} layer {l}: rel L2 of the layer's update {d:.3e} > {tol_delta}"
+            assert er <= tol_layer, f"step {t} layer {l}: worst row rel L2 {er:.3e} > {tol_layer}"
+            assert dr <= tol_delta, f"step {t} layer {l}: worst row rel L2 of the layer's update {dr:.3e} > {tol_delta}"
             prev_ref, prev_got = ref_layers[l], got_layers[l]
         # the stage output is the last layer's residual stream in the stage's element type
         out_tol = tol_layer if shape.dtype == "fp32" else max(tol_layer, 8e-3)
         assert rel_l2(got_out, ref_out) <= out_tol
+        assert max_row_rel_l2(got_out, ref_out) <= out_tol
         # bookkeeping after the step
         lens = runner.stage.get_ctx_lens(mb)
         assert lens.tolist() == [orc.ctx_len(mb, s) if (not oracle_seqs or s in seqs) else lens[s]
                                  for s in range(b)]
         res = runner.stage.get_residency(mb)
         assert np.all(res == pm.GPU)
-    print(f"worst rel L2: layer output {worst_layer:.3e}, layer update {worst_delta:.3e}", flush=True)
+    print(f"worst rel L2: layer output {worst_layer:.3e} (single row {worst_row:.3e}), layer update "
+          f"{worst_delta:.3e} (single row {worst_row_delta:.3e})", flush=True)
     return orc
 
 
@@ -315,6 +323,8 @@ def test_decode_over_a_chosen_part_of_a_microbatch(engine):
         for l in range(shape.n_layers):
             assert rel_l2(got_layers[l], ref_layers[l]) <= tol_layer, (t, l)
             assert rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref) <= tol_delta, (t, l)
+            assert max_row_rel_l2(got_layers[l], ref_layers[l]) <= tol_layer, (t, l)
+            assert max_row_rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref) <= tol_delta, (t, l)
             prev_ref, prev_got = ref_layers[l], got_layers[l]
         assert rel_l2(runner.to_numpy_f32(hout), ref_out) <= max(tol_layer, 8e-3 if shape.dtype == "bf16" else 0)
         after = st.get_ctx_lens(mb)
@@ -464,14 +474,17 @@ def test_config3_ragged_full_shape_sampled_rows():
     runner.stage.destroy()
 
 
-def test_config4_layer_shapes_sampled_rows():
-    """configs[3]'s layer shapes and batch (hidden 8192, 64/8 heads, ffn 28672, 256 sequences of 2048
-    tokens) on two of its ten layers and two micro-batches: the large-tile GEMMs at 256 rows with the
-    separate element-wise kernels, at the sizes bench.py --config C4 launches them."""
+def test_config4_full_depth_sampled_rows():
+    """configs[3] at its real depth and layer shapes (10 layers, hidden 8192, 64/8 heads, ffn 28672, 256 sequences
+    of 2048 tokens: 640 KiB pages, their per-layer stride, the 10-layer staging copy and host re-layout), two of
+    its eight micro-batches streamed through two arenas for two cycles (sigma = 1): the large-tile GEMMs at 256
+    rows with the separate element-wise kernels, at the sizes bench.py launches them.  (Two micro-batches are
+    43 GB of pinned memory; the remaining six differ only in their seed.)"""
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
-    shape = CONFIGS["C4"].with_(n_microbatches=2, n_layers=2)
+    shape = CONFIGS["C4"].with_(n_microbatches=2)
+    assert shape.n_layers == 10 and shape.page_bytes == 640 * 1024
     syn = SynthInputs(shape, seed=0, gain_jitter=0.1)
     steps = 2 * shape.n_microbatches
     runner = StageRunner(shape, syn, steps=steps, flags=pm.FLAG_CAPTURE_LAYERS).load()
@@ -481,3 +494,134 @@ def test_config4_layer_shapes_sampled_rows():
     check_tables(runner)
     _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs=sample)
     runner.stage.destroy()
+
+
+def test_config5_shapes_full_depth_sampled_rows():
+    """configs[4]'s shapes at full depth: 256 sequences with 4096-token contexts on the 10-layer 70B-shaped stage.
+    The new token makes 4097 tokens = 257 pages per sequence, one more than a single attention work-group takes,
+    so the 256-row large-tile GEMM path runs together with the split attention and its in-kernel merge.  One
+    micro-batch is 43 GB of pinned memory, all this host can pin beside the staging buffers, so the schedule is
+    the one-batch case of Eq. 3 (i = j = k): step, evict everything, prefetch everything back from the host
+    replica (which by then holds the first step's tokens), step again."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = CONFIGS["C5"].with_(n_microbatches=1)
+    syn = SynthInputs(shape, seed=0, gain_jitter=0.1)
+    runner = StageRunner(shape, syn, steps=3, flags=pm.FLAG_CAPTURE_LAYERS).load()
+    st = runner.stage
+    assert st.get_stats()["engine"] == 1
+    sample = [0, 77, 255]
+    orc = make_oracle(shape, syn, runner.ctx0, {0: sample})
+    st.prefetch_kv(0)
+    cur = torch.cuda.current_stream().cuda_stream
+    for t in range(3):
+        print(f"step {t}", flush=True)
+        hin = runner.hidden_tensor(t, 0)
+        hout = torch.empty_like(hin)
+        st.decode_step(0, hin.data_ptr(), hout.data_ptr(), cur)
+        x_in = syn.as_f32(syn.hidden(t, runner.b))[sample]
+        ref_out, ref_layers = orc.decode_step(0, x_in, seqs=sample)
+        got_layers = st.get_layer_outputs(runner.b)[:, sample, :]
+        prev_ref = prev_got = x_in
+        for l in range(shape.n_layers):
+            assert max_row_rel_l2(got_layers[l], ref_layers[l]) <= 1e-2, (t, l)
+            assert max_row_rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref) <= 3e-2, (t, l)
+            prev_ref, prev_got = ref_layers[l], got_layers[l]
+        assert max_row_rel_l2(runner.to_numpy_f32(hout)[sample], ref_out) <= 1e-2
+        assert st.get_ctx_lens(0).tolist() == [4096 + t + 1] * runner.b
+        if t == 0:
+            st.evict_kv(0)
+            assert np.all(st.get_residency(0) == pm.HOST)
+            st.prefetch_kv(0)
+    assert len(st.get_block_table(0, 0)[1]) == 257
+    check_tables(runner)
+    _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs={0: sample})
+    st.destroy()
+
+
+def test_alias_microbatches_move_the_same_bytes():
+    """pipemax_mb_define_alias (hosts that cannot pin a whole configuration): an alias takes nothing from the host
+    pool, names its source's host pages, prefetches the source's bytes into GPU pages of its own and runs the
+    cyclic schedule with the traffic of an ordinary micro-batch; the tokens that existed when it was defined stay
+    intact in the shared pages."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(n_microbatches=4, seqs_per_mb=6, ctx_lo=20, ctx_hi=120, decode_steps=8)
+    traffic = {}
+    for real in (4, 2):
+        syn = SynthInputs(shape, seed=9, pool_elems=1 << 23, gain_jitter=0.1)
+        ctx = {mb: syn.ctx_lens(mb % real) for mb in range(4)}       # the un-aliased run gets the same lengths
+        runner = StageRunner(shape, syn, ctx_lens=ctx, real_microbatches=real)
+        st = runner.stage
+        runner.load_weights()
+        free0 = None
+        if real == 2:
+            for mb in range(2):
+                st.mb_define(mb, runner.ctx0[mb])
+                for s, L in enumerate(runner.ctx0[mb]):
+                    for l in range(shape.n_layers):
+                        st.kv_host_write(mb, s, l, 0, *syn.kv_prefix(mb, s, l, int(L)))
+            free0 = st.get_stats()["host_pages_free"]
+            for mb in (2, 3):
+                st.mb_define_alias(mb, mb - 2)
+            assert st.get_stats()["host_pages_free"] == free0
+            assert [st.mb_alias_of(mb) for mb in range(4)] == [-1, -1, 0, 1]
+            for s in range(runner.b):
+                assert st.get_block_table(2, s)[1].tolist() == st.get_block_table(0, s)[1].tolist()
+            with pytest.raises(pm.PipemaxError) as e:
+                st.mb_define_alias(2, 0)                 # already defined
+            assert e.value.code == pm.ERR_ARG
+            with pytest.raises(pm.PipemaxError) as e:
+                st.kv_host_write(2, 0, 0, 0, *syn.kv_prefix(0, 0, 0, int(runner.ctx0[0][0])))
+            assert e.value.code == pm.ERR_STATE
+            # the alias's GPU pages receive the source's bytes
+            st.prefetch_kv(2)
+            st.prefetch_kv(0)
+            g2 = {int(p) for s in range(runner.b) for p in st.get_block_table(2, s)[0]}
+            g0 = {int(p) for s in range(runner.b) for p in st.get_block_table(0, s)[0]}
+            assert not (g2 & g0)
+            for s in range(runner.b):
+                L = int(runner.ctx0[0][s])
+                for l in range(shape.n_layers):
+                    K0, V0 = syn.kv_prefix(0, s, l, L)
+                    Kd, Vd = st.kv_dev_read(2, s, l, 0, L)
+                    np.testing.assert_array_equal(Kd, K0)
+                    np.testing.assert_array_equal(Vd, V0)
+            st.evict_kv(2)
+            st.evict_kv(0)
+            st.sync()
+        else:
+            runner.load_kv()
+        runner.warm_start()
+        st.sync()
+        st.reset_stats()
+        outs = []
+        for t in range(shape.decode_steps):
+            mb = t % 4
+            hin = runner.hidden_tensor(t, mb)
+            hout = torch.empty_like(hin)
+            runner.step(hin, hout)
+            st.sync()
+            outs.append(hout.float().cpu().numpy())
+        stats = st.get_stats()
+        traffic[real] = (stats["h2d_bytes"], stats["h2d_copies"], stats["d2h_bytes"], stats["d2h_copies"], stats["tokens"])
+        assert all(np.isfinite(o).all() for o in outs)
+        for mb in range(4):
+            assert st.get_ctx_lens(mb).tolist() == (runner.ctx0[mb] + 2).tolist()
+        if real == 2:
+            check_tables(runner)
+            assert st.get_stats()["host_pages_free"] == free0        # growth stayed inside the shared reservation
+            for mb in range(2):                                       # the prompts are untouched by either writer
+                for s in range(runner.b):
+                    L = int(runner.ctx0[mb][s])
+                    for l in range(shape.n_layers):
+                        K0, V0 = syn.kv_prefix(mb, s, l, L)
+                        Kh, Vh = st.kv_host_read(mb, s, l, 0, L)
+                        np.testing.assert_array_equal(Kh, K0)
+                        np.testing.assert_array_equal(Vh, V0)
+        st.destroy()
+    assert traffic[2] == traffic[4]
