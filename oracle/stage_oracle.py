@@ -27,6 +27,12 @@ and SiLU closed forms; GEMM against a triple loop; library cross-check of the
 attention against torch CPU ops.  Absolute activations are "parity unpinned" by
 the paper (it prints none); they are pinned only through those invariants.
 
+Diagnostic mode (not the contract): `operand_round`, when given, is applied where a bf16 matrix-core path has
+to store an operand in bf16 (the normalised activations, q after RoPE, the appended K and V, the softmax
+weights, the attention output, the SwiGLU output).  With it the oracle emulates what operand rounding alone
+costs against the plain fp32 result, which the parity tests use to place their accumulated-error bar; the
+default (None) is the plain definition and nothing else compares against the emulation.
+
 Precision: float32 by default (the precision the benchmark spec fixes for the
 oracle); every function takes the array dtype it is given, so the pins also run
 it in float64 to show that fp32 rounding does not matter at the tolerances used.
@@ -95,7 +101,7 @@ def softmax_lastaxis(s: np.ndarray) -> np.ndarray:
 
 
 def attention_decode(q: np.ndarray, K: np.ndarray, V: np.ndarray,
-                     return_weights: bool = False):
+                     return_weights: bool = False, weight_round=None):
     """One query token against T cached tokens, grouped-query attention.
 
     q [Hq, d]; K, V [T, Hkv, d]; query head u reads KV head u // G, G = Hq/Hkv.
@@ -112,7 +118,7 @@ def attention_decode(q: np.ndarray, K: np.ndarray, V: np.ndarray,
         c = u // G
         s = (K[:, c, :] @ q[u]) * scale               # [T]
         w = softmax_lastaxis(s)
-        out[u] = w @ V[:, c, :]
+        out[u] = (w if weight_round is None else weight_round(w)) @ V[:, c, :]
         if return_weights:
             ws.append(w)
     if return_weights:
@@ -159,11 +165,13 @@ class StageOracle:
 
     def __init__(self, n_layers: int, hidden: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, ffn: int, rope_base: float, rms_eps: float,
-                 dtype=np.float32):
+                 dtype=np.float32, operand_round=None):
         self.nl, self.h = n_layers, hidden
         self.Hq, self.Hkv, self.d, self.F = n_q_heads, n_kv_heads, head_dim, ffn
         self.base, self.eps = float(rope_base), float(rms_eps)
         self.dt = np.dtype(dtype)
+        self.rnd = operand_round if operand_round is not None else (lambda a: a)
+        self.wrnd = operand_round
         self.w = [None] * n_layers
         self.kv = {}          # (mb, seq) -> list over layers of (_Grow K, _Grow V)
 
@@ -205,23 +213,24 @@ class StageOracle:
         W = self.w[layer]
         b = x.shape[0]
         Hq, Hkv, d = self.Hq, self.Hkv, self.d
-        xn = rmsnorm(x, W["g1"], self.eps)
+        xn = self.rnd(rmsnorm(x, W["g1"], self.eps))
         q = (xn @ W["wq"]).reshape(b, Hq, d)
         k = (xn @ W["wk"]).reshape(b, Hkv, d)
         v = (xn @ W["wv"]).reshape(b, Hkv, d)
         pos = np.array([self.kv[(mb, s)][layer][0].n for s in seqs])   # p_i = L_i
-        q = rope(q, pos, self.base)
-        k = rope(k, pos, self.base)
+        q = self.rnd(rope(q, pos, self.base))
+        k = self.rnd(rope(k, pos, self.base))
+        v = self.rnd(v)
         o = np.empty((b, Hq, d), dtype=self.dt)
         for r, s in enumerate(seqs):
             Kc, Vc = self.kv[(mb, s)][layer]
             Kc.append(k[r])
             Vc.append(v[r])
-            o[r] = attention_decode(q[r], Kc.arr, Vc.arr)              # over L_i + 1 tokens
-        attn = o.reshape(b, Hq * d) @ W["wo"]
+            o[r] = attention_decode(q[r], Kc.arr, Vc.arr, weight_round=self.wrnd)   # over L_i + 1 tokens
+        attn = self.rnd(o.reshape(b, Hq * d)) @ W["wo"]
         x = x + attn
-        xn2 = rmsnorm(x, W["g2"], self.eps)
-        a = silu(xn2 @ W["wg"]) * (xn2 @ W["wu"])
+        xn2 = self.rnd(rmsnorm(x, W["g2"], self.eps))
+        a = self.rnd(silu(xn2 @ W["wg"]) * (xn2 @ W["wu"]))
         ffn = a @ W["wd"]
         x = x + ffn
         return x, dict(attn=attn, ffn=ffn)

@@ -5,11 +5,11 @@ from oracle.stage_oracle import StageOracle
 
 
 def make_oracle(shape, syn, ctx0: dict, seqs: dict | None = None, dtype=np.float32,
-                share_weights_of: StageOracle | None = None) -> StageOracle:
+                share_weights_of: StageOracle | None = None, operand_round=None) -> StageOracle:
     """ctx0[mb] = prompt lengths; seqs[mb] = which sequences to track (default all).  share_weights_of: another
     oracle of the same stage whose weight arrays this one reads too (the 70B-shaped stage is 34 GB in fp32)."""
     orc = StageOracle(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-                      shape.ffn, shape.rope_base, shape.rms_eps, dtype=dtype)
+                      shape.ffn, shape.rope_base, shape.rms_eps, dtype=dtype, operand_round=operand_round)
     for l in range(shape.n_layers):
         if share_weights_of is not None:
             orc.w[l] = share_weights_of.w[l]

