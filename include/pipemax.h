@@ -239,6 +239,23 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
 int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n,
                              const void* hidden_in, void* hidden_out, void* hip_stream);
 
+/* pipemax_decode_step for callers that cannot allocate: code under HIP graph capture, serving loops and
+ * harnesses that forbid hipMalloc.  Same arguments, same result, same errors and the same kernels as
+ * pipemax_decode_step, but every device buffer the step works in besides its inputs, outputs, weights and KV
+ * pages (residual stream, RoPE table, matrix-operand activations, split-K partials of the GEMMs and of the
+ * attention, arrival counters, partial sums of squares) lies in one static device array of
+ * PIPEMAX_NOALLOC_SCRATCH_BYTES that the library holds per GPU until the process ends, and the call itself calls
+ * no hipMalloc / hipFree / event creation (a timing flag set on the stage is ignored for this call).
+ * A step that needs more than the array holds is refused with ERR_ARG and a text naming both sizes, before
+ * anything is enqueued (8B-shaped stages of up to 128 rows fit; the 256-row passes of the 70B-shaped stage
+ * do not).  Only stages on the matrix-core engine are served (ERR_STATE otherwise).
+ * All stages and calls on one GPU share the array: it keeps the last call's contents, the call clears what
+ * must start at zero (with a kernel on hip_stream), and two calls whose work overlaps in time on one GPU --
+ * different streams, or different stages driven from different threads -- race; calls on one stream are safe. */
+#define PIPEMAX_NOALLOC_SCRATCH_BYTES (64u << 20)
+int pipemax_decode_step_noalloc(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
+                                void* hip_stream);
+
 /* Prefill (Sec. 3.1.1: the KV cache produced by prefill is offloaded to CPU memory asynchronously;
  * Sec. 3.4.2: per-layer offload and CPU re-layout): runs the stage over n_tokens NEW tokens of one
  * sequence, at positions L .. L + n_tokens - 1 where L is the sequence's current length (0 for a fresh

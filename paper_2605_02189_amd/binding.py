@@ -52,7 +52,7 @@ SYMBOLS = [
     "pipemax_stage_create", "pipemax_stage_destroy", "pipemax_set_weight", "pipemax_mb_define",
     "pipemax_mb_define_alias", "pipemax_mb_alias_of",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
-    "pipemax_decode_step", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
+    "pipemax_decode_step", "pipemax_decode_step_noalloc", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
     "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_config", "pipemax_mb_size",
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
@@ -184,6 +184,7 @@ _sig = {
     "pipemax_kv_dev_read": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]),
     "pipemax_prefetch_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
     "pipemax_decode_step": (C.c_int, [_vp, C.c_int, _vp, _vp, _vp]),
+    "pipemax_decode_step_noalloc": (C.c_int, [_vp, C.c_int, _vp, _vp, _vp]),
     "pipemax_decode_step_seqs": (C.c_int, [_vp, C.c_int, _i32p, C.c_int, _vp, _vp, _vp]),
     "pipemax_prefill": (C.c_int, [_vp, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp]),
     "pipemax_evict_kv": (C.c_int, [_vp, C.c_int, _i32p, C.c_int]),
@@ -318,6 +319,11 @@ class Stage:
         """Device pointers as integers (e.g. tensor.data_ptr(), torch stream .cuda_stream)."""
         _check(_lib.pipemax_decode_step(self._h, mb, _vp(hidden_in_ptr), _vp(hidden_out_ptr),
                                         _vp(stream_ptr) if stream_ptr else None))
+
+    def decode_step_noalloc(self, mb, hidden_in_ptr: int, hidden_out_ptr: int, stream_ptr: int = 0):
+        """pipemax_decode_step with the working buffers in the library's static per-GPU scratch."""
+        _check(_lib.pipemax_decode_step_noalloc(self._h, mb, _vp(hidden_in_ptr), _vp(hidden_out_ptr),
+                                                _vp(stream_ptr) if stream_ptr else None))
 
     def decode_step_seqs(self, mb, seq_ids, hidden_in_ptr: int, hidden_out_ptr: int, stream_ptr: int = 0):
         """Rows of the hidden tensors follow seq_ids (distinct sequence indices of mb)."""

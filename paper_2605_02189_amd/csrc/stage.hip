@@ -35,6 +35,9 @@
 #include "pipemax_xfer.h"
 #include "kv_pool.hpp"
 
+// Scratch of pipemax_decode_step_noalloc: one copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[PIPEMAX_NOALLOC_SCRATCH_BYTES];
+
 namespace pmx {
 
 static thread_local char g_err[512] = "";
@@ -57,6 +60,50 @@ enum { TC_H2D = PIPEMAX_N_KCLASS, TC_D2H = PIPEMAX_N_KCLASS + 1 };
 double now_s() {
   return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
+
+// ---- scratch of the entry point that allocates nothing (pipemax_decode_step_noalloc) -------------------------
+// One array per GPU, held for the life of the process.  Host code never uses the array's name as an address:
+// the device address is looked up once per device (scratch_base) and handed to the kernels as an argument.
+constexpr size_t kScratchBytes = PIPEMAX_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mu;
+
+// Device address of this GPU's copy of the scratch array (the device must be current); nullptr + error text on
+// failure.
+void* scratch_base(int dev) {
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("device %d is outside the %d devices the static scratch is tracked for", dev, kMaxDevices);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      set_error("hipGetSymbolAddress of the static scratch failed on device %d: %s", dev, hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// clears n16 16-byte words (a kernel, not a memset node: callers may be under graph capture)
+__global__ void k_clear16(uint4* p, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// The device buffers a step works in besides its inputs, outputs, weights and KV pages (matrix-core engine).
+struct Work {
+  float* x = nullptr;
+  float2* rope_cs = nullptr;
+  uint16_t *m_xn_t = nullptr, *m_q = nullptr, *m_attn_t = nullptr, *m_act_t = nullptr;
+  float *m_part = nullptr, *m_part_o = nullptr, *m_part_ml = nullptr, *m_ssq = nullptr;
+  int *m_cnt_gemm = nullptr, *m_cnt_attn = nullptr;
+};
 
 struct SeqState {
   int len = 0;
@@ -179,6 +226,8 @@ struct pipemax_stage {
   hipEvent_t ev_h2d_fence = nullptr;
   bool h2d_fence_pending = false;
   pipemax_xfer_t* xfer = nullptr;   // not owned: issues the prefetch copies when attached
+  void* scratch_dev = nullptr;      // device address of this GPU's static scratch (pipemax_decode_step_noalloc)
+  bool no_timing_now = false;       // the current step must not create events
   // worker
   std::thread worker;
   std::mutex mu;
@@ -204,7 +253,7 @@ struct pipemax_stage {
   std::vector<hipEvent_t> ev_free;
 
   // ---- helpers ---------------------------------------------------------------------------------
-  bool timing() const { return cfg.flags & PIPEMAX_FLAG_TIME_KERNELS; }
+  bool timing() const { return (cfg.flags & PIPEMAX_FLAG_TIME_KERNELS) && !no_timing_now; }
   hipEvent_t get_event() {
     if (!ev_free.empty()) {
       hipEvent_t e = ev_free.back();
@@ -811,6 +860,11 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   } while (0)
 
   PMX_TRY_HIP(hipSetDevice(st->dev));
+  st->scratch_dev = scratch_base(st->dev);       // this device's copy of the static scratch
+  if (!st->scratch_dev) {
+    destroy_impl(st);
+    return PIPEMAX_ERR_HIP;
+  }
   PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_own, hipStreamNonBlocking));
   PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_h2d, hipStreamNonBlocking));
   PMX_TRY_HIP(hipStreamCreateWithFlags(&st->s_d2h, hipStreamNonBlocking));
@@ -1286,6 +1340,77 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
 
 // ---- the decode step ----------------------------------------------------------------------------------
 namespace {
+// Chunking of the decode attention for a step of b rows whose longest context is max_len cached tokens and that
+// reads sum_pages pages per KV head and layer: pages per work-group (*cp_out) and the number of chunks (returned).
+int attention_plan(const pipemax_stage* st, int b, int max_len, int64_t sum_pages, int* cp_out) {
+  const Dims& D = st->D;
+  // attention split: about one wave per SIMD (1024 on the chip); a work-group of kAttnWaves waves
+  // covers up to 64 pages per wave, so most contexts are a single chunk
+  const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
+  const int per_chunk_waves = b * D.Hkv * mfma::kAttnWaves;
+  const int nch_target = std::max(1, (1024 + per_chunk_waves / 2) / per_chunk_waves);
+  int CP = (npages_max + nch_target - 1) / nch_target;
+  // Ragged batches: a work-group streams about 1.3 pages per microsecond whatever else runs (its four waves
+  // wait for one page each), the whole chip about 650 (8 KiB pages at 5.3 TB/s).  When the longest sequence
+  // alone would take longer than all pages take at the chip's rate, it -- and every sequence longer than the
+  // resulting chunk -- is split evenly, so that the tail of the launch is not one work-group.  Uniform
+  // batches (longest = mean) and batches with enough sequences to hide a long one keep a single chunk
+  // (measured: 64 ragged sequences of 512..4100 tokens -4 % per step; 128 of them no gain from splitting).
+  {
+    const double chip_bound = (double)D.Hkv * (double)sum_pages / 650.0 * 1.3;      // pages one work-group may own
+    const double target = std::max(chip_bound, (double)sum_pages / b);
+    const int nch_long = std::max(1, (int)std::ceil(npages_max / std::max(target, 1.0) - 1e-9));
+    CP = std::min(CP, (npages_max + nch_long - 1) / nch_long);
+  }
+  CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
+  if (st->attn_cp_override > 0) CP = std::max(8, std::min(64 * mfma::kAttnWaves, st->attn_cp_override));
+  *cp_out = CP;
+  return std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
+}
+
+// Lays the working buffers of a b-row step (matrix-core engine, nch attention chunks) out in the static scratch.
+// Sizes follow pipemax_stage_create with this call's row count in place of max_seqs_per_mb.  Returns the bytes
+// needed (the caller compares them with kScratchBytes); *clear_bytes = the leading part that must start at zero.
+size_t carve_work(const pipemax_stage* st, int b, int nch, Work* W, size_t* clear_bytes) {
+  const Dims& D = st->D;
+  const int nq = D.Hq * D.d;
+  const size_t mpad = (size_t)((b + 31) / 32) * 32;
+  const size_t mtile = (b <= 32) ? 32 : (b <= 64) ? 64 : (b <= 128) ? 128 : (size_t)((b + 255) / 256) * 256;
+  size_t part = 0;
+  if (b <= kFusedRows) {
+    part = std::max(part, (size_t)st->f_qkv.split * mtile * D.Nqkv);
+    part = std::max(part, (size_t)st->f_o.split * mtile * D.h);
+    part = std::max(part, (size_t)st->f_d.split * mtile * D.h);
+  } else {
+    part = std::max(part, (size_t)plan_rows(D.Nqkv, D.h, b).split * mtile * D.Nqkv);
+    part = std::max(part, (size_t)plan_rows(D.h, nq, b).split * mtile * D.h);
+    part = std::max(part, (size_t)plan_rows(2 * D.F, D.h, b).split * mtile * 2 * D.F);
+    part = std::max(part, (size_t)plan_rows(D.h, D.F, b).split * mtile * D.h);
+  }
+  const size_t n_cnt = (size_t)std::max(D.Nqkv, D.h) / 64 + 1;
+  char* base = (char*)st->scratch_dev;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base + off;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  };
+  W->m_cnt_gemm = (int*)take(n_cnt * sizeof(int));
+  W->m_cnt_attn = (int*)take((size_t)b * D.Hkv * sizeof(int));
+  W->m_ssq = (float*)take((size_t)kFusedRows * (D.h / 64) * sizeof(float));
+  W->m_xn_t = (uint16_t*)take(mtile * D.h * 2);
+  W->m_attn_t = (uint16_t*)take(mtile * nq * 2);
+  W->m_act_t = (uint16_t*)take(mtile * D.F * 2);
+  *clear_bytes = off;
+  W->x = (float*)take(mpad * D.h * sizeof(float));
+  W->rope_cs = (float2*)take((size_t)b * (D.d / 2) * sizeof(float2));
+  W->m_q = (uint16_t*)take((size_t)b * nq * 2);
+  W->m_part = (float*)take(part * sizeof(float));
+  W->m_part_o = (float*)take((size_t)b * D.Hq * nch * 128 * sizeof(float));
+  W->m_part_ml = (float*)take((size_t)b * D.Hq * nch * 2 * sizeof(float));
+  return off;
+}
+
 // One pass of the stage over a list of rows.  Row r is one new token: of sequence sel[r] at position
 // pos0[r] (= the number of tokens cached before it).  A decode step has one row per sequence at its current
 // length; a prefill chunk has consecutive positions of one sequence.  Rows of the same sequence must be
@@ -1295,7 +1420,8 @@ namespace {
 // every row's K,V is appended before any row's attention runs and row r attends to positions <= pos0[r],
 // which is causal attention within a chunk.
 int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const std::vector<int>& pos0, bool subset,
-                const void* hidden_in, void* hidden_out, void* hip_stream, bool one_seq_chunk = false) {
+                const void* hidden_in, void* hidden_out, void* hip_stream, bool one_seq_chunk = false,
+                bool static_scratch = false) {
   const double t_enter = now_s();
   int rc;
   if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
@@ -1325,9 +1451,22 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
   if (grow > st->gpu_pages->free_count() || grow_host > st->host_pages->free_count())
     PMX_FAIL(PIPEMAX_ERR_POOL_EXHAUSTED, "%d new pages needed; free: GPU %d, host %d", grow,
              st->gpu_pages->free_count(), st->host_pages->free_count());
+  if (static_scratch) {      // refused before anything changes: engine, the scratch's address, its size
+    if (st->engine != 1)
+      PMX_FAIL(PIPEMAX_ERR_STATE, "the entry point that allocates nothing serves stages on the matrix-core engine only");
+    if (!st->scratch_dev) PMX_FAIL(PIPEMAX_ERR_STATE, "the static scratch has no device address on device %d", st->dev);
+    int cp = 0;
+    Work probe;
+    size_t clear_bytes = 0;
+    const size_t need_bytes = carve_work(st, b, attention_plan(st, b, max_len, sum_pages, &cp), &probe, &clear_bytes);
+    if (need_bytes > kScratchBytes)
+      PMX_FAIL(PIPEMAX_ERR_ARG, "a step of %d rows on this stage needs %zu bytes of working buffers; the static scratch "
+               "of the entry point that allocates nothing holds %zu", b, need_bytes, kScratchBytes);
+  }
   PMX_HIP(hipSetDevice(st->dev));
   hipStream_t cs = hip_stream ? (hipStream_t)hip_stream : st->s_own;
   st->s_last = cs;
+  st->no_timing_now = static_scratch;      // no event is created on behalf of a caller that must not allocate
 
   // ---- bookkeeping: growth pages, positions of the new token ----------------------------------------
   const bool writeback = !(st->cfg.flags & PIPEMAX_FLAG_NO_WRITEBACK);
@@ -1492,44 +1631,39 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
   } else {
     const int mpad = ((b + 31) / 32) * 32;
     const int nq = D.Hq * D.d;
-    // attention split: about one wave per SIMD (1024 on the chip); a work-group of kAttnWaves waves
-    // covers up to 64 pages per wave, so most contexts are a single chunk
     const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
-    const int per_chunk_waves = b * D.Hkv * mfma::kAttnWaves;
-    const int nch_target = std::max(1, (1024 + per_chunk_waves / 2) / per_chunk_waves);
-    int CP = (npages_max + nch_target - 1) / nch_target;
-    // Ragged batches: a work-group streams about 1.3 pages per microsecond whatever else runs (its four waves
-    // wait for one page each), the whole chip about 650 (8 KiB pages at 5.3 TB/s).  When the longest sequence
-    // alone would take longer than all pages take at the chip's rate, it -- and every sequence longer than the
-    // resulting chunk -- is split evenly, so that the tail of the launch is not one work-group.  Uniform
-    // batches (longest = mean) and batches with enough sequences to hide a long one keep a single chunk
-    // (measured: 64 ragged sequences of 512..4100 tokens -4 % per step; 128 of them no gain from splitting).
-    {
-      const double chip_bound = (double)D.Hkv * (double)sum_pages / 650.0 * 1.3;      // pages one work-group may own
-      const double target = std::max(chip_bound, (double)sum_pages / b);
-      const int nch_long = std::max(1, (int)std::ceil(npages_max / std::max(target, 1.0) - 1e-9));
-      CP = std::min(CP, (npages_max + nch_long - 1) / nch_long);
+    int CP = 0;
+    const int nch = attention_plan(st, b, max_len, sum_pages, &CP);
+    Work W;     // the buffers the step works in: the stage's own, or carved from the static per-GPU scratch
+    if (!static_scratch) {
+      W.x = st->x; W.rope_cs = st->rope_cs; W.m_xn_t = st->m_xn_t; W.m_q = st->m_q; W.m_attn_t = st->m_attn_t;
+      W.m_act_t = st->m_act_t; W.m_part = st->m_part; W.m_part_o = st->m_part_o; W.m_part_ml = st->m_part_ml;
+      W.m_ssq = st->m_ssq; W.m_cnt_gemm = st->m_cnt_gemm; W.m_cnt_attn = st->m_cnt_attn;
+    } else {
+      size_t clear_bytes = 0;
+      carve_work(st, b, nch, &W, &clear_bytes);      // fits: checked before the bookkeeping above
+      // everything the stage's own buffers have zeroed at creation (counters, sums of squares, padding rows)
+      const size_t n16 = clear_bytes / 16;
+      hipLaunchKernelGGL(k_clear16, dim3((unsigned)std::min<size_t>(1024, (n16 + 255) / 256)), dim3(256), 0, cs,
+                         (uint4*)st->scratch_dev, n16);
     }
-    CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
-    if (st->attn_cp_override > 0) CP = std::max(8, std::min(64 * mfma::kAttnWaves, st->attn_cp_override));
-    const int nch = std::min(st->nch_alloc, (npages_max + CP - 1) / CP);
     const int64_t s_qkv = (int64_t)mpad * D.Nqkv, s_h = (int64_t)mpad * D.h, s_gu = (int64_t)mpad * 2 * D.F;
-    auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* W, int K, int N) {
-      mfma::gemm(cs, Xt, (const uint16_t*)W, st->m_part, b, K, N, p.split, p.wn);
+    auto run_gemm = [&](const GemmPlan& p, const uint16_t* Xt, const void* Wt, int K, int N) {
+      mfma::gemm(cs, Xt, (const uint16_t*)Wt, W.m_part, b, K, N, p.split, p.wn);
     };
     // a prefill chunk (consecutive positions of one sequence) has its own kernel: 16 rows share every K,V load
     const bool chunk_kernel = one_seq_chunk && b > 1 && npages_max <= 64 * mfma::kAttnWaves;
     auto run_attention = [&](int l) {
       if (chunk_kernel) {
         st->tbegin(PIPEMAX_K_ATTN, cs);
-        mfma::attention_prefill(cs, D, l, b, pos0[0], st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, st->m_attn_t);
+        mfma::attention_prefill(cs, D, l, b, pos0[0], W.m_q, (const uint16_t*)st->gpu_pool, M.d_table, W.m_attn_t);
         st->tend(cs);
       } else {
         // timed through the dispatch's own start / stop events: an event recorded before and after a launch
         // also counts the two gaps around the kernel (about 3.5 us here)
         auto* tp = st->tpair(PIPEMAX_K_ATTN);
-        mfma::attention(cs, D, l, b, st->m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, st->m_part_o,
-                        st->m_part_ml, CP, nch, st->m_cnt_attn, st->m_attn_t,
+        mfma::attention(cs, D, l, b, W.m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, W.m_part_o,
+                        W.m_part_ml, CP, nch, W.m_cnt_attn, W.m_attn_t,
                         M.d_table + (size_t)st->cfg.max_seqs_per_mb * D.max_pages, tp ? tp->a : nullptr,
                         tp ? tp->b : nullptr);
       }
@@ -1538,37 +1672,37 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
       // 5 launches per layer: every element-wise consumer runs in the epilogue of the GEMM before it
       const int nb = D.h / 64;       // partial sums of squares per row: one per column block of the residual GEMMs
       st->tbegin(PIPEMAX_K_NORM, cs);
-      mfma::first(cs, b, D.h, (const uint16_t*)hidden_in, st->x, (const uint16_t*)st->w[0].g1, st->m_xn_t, st->m_ssq,
-                  nb, M.d_ctx, st->rope_cs, D.rope_base);
+      mfma::first(cs, b, D.h, (const uint16_t*)hidden_in, W.x, (const uint16_t*)st->w[0].g1, W.m_xn_t, W.m_ssq,
+                  nb, M.d_ctx, W.rope_cs, D.rope_base);
       st->tend(cs);
       for (int l = 0; l < nl; ++l) {
         const LayerW& L = st->w[l];
         const bool last = (l == nl - 1);
         uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
         st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
-        mfma::gemm_qkv_rope_append(cs, D, l, b, st->m_xn_t, (const uint16_t*)L.wqkv, st->m_part, st->m_cnt_gemm,
-                                   st->m_ssq, nb, st->rope_cs, M.d_ctx, M.d_table, (uint16_t*)st->gpu_pool, stage_l,
-                                   st->m_q, st->f_qkv.split, st->f_qkv.nwk);
+        mfma::gemm_qkv_rope_append(cs, D, l, b, W.m_xn_t, (const uint16_t*)L.wqkv, W.m_part, W.m_cnt_gemm,
+                                   W.m_ssq, nb, W.rope_cs, M.d_ctx, M.d_table, (uint16_t*)st->gpu_pool, stage_l,
+                                   W.m_q, st->f_qkv.split, st->f_qkv.nwk);
         st->tend(cs);
         int rc2 = after_append(l);
         if (rc2) return rc2;
         run_attention(l);
         st->tbegin(PIPEMAX_K_GEMM_O, cs);
-        mfma::gemm_resid(cs, b, nq, D.h, st->m_attn_t, (const uint16_t*)L.wo, st->m_part, st->m_cnt_gemm, st->x,
-                         (const uint16_t*)L.g2, st->m_xn_t, st->m_ssq, nullptr, nullptr, st->f_o.split, st->f_o.nwk);
+        mfma::gemm_resid(cs, b, nq, D.h, W.m_attn_t, (const uint16_t*)L.wo, W.m_part, W.m_cnt_gemm, W.x,
+                         (const uint16_t*)L.g2, W.m_xn_t, W.m_ssq, nullptr, nullptr, st->f_o.split, st->f_o.nwk);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
-        mfma::gemm_swiglu(cs, b, D.h, D.F, D.eps, st->m_xn_t, (const uint16_t*)L.wgu, st->m_ssq, nb, st->m_act_t,
+        mfma::gemm_swiglu(cs, b, D.h, D.F, D.eps, W.m_xn_t, (const uint16_t*)L.wgu, W.m_ssq, nb, W.m_act_t,
                           b > 64 ? 8 : st->f_gu.nwk);   // four row tiles per wave: 8 waves keep two waves per SIMD
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
-        mfma::gemm_resid(cs, b, D.F, D.h, st->m_act_t, (const uint16_t*)L.wd, st->m_part, st->m_cnt_gemm, st->x,
-                         last ? nullptr : (const uint16_t*)st->w[l + 1].g1, st->m_xn_t, last ? nullptr : st->m_ssq,
+        mfma::gemm_resid(cs, b, D.F, D.h, W.m_act_t, (const uint16_t*)L.wd, W.m_part, W.m_cnt_gemm, W.x,
+                         last ? nullptr : (const uint16_t*)st->w[l + 1].g1, W.m_xn_t, last ? nullptr : W.m_ssq,
                          last ? (uint16_t*)hidden_out : nullptr, last ? M.d_ctx : nullptr, st->f_d.split,
                          st->f_d.nwk);
         st->tend(cs);
         if (st->layer_out)
-          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)l * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)l * b * D.h, W.x, (size_t)b * D.h * sizeof(float),
                                  hipMemcpyDeviceToDevice, cs));
       }
     } else {
@@ -1576,56 +1710,56 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
                      p_gu = plan_rows(2 * D.F, D.h, b), p_d = plan_rows(D.h, D.F, b);
       const float* prev_part = nullptr;     // partials of the previous layer's down projection
       st->tbegin(PIPEMAX_K_MISC, cs);
-      launch_rope_table(cs, M.d_ctx, st->rope_cs, b, D.d, D.rope_base);
+      launch_rope_table(cs, M.d_ctx, W.rope_cs, b, D.d, D.rope_base);
       st->tend(cs);
       for (int l = 0; l < nl; ++l) {
         const LayerW& L = st->w[l];
         uint16_t* stage_l = (uint16_t*)st->d_stage[slot] + (size_t)l * layer_elems;
         st->tbegin(PIPEMAX_K_NORM, cs);
         mfma::resid_norm(cs, b, D.h, D.eps, l == 0 ? (const uint16_t*)hidden_in : nullptr, prev_part,
-                         p_d.split, s_h, st->x, (const uint16_t*)L.g1, st->m_xn_t, nullptr);
+                         p_d.split, s_h, W.x, (const uint16_t*)L.g1, W.m_xn_t, nullptr);
         st->tend(cs);
         if (st->layer_out && l > 0)
-          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+          PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(l - 1) * b * D.h, W.x, (size_t)b * D.h * sizeof(float),
                                  hipMemcpyDeviceToDevice, cs));
         st->tbegin(PIPEMAX_K_GEMM_QKV, cs);
-        run_gemm(p_qkv, st->m_xn_t, L.wqkv, D.h, D.Nqkv);
+        run_gemm(p_qkv, W.m_xn_t, L.wqkv, D.h, D.Nqkv);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_ROPE_APPEND, cs);
-        mfma::rope_append(cs, D, l, b, st->m_part, p_qkv.split, s_qkv, st->rope_cs, M.d_ctx, M.d_table,
-                          (uint16_t*)st->gpu_pool, stage_l, st->m_q);
+        mfma::rope_append(cs, D, l, b, W.m_part, p_qkv.split, s_qkv, W.rope_cs, M.d_ctx, M.d_table,
+                          (uint16_t*)st->gpu_pool, stage_l, W.m_q);
         st->tend(cs);
         int rc2 = after_append(l);
         if (rc2) return rc2;
         run_attention(l);
         st->tbegin(PIPEMAX_K_GEMM_O, cs);
-        run_gemm(p_o, st->m_attn_t, L.wo, nq, D.h);
+        run_gemm(p_o, W.m_attn_t, L.wo, nq, D.h);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_NORM, cs);
-        mfma::resid_norm(cs, b, D.h, D.eps, nullptr, st->m_part, p_o.split, s_h, st->x, (const uint16_t*)L.g2,
-                         st->m_xn_t, nullptr);
+        mfma::resid_norm(cs, b, D.h, D.eps, nullptr, W.m_part, p_o.split, s_h, W.x, (const uint16_t*)L.g2,
+                         W.m_xn_t, nullptr);
         st->tend(cs);
         st->tbegin(PIPEMAX_K_GEMM_GU, cs);
         const bool gu_fused = (p_gu.wn == 0 && p_gu.split == 1);     // SwiGLU in the GEMM's epilogue
-        mfma::gemm(cs, st->m_xn_t, (const uint16_t*)L.wgu, st->m_part, b, D.h, 2 * D.F, p_gu.split, p_gu.wn,
-                   gu_fused ? st->m_act_t : nullptr);
+        mfma::gemm(cs, W.m_xn_t, (const uint16_t*)L.wgu, W.m_part, b, D.h, 2 * D.F, p_gu.split, p_gu.wn,
+                   gu_fused ? W.m_act_t : nullptr);
         st->tend(cs);
         if (!gu_fused) {
           st->tbegin(PIPEMAX_K_SWIGLU, cs);
-          mfma::swiglu(cs, b, D.F, st->m_part, p_gu.split, s_gu, st->m_act_t);
+          mfma::swiglu(cs, b, D.F, W.m_part, p_gu.split, s_gu, W.m_act_t);
           st->tend(cs);
         }
         st->tbegin(PIPEMAX_K_GEMM_D, cs);
-        run_gemm(p_d, st->m_act_t, L.wd, D.F, D.h);
+        run_gemm(p_d, W.m_act_t, L.wd, D.F, D.h);
         st->tend(cs);
-        prev_part = st->m_part;
+        prev_part = W.m_part;
       }
       st->tbegin(PIPEMAX_K_NORM, cs);
-      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, p_d.split, s_h, st->x, nullptr, nullptr,
+      mfma::resid_norm(cs, b, D.h, D.eps, nullptr, prev_part, p_d.split, s_h, W.x, nullptr, nullptr,
                        (uint16_t*)hidden_out);
       st->tend(cs);
       if (st->layer_out)
-        PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(nl - 1) * b * D.h, st->x, (size_t)b * D.h * sizeof(float),
+        PMX_HIP(hipMemcpyAsync(st->layer_out + (size_t)(nl - 1) * b * D.h, W.x, (size_t)b * D.h * sizeof(float),
                                hipMemcpyDeviceToDevice, cs));
       st->tbegin(PIPEMAX_K_MISC, cs);
       launch_advance_ctx(cs, M.d_ctx, b);
@@ -1660,6 +1794,20 @@ int pipemax_decode_step(pipemax_stage_t* st, int mb, const void* hidden_in, void
     pos[i] = st->mbs[mb].seq[i].len;
   }
   return decode_rows(st, mb, sel, pos, false, hidden_in, hidden_out, hip_stream);
+}
+
+int pipemax_decode_step_noalloc(pipemax_stage_t* st, int mb, const void* hidden_in, void* hidden_out,
+                                void* hip_stream) {
+  int rc = check_mb(st, mb, true);
+  if (rc) return rc;
+  std::vector<int> sel(st->mbs[mb].b), pos(st->mbs[mb].b);
+  for (int i = 0; i < (int)sel.size(); ++i) {
+    sel[i] = i;
+    pos[i] = st->mbs[mb].seq[i].len;
+  }
+  rc = decode_rows(st, mb, sel, pos, false, hidden_in, hidden_out, hip_stream, false, true);
+  st->no_timing_now = false;
+  return rc;
 }
 
 int pipemax_decode_step_seqs(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n, const void* hidden_in,
