@@ -1,20 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the stage-decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--sigma 1.0]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--sigma 1.0]
+    python bench.py --probes          # HBM stream rate and host-link rates only (one JSON line of their own)
 
-A step = one pass of the whole hot path over one micro-batch: pipemax_decode_step of D_i with the
-KV prefetch of D_{i+1} and the write-back running on the side streams (cyclic schedule, Eq. 3).
-The default workload is configs[1] (8 of 32 layers of an 8B-shaped model, 4 micro-batches x 64
-sequences x 1024-token prompts, bf16) with every inactive micro-batch's KV in pinned host memory
-(sigma = 1).  Inputs (weights, hidden states, the active micro-batch's pages once prefetched) are
-resident in HBM when the timed region starts; the KV of the inactive micro-batches is in host
-memory by construction: moving it is the method being measured, not input staging.
+A step = one pass of the whole hot path over one micro-batch: pipemax_decode_step of D_i with the KV prefetch of
+D_{i+1} and the write-back running beside it (cyclic schedule, Eq. 3).  The default workload is the largest
+configuration, configs[4] (C5: 10 of 80 layers of a 70B-shaped model, 8 micro-batches x 256 sequences x 4096-token
+contexts, bf16, 344 GB of KV: more than the HBM holds, so it is streamed from pinned host memory), with every
+inactive micro-batch's KV in host memory (sigma = 1).  A process here can pin about 64 GiB, so only as many
+micro-batches as fit get host pages and KV of their own; the others are aliases (pipemax_mb_define_alias: same
+lengths, the same host pages, GPU pages of their own): the transfers move the same bytes along the same access
+pattern and the kernels read the same amount of KV.  config.workload says how many are aliases.  Weights, hidden
+states and the active micro-batch's pages (once prefetched) are resident in HBM when the timed region starts; the
+KV of the inactive micro-batches is in host memory by construction: moving it is the method being measured.
 
 Prints ONE JSON line.  Besides the headline (tokens/s of the streamed schedule) it carries
-  roofline      achieved HBM GB/s of the attention kernel from HIP events on the compute stream,
+  roofline      achieved HBM GB/s of the attention kernel from the dispatches' own start / stop events,
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload,
-  legs          compute-only / transfers-only / both, the overlap fraction and the link rate.
+  legs          compute-only / transfers-only / both, both overlap figures and the link rate,
+  sigma_sweep   step time against the streamed fraction sigma of every micro-batch, with the crossover from
+                link-bound to HBM-bound and whether the transfers are hidden there,
+  also          (default run only) the same figures, compact, for configs[3] (C4).
 """
 from __future__ import annotations
 
@@ -30,6 +37,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction (the figure the paper uses, Sec. 4.1)
+PIN_BUDGET_GIB = 60.0          # pinned host memory the page pool may take (a process here pins about 64 GiB)
 
 
 def log(*a):
@@ -54,9 +62,9 @@ def measured_traffic(config_name, key="traffic_bytes_per_launch"):
     return None
 
 
-def cpu_baseline(shape, syn, ctx0, k_seqs, n_steps):
-    """The oracle as it stands on a sample of micro-batch 0: k sequences, all layers, full context."""
-    import numpy as np
+def cpu_baseline(shape, syn, ctx0, k_seqs, budget_s):
+    """The oracle as it stands on a sample of micro-batch 0: k sequences, all layers, full context; as many decode
+    steps as fit the time budget (at least one)."""
     from oracle.stage_oracle import StageOracle
     orc = StageOracle(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                       shape.ffn, shape.rope_base, shape.rms_eps)
@@ -64,14 +72,17 @@ def cpu_baseline(shape, syn, ctx0, k_seqs, n_steps):
         orc.set_layer_weights(l, **{k: syn.as_f32(v) for k, v in syn.weights(l).items()})
     seqs = list(range(k_seqs))
     for s in seqs:
-        kv = [syn.kv_prefix(0, s, l, int(ctx0[0][s])) for l in range(shape.n_layers)]
+        kv = [syn.kv_prefix(0, s, l, int(ctx0[s])) for l in range(shape.n_layers)]
         orc.define_sequence(0, s, [syn.as_f32(k) for k, _ in kv], [syn.as_f32(v) for _, v in kv])
     x = syn.as_f32(syn.hidden(0, shape.seqs_per_mb))[seqs]
     orc.decode_step(0, x, seqs=seqs)                      # untimed first step (page-in, BLAS start-up)
-    t0 = time.perf_counter()
-    for _ in range(n_steps):
+    n_steps, t0 = 0, time.perf_counter()
+    while True:
         orc.decode_step(0, x, seqs=seqs)
-    dt = time.perf_counter() - t0
+        n_steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or n_steps >= 64:
+            break
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -83,169 +94,147 @@ def cpu_baseline(shape, syn, ctx0, k_seqs, n_steps):
             cores = min(cores, max(blas))
     except Exception:
         pass
-    return {"value": k_seqs * n_steps / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_steps} decode steps of {k_seqs} of the {shape.seqs_per_mb} sequences of "
-                      f"micro-batch 0, all {shape.n_layers} layers, full {int(ctx0[0][0])}-token context, fp32"}
+    return {"value": round(k_seqs * n_steps / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n_steps} decode steps ({dt:.1f} s) of {k_seqs} of the {shape.seqs_per_mb} sequences of "
+                      f"micro-batch 0, all {shape.n_layers} layers, full {int(ctx0[0])}-token context, fp32"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="C2")
-    ap.add_argument("--sigma", type=float, default=1.0, help="streamed fraction of every micro-batch")
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--microbatches", type=int, default=None,
-                    help="run with fewer micro-batches than the configuration names (host memory limits)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-legs", action="store_true", help="skip the compute-only / transfer-only legs")
-    ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
-    ap.add_argument("--probe-copy", action="store_true",
-                    help="also launch the library's plain copy kernel (256 MiB, 3 times): calibration for --pmc runs")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time sigma = 1, 1/2, ..., 1/128, 0 (two cycles each) to locate the crossover "
-                         "from link-bound to HBM-bound")
-    ap.add_argument("--orchestrated", type=float, default=0.0, metavar="CHUNK_MIB",
-                    help="issue the prefetch copies through the transfer orchestrator in chunks of this many MiB "
-                         "(window of 2); 0 = the stage's own prefetch stream")
-    ap.add_argument("--cpu-seqs", type=int, default=16)
-    ap.add_argument("--cpu-steps", type=int, default=48)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
-              "(the stages of a pipeline are independent processes, one per GPU; nothing here runs on a second GPU)", file=sys.stderr)
-        sys.exit(2)
+def run_probes(args):
+    """The rates the roofline arguments lean on, measured with the library's probe entry points."""
+    import torch
+    from paper_2605_02189_amd import binding as pm
+    out = {"probe": "hbm stream + host link", "unit": "GB/s"}
+    n = 4 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_()
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    sp = torch.cuda.current_stream().cuda_stream
 
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) * 1e-3)
+        return best
+    hbm = {}
+    for name, seg in (("grid_stride", 0), ("contiguous_8KiB_per_group", 2), ("contiguous_64KiB_per_group", 16),
+                      ("contiguous_1MiB_per_group", 256)):
+        hbm["read_" + name] = round(n / timed(lambda: pm.probe_read(src.data_ptr(), n, seg, sink.data_ptr(), sp)) / 1e9, 1)
+    hbm["copy_read_plus_write"] = round(2 * n / timed(lambda: pm.probe_copy(dst.data_ptr(), src.data_ptr(), n, sp)) / 1e9, 1)
+    out["hbm_gbs"] = hbm
+    log("hbm:", json.dumps(hbm))
+    del src, dst
+    torch.cuda.empty_cache()
+    link = {}
+    total = 2 << 30
+    for name, direction in (("h2d", 0), ("d2h", 1), ("both", 2)):
+        r = pm.probe_link(total, 64 << 20, None, direction, repeats=3)
+        link[name + "_64MiB_pieces"] = {"h2d": round(r["h2d_bytes"] / r["h2d_s"] / 1e9, 2) if r["h2d_s"] else None,
+                                        "d2h": round(r["d2h_bytes"] / r["d2h_s"] / 1e9, 2) if r["d2h_s"] else None}
+    # block-first (whole pages and merged runs of pages) against layer-first fragments (Sec. 4.4): one hipMemcpyAsync
+    # per piece, pieces one page apart for the fragments (the other layers of the page lie between them)
+    pieces = {}
+    for label, piece, stride in (("run_64MiB (block-first, merged page runs)", 64 << 20, None),
+                                 ("page_640KiB (block-first, one copy per page, 70B stage)", 640 << 10, None),
+                                 ("page_512KiB (block-first, one copy per page, 8B stage)", 512 << 10, None),
+                                 ("fragment_64KiB (layer-first, K+V of one layer of a page)", 64 << 10, 640 << 10),
+                                 ("fragment_32KiB (layer-first, K or V of one layer of a page)", 32 << 10, 320 << 10)):
+        tot = min(total, piece * 16384)
+        r = pm.probe_link(tot, piece, stride, 0, repeats=2)
+        pieces[label] = round(r["h2d_bytes"] / r["h2d_s"] / 1e9, 2)
+        log("link piece", label, pieces[label])
+    link["h2d_by_piece"] = pieces
+    out["link_gbs"] = link
+    out["link_peak_nominal_gbs"] = LINK_PEAK_GBS
+    out["hbm_peak_nominal_gbs"] = HBM_PEAK_GBS
+    print(json.dumps(out), flush=True)
+
+
+def run_config(name, args, *, light=False):
+    """Sets one configuration up and measures it.  light: shorter timed run, no per-class breakdown."""
     import numpy as np
     import torch
-    from paper_2605_02189_amd.build import ensure_built
-    ensure_built()      # loads what is built; builds only if nothing is
     from paper_2605_02189_amd import binding as pm
-    from paper_2605_02189_amd.harness import StageRunner
+    from paper_2605_02189_amd.harness import StageRunner, pages_for
     from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    shape = CONFIGS[args.config]
+    shape = CONFIGS[name]
     if args.microbatches:
         shape = shape.with_(n_microbatches=args.microbatches)
-    n = shape.n_microbatches
-    K = args.steps if args.steps is not None else shape.decode_steps
-    W = args.warmup if args.warmup is not None else 2 * n
-    legs_steps = 0 if args.no_legs else (W + 3 * min(K, 16 * n))
-    total_steps = (W + K) + legs_steps + 4 * n + (9 * 4 * n if args.sweep else 0)
+    n, b = shape.n_microbatches, shape.seqs_per_mb
+    K = args.steps if args.steps is not None else (2 * n if light else shape.decode_steps)
+    W = args.warmup if args.warmup is not None else n
+    sweep_sigmas = [] if args.no_sweep else [0.5, 0.25, 0.125, 1 / 16, 1 / 32, 1 / 64, 1 / 128, 0.0]
+    Kc = min(K, 4 * n) if light else min(K, 8 * n)
+    total_steps = (W + K) + (0 if args.no_legs else 2 * n + 3 * Kc + 2 * n) + len(sweep_sigmas) * 3 * n + 2 * n
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
-    run = StageRunner(shape, syn, sigma=args.sigma, steps=total_steps, gpu_pool_all_resident=not args.no_legs,
+    lens = {mb: syn.ctx_lens(mb) for mb in range(n)}
+    steps_per_mb = -(-total_steps // n)
+    grow = pages_for(steps_per_mb) + 1
+    mb_bytes = [sum(pages_for(int(l)) + grow for l in lens[mb]) * shape.page_bytes for mb in range(n)]
+    real = 0
+    while real < n and sum(mb_bytes[: real + 1]) <= PIN_BUDGET_GIB * 2 ** 30:
+        real += 1
+    real = max(1, real)
+    # GPU pool: every micro-batch resident if the HBM has room for them beside the weights, else as many as fit
+    free_b, _ = torch.cuda.mem_get_info()
+    room = free_b - shape.weight_bytes - (10 << 30)
+    n_res = n
+    while n_res > 2 and sum(sorted(mb_bytes, reverse=True)[:n_res]) > room:
+        n_res -= 1
+    run = StageRunner(shape, syn, sigma=args.sigma, steps=total_steps, real_microbatches=real,
+                      gpu_resident_microbatches=n_res, arenas=args.arenas,
                       flags=pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
     st = run.stage
     run.load()
-    xfer = None
-    if args.orchestrated > 0:
-        xfer = pm.Xfer(device=0, max_inflight_bulk=2, chunk_bytes=int(args.orchestrated * (1 << 20)))
-        st.attach_xfer(xfer)
     hin = [run.hidden_tensor(mb, mb) for mb in range(n)]
     hout = [torch.empty_like(h) for h in hin]
     stream = torch.cuda.current_stream()
-    log(f"setup {time.perf_counter() - t_setup:.1f}s: {shape.name} engine={st.get_stats()['engine']} "
-        f"weights {shape.weight_bytes / 1e9:.2f} GB, KV/mb {sum(int(l) for l in run.ctx0[0]) * shape.kv_bytes_per_token / 1e9:.2f} GB")
+    kv_mb = sum(int(l) for l in run.ctx0[0]) * shape.kv_bytes_per_token
+    log(f"setup {time.perf_counter() - t_setup:.1f}s: {name} engine={st.get_stats()['engine']} weights "
+        f"{shape.weight_bytes / 1e9:.2f} GB, KV/mb {kv_mb / 1e9:.2f} GB, {real} of {n} micro-batches with host pages of "
+        f"their own, GPU pool for {n_res} whole micro-batches")
 
     def sync():
         torch.cuda.synchronize()
         st.sync()
 
-    legs = {}
-    roofline = None
-    # ---- the timed run: compute + transfers, the literal configuration -----------------------------------
+    def timed_steps(k):
+        sync()
+        st.reset_stats()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            i = run.t % n
+            run.step(hin[i], hout[i], stream)
+        sync()
+        dt = time.perf_counter() - t0
+        return dt, st.get_stats()
+
+    res = {"name": name, "shape": shape, "n": n, "b": b, "K": K, "W": W, "real": real, "n_res": n_res}
+    # ---- the timed run: compute + transfers, the literal configuration (sigma = 1 unless --sigma) --------------
     run.warm_start()
     for _ in range(W):
         i = run.t % n
         run.step(hin[i], hout[i], stream)
-    sync()
-    st.reset_stats()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        i = run.t % n
-        run.step(hin[i], hout[i], stream)
-    sync()
-    dt = time.perf_counter() - t0
-    s3 = st.get_stats()
-    tokens = s3["tokens"]
-    value = tokens / dt
-    ms_per_step = dt / K * 1e3
+    dt, s3 = timed_steps(K)
+    res.update(value=s3["tokens"] / dt, ms_per_step=dt / K * 1e3, dt=dt, s_both=s3)
+    log(f"{name} sigma={args.sigma}: {dt / K * 1e3:.3f} ms/step, {s3['tokens'] / dt:.1f} tokens/s, "
+        f"h2d {s3['h2d_bytes'] / dt / 1e9:.2f} GB/s")
+    legs, roofline = {}, None
     if not args.no_legs:
-        # ---- leg 1: compute only (everything resident), kernel classes timed with HIP events -----------
-        for mb in range(n):
-            st.prefetch_kv(mb)
-        sync()
-        for _ in range(W):
-            i = run.t % n
-            run.step(hin[i], hout[i], stream, transfers=False)
-        sync()
-        Kc = min(K, 16 * n)
-        # (a) only the attention kernel bracketed by HIP events on the compute stream: the roofline figure
-        st.set_flags(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY, 0)
-        st.reset_stats()
-        bytes_attn = 0
-        for _ in range(Kc):
-            i = run.t % n
-            bytes_attn += shape.n_layers * attn_bytes(shape, st.get_ctx_lens(i))
-            run.step(hin[i], hout[i], stream, transfers=False)
-        sync()
-        s0 = st.get_stats()
-        attn_ms = s0["kernel_ms"]["attn"] / max(s0["kernel_launches"]["attn"], 1)
-        attn_launches = int(s0["kernel_launches"]["attn"])
-        # (b) every kernel class bracketed: the per-class breakdown (the brackets themselves cost time)
-        st.set_flags(pm.FLAG_TIME_KERNELS, pm.FLAG_TIME_ATTN_ONLY)
-        st.reset_stats()
-        t0 = time.perf_counter()
-        for _ in range(Kc):
-            i = run.t % n
-            run.step(hin[i], hout[i], stream, transfers=False)
-        sync()
-        t_timed = time.perf_counter() - t0
-        s1 = st.get_stats()
-        st.set_flags(0, pm.FLAG_TIME_KERNELS)
-        # (c) the same steps without any bracket: the compute-only step time
-        t0 = time.perf_counter()
-        for _ in range(Kc):
-            i = run.t % n
-            run.step(hin[i], hout[i], stream, transfers=False)
-        sync()
-        t_c = (time.perf_counter() - t0) / Kc
-        kms, kl = s1["kernel_ms"], s1["kernel_launches"]
-        achieved = bytes_attn / max(attn_launches, 1) / (attn_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
-                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(shape.name),
-                    "traffic_measured_on_algorithmic_bytes": measured_traffic(shape.name, "algorithmic_bytes_per_launch"),
-                    "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_launches,
-                    "bytes_per_launch": int(bytes_attn / max(attn_launches, 1))}
-        hbm_bytes_step = shape.weight_bytes + bytes_attn / Kc
-        legs["compute_only"] = {
-            "ms_per_step": round(t_c * 1e3, 4), "tokens_per_s": round(run.b / t_c, 1),
-            "ms_per_step_with_event_brackets": round(t_timed / Kc * 1e3, 4),
-            "hbm_bytes_per_step": int(hbm_bytes_step),
-            "frac_of_hbm_roofline": round(hbm_bytes_step / t_c / 1e9 / HBM_PEAK_GBS, 4),
-            "kernel_us_per_launch": {k: round(kms[k] / max(kl[k], 1) * 1e3, 2) for k in kms if kl[k]},
-            "kernel_ms_per_step": {k: round(kms[k] / Kc, 4) for k in kms if kl[k]},
-            "gemm_tflops": round(2 * (shape.weight_bytes / shape.elem_bytes) * run.b /
-                                 ((kms["gemm_qkv"] + kms["gemm_o"] + kms["gemm_gu"] + kms["gemm_d"]) / Kc * 1e-3) / 1e12, 1),
-            "gemm_weight_gbs": round(shape.weight_bytes /
-                                     ((kms["gemm_qkv"] + kms["gemm_o"] + kms["gemm_gu"] + kms["gemm_d"]) / Kc * 1e-3) / 1e9, 1),
-            "host_enqueue_ms_per_step": round(s1["host_enqueue_s"] / Kc * 1e3, 4)}
-        log("compute-only:", json.dumps(legs["compute_only"]))
-        # ---- leg 2: transfers only (the same evict / prefetch traffic, no kernels) ---------------------
-        for mb in range(n):
-            st.evict_kv(mb)
-        sync()
-        run.t = 0
-        run.warm_start()
+        # ---- transfers only: the same evict / prefetch traffic, no kernels ---------------------------------
         sync()
         st.set_flags(pm.FLAG_TIME_KERNELS, 0)
         st.reset_stats()
-        Kx = 2 * n
+        Kx = n if light else 2 * n
         t0 = time.perf_counter()
         for _ in range(Kx):
             run.step(None, None, stream, compute=False)
@@ -253,83 +242,235 @@ def main():
         t_x = (time.perf_counter() - t0) / Kx
         s2 = st.get_stats()
         st.set_flags(0, pm.FLAG_TIME_KERNELS)
+        link_gbs = s2["h2d_bytes"] / Kx / t_x / 1e9
         legs["transfer_only"] = {
             "ms_per_step": round(t_x * 1e3, 3), "h2d_bytes_per_step": int(s2["h2d_bytes"] / Kx),
             "h2d_copies_per_step": s2["h2d_copies"] / Kx,
-            "h2d_gbs_busy": round(s2["h2d_bytes"] / max(s2["h2d_ms"], 1e-9) / 1e6, 2),
-            "h2d_gbs_wall": round(s2["h2d_bytes"] / Kx / t_x / 1e9, 2)}
+            "h2d_gbs_busy": round(s2["h2d_bytes"] / max(s2["h2d_ms"], 1e-9) / 1e6, 2), "h2d_gbs_wall": round(link_gbs, 2)}
         log("transfer-only:", json.dumps(legs["transfer_only"]))
+        # ---- compute only: n_res micro-batches resident, no transfers ----------------------------------------
         for mb in range(n):
             st.evict_kv(mb)
         sync()
-        run.t = 0
+        res_mbs = list(range(n_res))
+        for mb in res_mbs:
+            st.prefetch_kv(mb)
+        sync()
+        sp = stream.cuda_stream
 
-    if legs:
+        def compute_steps(k, count_bytes=False):
+            nbytes = 0
+            for q in range(k):
+                i = res_mbs[q % n_res]
+                if count_bytes:
+                    nbytes += shape.n_layers * attn_bytes(shape, st.get_ctx_lens(i))
+                st.decode_step(i, hin[i].data_ptr(), hout[i].data_ptr(), sp)
+            return nbytes
+        compute_steps(n_res)
+        sync()
+        # (a) only the attention kernel timed, by the dispatches' own start / stop events: the roofline figure
+        st.set_flags(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY, 0)
+        st.reset_stats()
+        bytes_attn = compute_steps(Kc, count_bytes=True)
+        sync()
+        s0 = st.get_stats()
+        attn_launches = int(s0["kernel_launches"]["attn"])
+        attn_ms = s0["kernel_ms"]["attn"] / max(attn_launches, 1)
+        # (b) every kernel class bracketed: the per-class breakdown (the brackets themselves cost time)
+        st.set_flags(pm.FLAG_TIME_KERNELS, pm.FLAG_TIME_ATTN_ONLY)
+        st.reset_stats()
+        t0 = time.perf_counter()
+        compute_steps(Kc)
+        sync()
+        t_timed = time.perf_counter() - t0
+        s1 = st.get_stats()
+        st.set_flags(0, pm.FLAG_TIME_KERNELS)
+        # (c) the same steps without any bracket: the compute-only step time
+        sync()
+        st.reset_stats()
+        t0 = time.perf_counter()
+        compute_steps(Kc)
+        sync()
+        t_c = (time.perf_counter() - t0) / Kc
+        s_plain = st.get_stats()
+        kms, kl = s1["kernel_ms"], s1["kernel_launches"]
+        achieved = bytes_attn / max(attn_launches, 1) / (attn_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(name),
+                    "traffic_measured_on_algorithmic_bytes": measured_traffic(name, "algorithmic_bytes_per_launch"),
+                    "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_launches,
+                    "bytes_per_launch": int(bytes_attn / max(attn_launches, 1))}
+        hbm_bytes_step = shape.weight_bytes + bytes_attn / Kc
+        gemm_ms = (kms["gemm_qkv"] + kms["gemm_o"] + kms["gemm_gu"] + kms["gemm_d"]) / Kc
+        legs["compute_only"] = {
+            "ms_per_step": round(t_c * 1e3, 4), "tokens_per_s": round(b / t_c, 1),
+            "resident_microbatches": n_res,
+            "ms_per_step_with_event_brackets": round(t_timed / Kc * 1e3, 4),
+            "hbm_bytes_per_step": int(hbm_bytes_step),
+            "frac_of_hbm_roofline": round(hbm_bytes_step / t_c / 1e9 / HBM_PEAK_GBS, 4),
+            "kernel_us_per_launch": {k: round(kms[k] / max(kl[k], 1) * 1e3, 2) for k in kms if kl[k]},
+            "kernel_ms_per_step": {k: round(kms[k] / Kc, 4) for k in kms if kl[k]},
+            "gemm_tflops": round(2 * (shape.weight_bytes / shape.elem_bytes) * b / (gemm_ms * 1e-3) / 1e12, 1),
+            "gemm_weight_gbs": round(shape.weight_bytes / (gemm_ms * 1e-3) / 1e9, 1),
+            "host_enqueue_ms_per_step_with_event_brackets": round(s1["host_enqueue_s"] / Kc * 1e3, 4),
+            "host_enqueue_ms_per_step": round(s_plain["host_enqueue_s"] / Kc * 1e3, 4)}
+        log("compute-only:", json.dumps(legs["compute_only"]))
         t_both = dt / K
-        t_c, t_x = legs["compute_only"]["ms_per_step"] * 1e-3, legs["transfer_only"]["ms_per_step"] * 1e-3
         legs["both"] = {
             "ms_per_step": round(t_both * 1e3, 3),
+            # the survey's figure (written for the compute-bound regime) and a symmetric one: the share of the
+            # shorter of the two activities that runs under the longer one
             "overlap_frac": round(1.0 - max(0.0, t_both - t_c) / t_x, 4) if t_x > 0 else None,
+            "overlap_frac_symmetric": round(1.0 - max(0.0, t_both - max(t_c, t_x)) / min(t_c, t_x), 4),
             "hidden": bool(t_both <= 1.05 * max(t_c, t_x)),
             "h2d_gbs_wall": round(s3["h2d_bytes"] / dt / 1e9, 2),
             "frac_of_link_roofline": round(s3["h2d_bytes"] / dt / 1e9 / LINK_PEAK_GBS, 4),
+            "frac_of_measured_link": round(s3["h2d_bytes"] / dt / 1e9 / link_gbs, 4),
             "d2h_bytes_per_step": int(s3["d2h_bytes"] / K), "host_wait_s": round(s3["host_wait_s"], 4),
             "host_enqueue_ms_per_step": round(s3["host_enqueue_s"] / K * 1e3, 4)}
+        res.update(t_c=t_c, t_x=t_x, link_gbs=link_gbs)
     sweep = None
-    if args.sweep:
-        sweep = []
-        for sg in [1.0] + [2.0 ** -k for k in range(1, 8)] + [0.0]:
+    if sweep_sigmas and not args.no_legs:
+        # ---- step time against the streamed fraction; sigma shrinks, so only the newly resident part moves ----
+        t_c, link_gbs = res["t_c"], res["link_gbs"]
+        pool_pages = st.get_stats()["gpu_pages_total"]
+        per_seq = pages_for(int(max(int(c.max()) for c in run.ctx0.values()))) + grow
+        sweep = [{"sigma": args.sigma, "ms_per_step": round(res["ms_per_step"], 3),
+                  "h2d_gb_per_step": round(s3["h2d_bytes"] / K / 1e9, 4), "feasible": True}]
+        for sg in sweep_sigmas:
+            ns = int(round(sg * b))
+            need = n * (b - ns) * per_seq + run.arenas * ns * per_seq + 8
+            if need > pool_pages:
+                sweep.append({"sigma": sg, "feasible": False,
+                              "why": f"resident parts + two streamed arenas need {need} GPU pages, the HBM holds {pool_pages}"})
+                continue
             run.restart(sg)
             for _ in range(n):
                 i = run.t % n
                 run.step(hin[i], hout[i], stream)
-            sync()
-            st.reset_stats()
-            Ks = 3 * n
-            t0 = time.perf_counter()
-            for _ in range(Ks):
-                i = run.t % n
-                run.step(hin[i], hout[i], stream)
-            sync()
-            dts = time.perf_counter() - t0
-            ss = st.get_stats()
-            sweep.append({"sigma": sg, "streamed_seqs_per_mb": run.n_stream[0], "ms_per_step": round(dts / Ks * 1e3, 3),
-                          "tokens_per_s": round(ss["tokens"] / dts, 1),
-                          "h2d_gb_per_step": round(ss["h2d_bytes"] / Ks / 1e9, 4),
-                          "h2d_gbs_wall": round(ss["h2d_bytes"] / dts / 1e9, 2)})
+            # at least two cycles and at least ~0.15 s, so that the drain at the end does not weigh on short steps
+            est = max(t_c, ns * per_seq * shape.page_bytes / (link_gbs * 1e9))
+            ks = n * max(2, min(64, int(0.15 / est / n + 0.5)))
+            dts, ss = timed_steps(ks)
+            sweep.append({"sigma": sg, "feasible": True, "streamed_seqs_per_mb": ns, "steps": ks,
+                          "ms_per_step": round(dts / ks * 1e3, 3),
+                          "h2d_gb_per_step": round(ss["h2d_bytes"] / ks / 1e9, 4),
+                          "host_wait_s": round(ss["host_wait_s"], 4)})
             log("sweep:", json.dumps(sweep[-1]))
+        for p in sweep:
+            if not p["feasible"]:
+                continue
+            tx = p["h2d_gb_per_step"] / link_gbs        # what the step's prefetch takes on the link alone (s)
+            p["t_transfer_ms_at_measured_link"] = round(tx * 1e3, 3)
+            p["bound"] = "link" if tx > t_c else "hbm"
+            p["hidden"] = bool(p["ms_per_step"] * 1e-3 <= 1.05 * max(t_c, tx))
+            p["vs_compute_only"] = round(p["ms_per_step"] * 1e-3 / t_c, 3)
+        sigma_star = t_c * link_gbs * 1e9 / kv_mb
+        hbm_side = [p for p in sweep if p["feasible"] and p["bound"] == "hbm" and p["sigma"] > 0]
+        link_side = [p for p in sweep if p["feasible"] and p["bound"] == "link"]
+        res["crossover"] = {
+            "sigma_star_predicted": round(sigma_star, 4),
+            "formula": "sigma* = T_compute_only * link rate / KV bytes of one micro-batch",
+            "smallest_link_bound_sigma_measured": min((p["sigma"] for p in link_side), default=None),
+            "largest_hbm_bound_sigma_measured": max((p["sigma"] for p in hbm_side), default=None),
+            "hidden_at_largest_hbm_bound_sigma": (max(hbm_side, key=lambda p: p["sigma"])["hidden"] if hbm_side else None),
+            "reachable": bool(hbm_side),
+        }
+    res.update(legs=legs, roofline=roofline, sweep=sweep, syn=syn, ctx0=run.ctx0[0])
+    st.destroy()
+    del run
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default=None, help="C1..C5 (default: C5, with a compact C4 run beside it)")
+    ap.add_argument("--sigma", type=float, default=1.0, help="streamed fraction of every micro-batch")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--microbatches", type=int, default=None,
+                    help="run with fewer micro-batches than the configuration names")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-legs", action="store_true", help="skip the compute-only / transfer-only legs and the sweep")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the sweep over the streamed fraction")
+    ap.add_argument("--no-also", action="store_true", help="default run: skip the compact C4 run")
+    ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
+    ap.add_argument("--arenas", type=int, default=2,
+                    help="GPU room for this many streamed parts: 2 = Eq. 3 (the prefetch overwrites D_i-1), 3 = it "
+                         "overwrites D_i-2 and never waits for the compute stream")
+    ap.add_argument("--probes", action="store_true", help="only the HBM stream / host link probes")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also launch the library's plain copy kernel (256 MiB, 3 times): calibration for --pmc runs")
+    ap.add_argument("--cpu-seqs", type=int, default=8)
+    ap.add_argument("--cpu-budget-s", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU; --gpus must be 1 "
+              "(the stages of a pipeline are independent processes, one per GPU; nothing here runs on a second GPU)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_02189_amd.build import ensure_built
+    ensure_built()      # loads what is built; builds only if nothing is
+    from paper_2605_02189_amd import binding as pm
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.probes:
+        run_probes(args)
+        return
+
+    name = args.config or "C5"
+    r = run_config(name, args)
+    shape, n = r["shape"], r["n"]
     out = {
-        "metric": "stage decode tokens/sec with host-offloaded KV", "value": round(value, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "metric": "stage decode tokens/sec with host-offloaded KV", "value": round(r["value"], 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": r["K"], "warmup": r["W"], "ms_per_step": round(r["ms_per_step"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
         "data": "synthetic" if not args.no_writeback else "synthetic (DIAGNOSTIC RUN WITHOUT KV WRITE-BACK: not a result)",
         "config": {"workload": f"{shape.name}: {shape.n_layers} layers, hidden {shape.hidden}, "
                                f"{shape.n_q_heads}Q/{shape.n_kv_heads}KV heads x {shape.head_dim}, ffn {shape.ffn}, "
-                               f"{n} micro-batches x {shape.seqs_per_mb} seqs, prompts {shape.ctx_lo}-{shape.ctx_hi} tokens",
-                   "sigma": args.sigma, "schedule": "cyclic (execute D_i, prefetch D_i+1, overwrite D_i-1)",
-                   "inactive_kv": "pinned host memory", "page_tokens": 16,
-                   "prefetch_issue": (f"transfer orchestrator, {args.orchestrated:g} MiB chunks, window 2"
-                                      if args.orchestrated > 0 else "stage's own prefetch stream, whole runs")},
-        "roofline": roofline, "legs": legs,
+                               f"{n} micro-batches x {shape.seqs_per_mb} seqs, prompts {shape.ctx_lo}-{shape.ctx_hi} tokens; "
+                               f"{r['real']} micro-batches with pinned host pages of their own, {n - r['real']} aliases "
+                               f"of them (same lengths and host pages, own GPU pages)",
+                   "sigma": args.sigma, "schedule": "cyclic (execute D_i, overwrite D_i-1, prefetch D_i+1)",
+                   "inactive_kv": "pinned host memory", "page_tokens": 16, "gpu_arenas_for_streamed_kv": args.arenas,
+                   "prefetch_issue": "stage's prefetch worker, whole page runs on the prefetch stream"},
+        "roofline": r["roofline"], "legs": r["legs"],
     }
-    if sweep is not None:
-        out["sigma_sweep"] = sweep
+    if r["sweep"] is not None:
+        out["sigma_sweep"] = r["sweep"]
+        out["crossover"] = r["crossover"]
+    if args.config is None and not args.no_also:
+        import copy
+        a2 = copy.copy(args)
+        a2.steps, a2.warmup = None, None
+        c4 = run_config("C4", a2, light=True)
+        out["also"] = {"C4": {
+            "workload": f"C4: 10 layers, 8 micro-batches x 256 seqs x 2048-token prompts; {c4['real']} with host pages of "
+                        f"their own, {c4['n'] - c4['real']} aliases",
+            "tokens_per_s": round(c4["value"], 1), "ms_per_step": round(c4["ms_per_step"], 3), "steps": c4["K"],
+            "sigma": args.sigma, "roofline": c4["roofline"],
+            "compute_only_ms_per_step": c4["legs"].get("compute_only", {}).get("ms_per_step"),
+            "compute_only_tokens_per_s": c4["legs"].get("compute_only", {}).get("tokens_per_s"),
+            "frac_of_hbm_roofline": c4["legs"].get("compute_only", {}).get("frac_of_hbm_roofline"),
+            "both": c4["legs"].get("both"),
+            "sigma_sweep": [{k: p.get(k) for k in ("sigma", "ms_per_step", "bound", "hidden", "vs_compute_only", "feasible")}
+                            for p in (c4["sweep"] or [])],
+            "crossover": c4.get("crossover")}}
     if args.probe_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         for _ in range(3):
-            pm.probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), stream.cuda_stream)
+            pm.probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         del src, dst
-    if xfer is not None:
-        st.attach_xfer(None)
-        xfer.destroy()
     if not args.no_cpu_baseline:
-        st.destroy()
-        del run
-        out["cpu_baseline"] = cpu_baseline(shape, syn, {0: syn.ctx_lens(0)}, min(args.cpu_seqs, shape.seqs_per_mb),
-                                           args.cpu_steps)
+        out["cpu_baseline"] = cpu_baseline(shape, r["syn"], r["ctx0"], min(args.cpu_seqs, shape.seqs_per_mb),
+                                           args.cpu_budget_s)
     print(json.dumps(out), flush=True)
 
 

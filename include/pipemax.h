@@ -329,6 +329,26 @@ const char* pipemax_version(void);
  * the HBM-traffic figures are derived from.                                                   */
 int pipemax_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* Launches a read-only streaming kernel over `bytes` bytes of device memory at src (16-byte aligned pointer and
+ * size) on hip_stream: what HBM delivers to a plain coalesced reader.  segment_trips = 0: grid-stride order; > 0:
+ * every work-group reads contiguous pieces of segment_trips * 4 KiB.  sink16: 16 bytes of device memory (never
+ * written in practice; it keeps the loads alive).  The caller times the launch (events on hip_stream).        */
+int pipemax_probe_read(const void* src, size_t bytes, int segment_trips, void* sink16, void* hip_stream);
+
+/* Host-link probe (Sec. 4.4 compares the block-first layout, whose transfers are whole pages and page runs, with a
+ * layer-first layout, whose transfers are per-(page, layer) fragments): allocates pinned host and device buffers of
+ * its own on `device`, copies total_bytes in pieces of piece_bytes lying piece_stride bytes apart on both sides
+ * (stride = piece: one contiguous region) with one hipMemcpyAsync per piece, `repeats` times after a warm-up pass, and
+ * reports the fastest pass.  direction: 0 = host->device, 1 = device->host, 2 = both at once on two streams.
+ * h2d_s / d2h_s: first copy issued to last copy done on each stream (HIP events); wall_s: the same for the whole pass
+ * by the host clock.  Synchronises the device.  Errors: ERR_ARG, ERR_OOM_HOST, ERR_OOM_DEVICE, ERR_HIP.           */
+typedef struct {
+  double   h2d_s, d2h_s, wall_s;
+  uint64_t h2d_bytes, d2h_bytes, pieces;
+} pipemax_link_probe_t;
+int pipemax_probe_link(int device, size_t total_bytes, size_t piece_bytes, size_t piece_stride, int direction,
+                       int repeats, pipemax_link_probe_t* out);
+
 /* ---- host-side planning helpers (pure host code; also used by the CPU tests) ------------- */
 
 /* Element offset, inside one KV page, of element `dd` of token slot `tok` (0..15) of head

@@ -53,7 +53,7 @@ SYMBOLS = [
     "pipemax_mb_define_alias", "pipemax_mb_alias_of",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_decode_step_noalloc", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
-    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_get_config", "pipemax_mb_size",
+    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_probe_read", "pipemax_probe_link", "pipemax_get_config", "pipemax_mb_size",
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
     "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
@@ -108,6 +108,11 @@ class Stats(C.Structure):
 
 
 _vp, _i32p = C.c_void_p, C.POINTER(C.c_int32)
+
+
+class LinkProbe(C.Structure):
+    _fields_ = [("h2d_s", C.c_double), ("d2h_s", C.c_double), ("wall_s", C.c_double),
+                ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64), ("pieces", C.c_uint64)]
 
 
 class XferConfig(C.Structure):
@@ -193,6 +198,9 @@ _sig = {
     "pipemax_reset_stats": (C.c_int, [_vp]),
     "pipemax_set_flags": (C.c_int, [_vp, C.c_uint32, C.c_uint32]),
     "pipemax_probe_copy": (C.c_int, [_vp, _vp, C.c_size_t, _vp]),
+    "pipemax_probe_read": (C.c_int, [_vp, C.c_size_t, C.c_int, _vp, _vp]),
+    "pipemax_probe_link": (C.c_int, [C.c_int, C.c_size_t, C.c_size_t, C.c_size_t, C.c_int, C.c_int,
+                                     C.POINTER(LinkProbe)]),
     "pipemax_get_ctx_lens": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_residency": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_block_table": (C.c_int, [_vp, C.c_int, C.c_int, _i32p, _i32p, C.POINTER(C.c_int)]),
@@ -398,6 +406,19 @@ def probe_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream_ptr: int = 0):
 
 
 # -- host-side planning helpers ---------------------------------------------------------------
+def probe_read(src_ptr: int, nbytes: int, segment_trips: int, sink_ptr: int, stream_ptr: int = 0):
+    _check(_lib.pipemax_probe_read(_vp(src_ptr), nbytes, segment_trips, _vp(sink_ptr),
+                                   _vp(stream_ptr) if stream_ptr else None))
+
+
+def probe_link(total_bytes: int, piece_bytes: int, piece_stride: int | None = None, direction: int = 0,
+               repeats: int = 3, device: int = 0) -> dict:
+    out = LinkProbe()
+    _check(_lib.pipemax_probe_link(device, total_bytes, piece_bytes, piece_stride or piece_bytes, direction, repeats,
+                                   C.byref(out)))
+    return {k: getattr(out, k) for k, _ in LinkProbe._fields_}
+
+
 def page_elem_offset(n_layers, n_kv_heads, head_dim, layer, kv, head, tok, dd) -> int:
     return int(_lib.pipemax_page_elem_offset(n_layers, n_kv_heads, head_dim, layer, kv, head, tok, dd))
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipemax.so")
-SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip", "xfer.hip", "scheduler.cpp", "dma_copy.cpp"]
+SOURCES = ["stage.hip", "kernels_generic.hip", "kernels_mfma.hip", "xfer.hip", "probes.hip", "scheduler.cpp", "dma_copy.cpp"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 FLAGS = ["--offload-arch=gfx950", "-fopenmp", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *COMMON]

@@ -28,14 +28,19 @@ class StageRunner:
                  ctx_lens: dict | None = None, gpu_pool_all_resident: bool = False,
                  wb_layers_per_copy: int = 0, reserve: bool = True, gpu_pages: int | None = None,
                  max_rows: int | None = None, real_microbatches: int | None = None,
-                 gpu_resident_microbatches: int | None = None):
+                 gpu_resident_microbatches: int | None = None, arenas: int = 2):
         """real_microbatches = r < n: only micro-batches 0..r-1 get host pages and KV of their own; micro-batch
         m >= r is an alias of m mod r (same lengths, same host pages; hosts that cannot pin the whole
         configuration; timing only).  gpu_resident_microbatches: size the GPU pool for that many whole
-        micro-batches (compute-only legs of configurations whose KV exceeds the HBM)."""
+        micro-batches (compute-only legs of configurations whose KV exceeds the HBM).
+        arenas: GPU room for that many streamed parts.  2 = the schedule of Eq. 3: the prefetch of D_{i+1} overwrites
+        D_{i-1}, so it can start only when step t-1 has ended and has exactly the length of step t to finish.
+        3 = D_{i-1} stays one iteration longer and the prefetch overwrites D_{i-2}, whose last step ended long ago:
+        the copy no longer waits for the compute stream at all (needs n >= 4 micro-batches)."""
         self.shape, self.syn = shape, syn
         pool_override = gpu_pages
         self.n = n_microbatches or shape.n_microbatches
+        self.arenas = 3 if (arenas >= 3 and self.n >= 4) else 2
         self.n_real = min(self.n, real_microbatches or self.n)
         self.b = shape.seqs_per_mb
         self.steps = steps if steps is not None else shape.decode_steps
@@ -54,7 +59,7 @@ class StageRunner:
         resident_pages = sum(sum(full[mb][: self.b_of[mb] - self.n_stream[mb]]) for mb in range(self.n))
         stream_pages = sorted((sum(full[mb][self.b_of[mb] - self.n_stream[mb]:]) for mb in range(self.n)),
                               reverse=True)
-        gpu_pages = resident_pages + sum(stream_pages[:2]) + 8          # two arenas for the streamed part
+        gpu_pages = resident_pages + sum(stream_pages[:self.arenas]) + 8     # arenas for the streamed part
         if gpu_pool_all_resident:                                       # room to keep everything on the GPU
             gpu_pages = all_pages + 8
         if gpu_resident_microbatches is not None:
@@ -84,12 +89,15 @@ class StageRunner:
                            for mb in range(self.n)}
 
     def restart(self, sigma: float):
-        """Evicts everything, changes the streamed fraction and restarts the cycle at iteration 0
-        (needs a GPU pool that can hold the resident parts plus two streamed parts)."""
-        for mb in range(self.n):
-            self.stage.evict_kv(mb)
+        """Changes the streamed fraction and restarts the cycle at iteration 0: the sequences that are streamed from
+        now on leave the GPU, the others come (or stay) resident.  Needs a GPU pool that can hold the resident
+        parts plus two streamed parts."""
         self.stage.sync()
         self._set_sigma(sigma)
+        for mb in range(self.n):
+            if self.n_stream[mb]:
+                self.stage.evict_kv(mb, self.stream_ids[mb])
+        self.stage.sync()
         self.t = 0
         self.warm_start()
         self.stage.sync()
@@ -151,12 +159,13 @@ class StageRunner:
         transfers=False keeps everything where it is (all micro-batches must be resident);
         compute=False issues only the evict / prefetch traffic of the iteration."""
         n, t = self.n, self.t
-        i, j, k = t % n, (t + 1) % n, (t - 1) % n
+        lag = self.arenas - 1                      # the micro-batch that ran `lag` iterations ago is overwritten
+        i, j, k = t % n, (t + 1) % n, (t - lag) % n
         if compute:
             sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
             self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         if transfers:
-            if t > 0 and self.n_stream[k] and k != i and k != j:
+            if t >= lag and self.n_stream[k] and k != i and k != j:
                 self.stage.evict_kv(k, self.stream_ids[k])
             if j != i and self.n_stream[j]:
                 self.stage.prefetch_kv(j, self.stream_ids[j])
