@@ -172,7 +172,11 @@ def run_config(name, args, *, light=False):
     W = args.warmup if args.warmup is not None else n
     sweep_sigmas = [] if args.no_sweep else [0.5, 0.25, 0.125, 1 / 16, 1 / 32, 1 / 64, 1 / 128, 0.0]
     Kc = min(K, 4 * n) if light else min(K, 8 * n)
-    total_steps = (W + K) + (0 if args.no_legs else 2 * n + 3 * Kc + 2 * n) + len(sweep_sigmas) * 3 * n + 2 * n
+    # cycles per sweep point: at least two, at most 24, about 0.15 s (guessing the step at 5 TB/s of HBM traffic)
+    kv_guess = b * (shape.ctx_lo + shape.ctx_hi) // 2 * shape.kv_bytes_per_token
+    sweep_cycles = max(2, min(24, int(0.15 / ((shape.weight_bytes + kv_guess) / 5e12) / n + 0.5)))
+    total_steps = ((W + K) + (0 if args.no_legs else 2 * n + 3 * Kc + 2 * n)
+                   + len(sweep_sigmas) * (1 + sweep_cycles) * n + 2 * n)
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
@@ -351,7 +355,7 @@ def run_config(name, args, *, light=False):
                 run.step(hin[i], hout[i], stream)
             # at least two cycles and at least ~0.15 s, so that the drain at the end does not weigh on short steps
             est = max(t_c, ns * per_seq * shape.page_bytes / (link_gbs * 1e9))
-            ks = n * max(2, min(64, int(0.15 / est / n + 0.5)))
+            ks = n * max(2, min(sweep_cycles, int(0.15 / est / n + 0.5)))
             dts, ss = timed_steps(ks)
             sweep.append({"sigma": sg, "feasible": True, "streamed_seqs_per_mb": ns, "steps": ks,
                           "ms_per_step": round(dts / ks * 1e3, 3),

@@ -1,10 +1,12 @@
-"""Decode execution-time estimator and prefetch budget of the control plane (host code, no GPU).
+"""Offline profiling step of the decode execution-time estimator (host code, no GPU).
 
 The paper models the time of one decode iteration of a batch as  alpha * b + beta * L + delta  with
 b = batch size and L = total prefix length of the batch, the three parameters coming from offline
 profiling (Sec. 3.3.1, Eq. 2), and sizes the prefetch that can hide behind it as  B * T_hat  with B
-the effective host-to-device bandwidth (Sec. 3.3.2, Eq. 6).  Here the parameters are fitted by least
-squares to step times measured on the stage (bench.py --estimator).
+the effective host-to-device bandwidth (Sec. 3.3.2, Eq. 6).  This module holds the fit only (least
+squares on step times measured on the stage, see fit_estimator.py); evaluating the model and the
+budget is the scheduler's job (pipemax_sched_predict, pipemax_sched_budget), and the accuracy check
+below goes through it, so there is one implementation of Eq. 2 and Eq. 6 in the product.
 """
 from __future__ import annotations
 
@@ -19,8 +21,11 @@ class DecodeTimeModel:
     beta: float       # seconds per cached token
     delta: float      # seconds per step
 
-    def predict(self, b, L):
-        return self.alpha * np.asarray(b, dtype=np.float64) + self.beta * np.asarray(L, dtype=np.float64) + self.delta
+    def scheduler(self, link_tokens_per_s: float = 1.0, n_batches: int = 1):
+        """A scheduler object carrying these parameters (its predict / budget calls are Eq. 2 / Eq. 6)."""
+        from . import binding as pm
+        return pm.Scheduler(alpha_s=self.alpha, beta_s=self.beta, delta_s=self.delta,
+                            link_tokens_per_s=link_tokens_per_s, n_batches=n_batches)
 
 
 def fit(b, L, t) -> DecodeTimeModel:
@@ -32,25 +37,12 @@ def fit(b, L, t) -> DecodeTimeModel:
 
 
 def accuracy(model: DecodeTimeModel, b, L, t) -> dict:
-    """actual / predicted statistics in the form the paper reports them (Sec. 4.3)."""
-    r = np.asarray(t, dtype=np.float64) / model.predict(b, L)
+    """actual / predicted statistics in the form the paper reports them (Sec. 4.3); the prediction is the
+    scheduler's (pipemax_sched_predict)."""
+    sched = model.scheduler()
+    pred = np.array([sched.predict(int(bi), int(Li)) for bi, Li in zip(np.atleast_1d(b), np.atleast_1d(L))])
+    sched.destroy()
+    r = np.asarray(t, dtype=np.float64) / pred
     dev = np.abs(r - 1.0)
     return {"n": int(r.size), "within_5pct": float(np.mean(dev <= 0.05)), "worst_dev": float(dev.max()),
             "mean_ratio": float(r.mean())}
-
-
-def prefetch_budget_bytes(t_hat: float, link_bytes_per_s: float) -> float:
-    """Bytes that can be prefetched while a step of predicted duration t_hat runs (Eq. 6)."""
-    return link_bytes_per_s * t_hat
-
-
-def prefetch_budget_tokens(t_hat: float, link_bytes_per_s: float, kv_bytes_per_token: int) -> float:
-    """The same budget in cached tokens of this stage (the unit Alg. 1 compares it in)."""
-    return prefetch_budget_bytes(t_hat, link_bytes_per_s) / kv_bytes_per_token
-
-
-def hidden_streamed_fraction(model: DecodeTimeModel, b: int, L: int, link_bytes_per_s: float,
-                             kv_bytes_per_token: int) -> float:
-    """sigma*: the fraction of a micro-batch's KV that can stream in behind one step of another."""
-    t = float(model.predict(b, L))
-    return min(1.0, prefetch_budget_tokens(t, link_bytes_per_s, kv_bytes_per_token) / max(L, 1))

@@ -86,7 +86,10 @@ def main():
     eb, eL, et = (np.array(x) for x in zip(*ev))
     ev_acc = est.accuracy(model, eb, eL, et)
     own_L = base.seqs_per_mb * (base.ctx_lo + base.ctx_hi) // 2
-    t_hat = float(model.predict(base.seqs_per_mb, own_L))
+    sched = model.scheduler(link_tokens_per_s=B / base.kv_bytes_per_token)     # Eq. 2 / Eq. 6 live in the scheduler
+    t_hat = sched.predict(base.seqs_per_mb, own_L)
+    budget_tokens = sched.budget(t_hat)
+    sched.destroy()
     out = {
         "config": base.name, "grid_b": bs, "grid_prefix_len_ranges": Ls,
         "alpha_us_per_request": model.alpha * 1e6, "beta_ns_per_token": model.beta * 1e9, "delta_ms": model.delta * 1e3,
@@ -95,10 +98,9 @@ def main():
                        "ms_first": float(et[0] * 1e3), "ms_last": float(et[-1] * 1e3)},
         "B_prefetch_gbs": B / 1e9,
         "own_microbatch": {"b": base.seqs_per_mb, "L": int(own_L), "t_hat_ms": t_hat * 1e3,
-                           "budget_mb": est.prefetch_budget_bytes(t_hat, B) / 1e6,
-                           "budget_tokens": est.prefetch_budget_tokens(t_hat, B, base.kv_bytes_per_token),
-                           "sigma_star": est.hidden_streamed_fraction(model, base.seqs_per_mb, own_L, B,
-                                                                       base.kv_bytes_per_token)},
+                           "budget_mb": budget_tokens * base.kv_bytes_per_token / 1e6,
+                           "budget_tokens": budget_tokens,
+                           "sigma_star": min(1.0, budget_tokens / max(own_L, 1))},
     }
     print(json.dumps(out))
     st.destroy()

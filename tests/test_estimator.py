@@ -26,10 +26,18 @@ def test_fit_is_least_squares_under_noise():
     assert acc["within_5pct"] > 0.99
 
 
-def test_budget_is_bandwidth_times_time_and_converts_to_tokens():
-    assert est.prefetch_budget_bytes(2e-3, 55e9) == 110e6
-    assert est.prefetch_budget_tokens(2e-3, 55e9, 32768) == 110e6 / 32768
-    m = est.DecodeTimeModel(0.0, 0.0, 1.5e-3)
+def test_model_evaluation_goes_through_the_scheduler_and_matches_the_oracle():
+    """Eq. 2 and Eq. 6 have one implementation in the product, the scheduler's; the fitted model hands its
+    parameters to it.  Values against the scheduler oracle's plain formulas, bit for bit."""
+    from oracle import scheduler_oracle as so
+    m = est.DecodeTimeModel(2.7e-6, 6.3e-9, 0.87e-3)
+    link_tokens_per_s = 56.7e9 / 32768
+    sched = m.scheduler(link_tokens_per_s=link_tokens_per_s, n_batches=4)
+    for b, L in ((64, 64 * 1024), (1, 0), (128, 300000), (17, 12345)):
+        t_hat = sched.predict(b, L)
+        assert t_hat == so.predict_time(m.alpha, m.beta, m.delta, b, L)
+        assert sched.budget(t_hat) == so.budget_tokens(link_tokens_per_s, t_hat)
     # configs[1]: 64 x 1024 tokens, 32 KiB per token: about 3.8 % of a micro-batch hides behind a step
-    s = est.hidden_streamed_fraction(m, 64, 64 * 1024, 55e9, 32768)
-    assert abs(s - 1.5e-3 * 55e9 / 32768 / 65536) < 1e-12 and 0.03 < s < 0.05
+    s = sched.budget(sched.predict(64, 65536)) / 65536
+    assert 0.03 < s < 0.05
+    sched.destroy()
