@@ -149,6 +149,16 @@ def run_probes(args):
         r = pm.probe_link(tot, piece, stride, 0, repeats=2)
         pieces[label] = round(r["h2d_bytes"] / r["h2d_s"] / 1e9, 2)
         log("link piece", label, pieces[label])
+    # strided copies: one layer's 64 KiB block of each page of a run, out of block-first host pages (640 / 512 KiB
+    # apart), into a packed device region -- the prefetch of a layer-major device pool
+    for label, row, pitch, rows in (("2d_64KiB_rows_x257 (70B stage, one sequence of 4097 tokens, one layer)", 64 << 10, 640 << 10, 257),
+                                    ("2d_64KiB_rows_x129 (70B stage, 2049 tokens)", 64 << 10, 640 << 10, 129),
+                                    ("2d_64KiB_rows_x65 (8B stage, 1025 tokens)", 64 << 10, 512 << 10, 65),
+                                    ("2d_64KiB_rows_x1024", 64 << 10, 640 << 10, 1024)):
+        copies = max(1, min(2048, (2 << 30) // (row * rows)))
+        r = pm.probe_link_2d(row, pitch, rows, copies, repeats=2)
+        pieces[label] = round(r["h2d_bytes"] / r["h2d_s"] / 1e9, 2)
+        log("link piece", label, pieces[label])
     link["h2d_by_piece"] = pieces
     out["link_gbs"] = link
     out["link_peak_nominal_gbs"] = LINK_PEAK_GBS
@@ -196,7 +206,8 @@ def run_config(name, args, *, light=False):
         n_res -= 1
     run = StageRunner(shape, syn, sigma=args.sigma, steps=total_steps, real_microbatches=real,
                       gpu_resident_microbatches=n_res, arenas=args.arenas,
-                      flags=pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
+                      flags=(pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
+                      | (pm.FLAG_DEVICE_LAYER_MAJOR if args.device_layout == "layer" else 0))
     st = run.stage
     run.load()
     hin = [run.hidden_tensor(mb, mb) for mb in range(n)]
@@ -406,6 +417,8 @@ def main():
     ap.add_argument("--arenas", type=int, default=2,
                     help="GPU room for this many streamed parts: 2 = Eq. 3 (the prefetch overwrites D_i-1), 3 = it "
                          "overwrites D_i-2 and never waits for the compute stream")
+    ap.add_argument("--device-layout", choices=["block", "layer"], default="block",
+                    help="GPU page pool block-first (as the host replica) or [layer][page]")
     ap.add_argument("--probes", action="store_true", help="only the HBM stream / host link probes")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the library's plain copy kernel (256 MiB, 3 times): calibration for --pmc runs")
@@ -441,6 +454,7 @@ def main():
                                f"of them (same lengths and host pages, own GPU pages)",
                    "sigma": args.sigma, "schedule": "cyclic (execute D_i, overwrite D_i-1, prefetch D_i+1)",
                    "inactive_kv": "pinned host memory", "page_tokens": 16, "gpu_arenas_for_streamed_kv": args.arenas,
+                   "gpu_pool_layout": "[layer][page]" if args.device_layout == "layer" else "block-first pages",
                    "prefetch_issue": "stage's prefetch worker, whole page runs on the prefetch stream"},
         "roofline": r["roofline"], "legs": r["legs"],
     }

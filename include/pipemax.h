@@ -79,6 +79,12 @@ enum {
                                        (compute-only timing runs; evict then loses new tokens)   */
   PIPEMAX_FLAG_TIME_ATTN_ONLY = 16, /* with TIME_KERNELS: bracket only the attention kernel, so that
                                        the other launches' event records do not perturb it       */
+  PIPEMAX_FLAG_DEVICE_LAYER_MAJOR = 64,  /* GPU page pool laid out [layer][page] instead of block-first: the pages of
+                                       the host replica (and a page's bytes on the link) stay block-first, a
+                                       prefetch scatters each page run with one strided copy per layer.  An
+                                       attention launch then reads one contiguous n_layers-th of the pool
+                                       instead of one layer's 64 KiB out of every page.  Not with a transfer
+                                       orchestrator attached (ERR_STATE).                                    */
   PIPEMAX_FLAG_STREAM_ORDERED_EVICT = 32  /* order a prefetch after the last reader of the pages it
                                        re-uses with a stream-side event wait instead of the default
                                        host-side wait of the prefetch worker (see pipemax_prefetch_kv) */
@@ -348,6 +354,12 @@ typedef struct {
 } pipemax_link_probe_t;
 int pipemax_probe_link(int device, size_t total_bytes, size_t piece_bytes, size_t piece_stride, int direction,
                        int repeats, pipemax_link_probe_t* out);
+
+/* The same probe for strided host->device copies (hipMemcpy2DAsync): n_copies copies of rows_per_copy rows of
+ * row_bytes each, the rows host_pitch bytes apart in pinned host memory and packed on the device -- what a prefetch
+ * from block-first host pages into a layer-major device pool issues per (page run, layer).                       */
+int pipemax_probe_link_strided(int device, size_t row_bytes, size_t host_pitch, int rows_per_copy, int n_copies,
+                          int repeats, pipemax_link_probe_t* out);
 
 /* ---- host-side planning helpers (pure host code; also used by the CPU tests) ------------- */
 

@@ -42,6 +42,7 @@ W_QKV, W_O, W_GU, W_D, G_ATTN, G_FFN = range(6)
 FLAG_FORCE_GENERIC, FLAG_CAPTURE_LAYERS, FLAG_TIME_KERNELS, FLAG_NO_WRITEBACK = 1, 2, 4, 8
 FLAG_TIME_ATTN_ONLY = 16
 FLAG_STREAM_ORDERED_EVICT = 32
+FLAG_DEVICE_LAYER_MAJOR = 64
 K_CLASSES = ["norm", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gu", "swiglu",
              "gemm_d", "misc"]
 N_KCLASS = len(K_CLASSES)
@@ -53,7 +54,8 @@ SYMBOLS = [
     "pipemax_mb_define_alias", "pipemax_mb_alias_of",
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_decode_step_noalloc", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
-    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_probe_read", "pipemax_probe_link", "pipemax_get_config", "pipemax_mb_size",
+    "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_probe_read", "pipemax_probe_link",
+    "pipemax_probe_link_strided", "pipemax_get_config", "pipemax_mb_size",
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
     "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
@@ -201,6 +203,8 @@ _sig = {
     "pipemax_probe_read": (C.c_int, [_vp, C.c_size_t, C.c_int, _vp, _vp]),
     "pipemax_probe_link": (C.c_int, [C.c_int, C.c_size_t, C.c_size_t, C.c_size_t, C.c_int, C.c_int,
                                      C.POINTER(LinkProbe)]),
+    "pipemax_probe_link_strided": (C.c_int, [C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int,
+                                        C.POINTER(LinkProbe)]),
     "pipemax_get_ctx_lens": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_residency": (C.c_int, [_vp, C.c_int, _i32p]),
     "pipemax_get_block_table": (C.c_int, [_vp, C.c_int, C.c_int, _i32p, _i32p, C.POINTER(C.c_int)]),
@@ -416,6 +420,13 @@ def probe_link(total_bytes: int, piece_bytes: int, piece_stride: int | None = No
     out = LinkProbe()
     _check(_lib.pipemax_probe_link(device, total_bytes, piece_bytes, piece_stride or piece_bytes, direction, repeats,
                                    C.byref(out)))
+    return {k: getattr(out, k) for k, _ in LinkProbe._fields_}
+
+
+def probe_link_2d(row_bytes: int, host_pitch: int, rows_per_copy: int, n_copies: int, repeats: int = 3,
+                  device: int = 0) -> dict:
+    out = LinkProbe()
+    _check(_lib.pipemax_probe_link_strided(device, row_bytes, host_pitch, rows_per_copy, n_copies, repeats, C.byref(out)))
     return {k: getattr(out, k) for k, _ in LinkProbe._fields_}
 
 

@@ -11,7 +11,13 @@ struct Dims {
   float rope_base, eps;
   int max_pages;        // block-table row length
   int max_ctx_pad;      // row length of the generic attention's score scratch
-  int64_t page_elems;   // elements per page
+  int64_t page_elems;   // elements per page (all layers): the unit of the host replica and of a prefetch
+  // Device pool addressing: sub-block (page, layer, head, kv) starts at element
+  //   page * page_stride + layer * layer_stride + sub_block_off(Hkv, d, 0, head, kv).
+  // Block-first pool (the host replica's layout): page_stride = page_elems, layer_stride = one layer's block of a
+  // page.  Layer-major pool [layer][page]: page_stride = one layer's block, layer_stride = pages * that block, so
+  // that an attention launch (one layer) reads one contiguous tenth of the pool instead of 64 KiB out of every page.
+  int64_t page_stride, layer_stride;
 };
 
 // ---- shared small kernels ----------------------------------------------------------------------

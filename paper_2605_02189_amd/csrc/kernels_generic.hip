@@ -122,7 +122,7 @@ __global__ void k_rope_append(Dims D, int layer, const float* qkv, const float2*
   }
   int phys = table[(int64_t)i * D.max_pages + pos / kPageTokens];
   int slot = pos % kPageTokens;
-  T* sub = pool + (int64_t)phys * D.page_elems + sub_block_off(D.Hkv, D.d, layer, head, kv);
+  T* sub = pool + (int64_t)phys * D.page_stride + (int64_t)layer * D.layer_stride + sub_block_off(D.Hkv, D.d, 0, head, kv);
   if (kv == 0) {
     stf(sub + k_sub_idx(slot, j), lo);
     stf(sub + k_sub_idx(slot, j + half), hi);
@@ -151,8 +151,8 @@ __global__ void k_attention(Dims D, int layer, const float* q, const T* pool, co
   float scale = 1.0f / sqrtf((float)D.d);
   float mx = -INFINITY;
   for (int t = threadIdx.x; t < n_tok; t += blockDim.x) {
-    const T* sub = pool + (int64_t)trow[t / kPageTokens] * D.page_elems +
-                   sub_block_off(D.Hkv, D.d, layer, c, 0);
+    const T* sub = pool + (int64_t)trow[t / kPageTokens] * D.page_stride + (int64_t)layer * D.layer_stride +
+                   sub_block_off(D.Hkv, D.d, 0, c, 0);
     int slot = t % kPageTokens;
     float s = 0.f;
     for (int e = 0; e < D.d; ++e) s = fmaf(qs[e], ldf(sub + k_sub_idx(slot, e)), s);
@@ -172,8 +172,8 @@ __global__ void k_attention(Dims D, int layer, const float* q, const T* pool, co
   for (int e = threadIdx.x; e < D.d; e += blockDim.x) {
     float o = 0.f;
     for (int t = 0; t < n_tok; ++t) {
-      const T* sub = pool + (int64_t)trow[t / kPageTokens] * D.page_elems +
-                     sub_block_off(D.Hkv, D.d, layer, c, 1);
+      const T* sub = pool + (int64_t)trow[t / kPageTokens] * D.page_stride + (int64_t)layer * D.layer_stride +
+                     sub_block_off(D.Hkv, D.d, 0, c, 1);
       o = fmaf(sc[t], ldf(sub + v_sub_idx(t % kPageTokens, e)), o);
     }
     out[((int64_t)i * D.Hq + u) * D.d + e] = o * inv;

@@ -565,7 +565,7 @@ struct FusedArgs {
   uint16_t* staging;
   uint16_t* q_out;
   int Hq, Hkv, max_pages;
-  int64_t page_elems;
+  int64_t page_stride, layer_off;     // device pool addressing: see Dims (layer_off = layer * layer_stride)
 };
 
 template <int MT, int NWK, int U, int EPI, int MP>
@@ -728,7 +728,7 @@ __global__ __launch_bounds__(NWK * 64) void k_gemm_f(const uint4* __restrict__ X
             hi = b2;
           }
           const int slot = P.pos & 15;
-          uint16_t* sub = A.pool + (int64_t)P.phys * A.page_elems + sub_block_off(A.Hkv, 128, A.layer, head, kv);
+          uint16_t* sub = A.pool + (int64_t)P.phys * A.page_stride + A.layer_off + sub_block_off(A.Hkv, 128, 0, head, kv);
           const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
           if (kv == 0) {
             sub[k_sub_idx(slot, j)] = blo;
@@ -903,7 +903,7 @@ __global__ __launch_bounds__(64) void k_rope_append(Dims D, int layer, const flo
   }
   const int phys = table[(int64_t)i * D.max_pages + (pos >> 4)];
   const int slot = pos & 15;
-  uint16_t* sub = pool + (int64_t)phys * D.page_elems + sub_block_off(D.Hkv, 128, layer, head, kv);
+  uint16_t* sub = pool + (int64_t)phys * D.page_stride + (int64_t)layer * D.layer_stride + sub_block_off(D.Hkv, 128, 0, head, kv);
   const uint16_t blo = f2bf(lo), bhi = f2bf(hi);
   if (kv == 0) {
     sub[k_sub_idx(slot, j)] = blo;
@@ -983,7 +983,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
   // at most 64 pages per wave: the host keeps CP <= 64 * NW
   const int span = p1 - p0;
   const int npw = (span > w) ? ((span - w + NW - 1) / NW) : 0;
-  const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
+  const int64_t sub_off = (int64_t)layer * D.layer_stride + sub_block_off(D.Hkv, 128, 0, c, 0);
   const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
 
   float m_run = -INFINITY, l_run = 0.f;
@@ -995,7 +995,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
   uint4 kf[2][4], vf[2][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
     const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
-    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
+    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_stride + sub_off) + lane;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
 #pragma unroll
@@ -1175,7 +1175,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_prefill(Dims D, int layer, 
     for (int kk = 0; kk < 4; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + kk * 32));
   }
   const int npw = (npages > w) ? ((npages - w + NW - 1) / NW) : 0;
-  const int64_t sub_off = sub_block_off(D.Hkv, 128, layer, c, 0);
+  const int64_t sub_off = (int64_t)layer * D.layer_stride + sub_block_off(D.Hkv, 128, 0, c, 0);
   const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
 
   float m_run = -INFINITY, l_run = 0.f;
@@ -1190,7 +1190,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_prefill(Dims D, int layer, 
   uint4 kf[2][2][4], vf[2][2][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
     const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t < npw ? t : 0));
-    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_elems + sub_off) + lane;
+    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_stride + sub_off) + lane;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
 #pragma unroll
@@ -1548,7 +1548,8 @@ void gemm_qkv_rope_append(hipStream_t s, const Dims& D, int layer, int b, const 
   FusedArgs A{};
   A.counters = counters; A.ssq_in = ssq_in; A.n_ssq_in = n_ssq_in; A.inv_h = 1.0f / (float)D.h; A.eps = D.eps;
   A.layer = layer; A.cs = cs; A.ctx = ctx; A.table = table; A.pool = pool; A.staging = staging; A.q_out = q_out;
-  A.Hq = D.Hq; A.Hkv = D.Hkv; A.max_pages = D.max_pages; A.page_elems = D.page_elems;
+  A.Hq = D.Hq; A.Hkv = D.Hkv; A.max_pages = D.max_pages; A.page_stride = D.page_stride;
+  A.layer_off = (int64_t)layer * D.layer_stride;
   gemm_fused(s, EPI_QKV, xg_t, Wt, part, A, b, D.h, D.Nqkv, n_split, nwk);
 }
 

@@ -158,4 +158,64 @@ int pipemax_probe_link(int device, size_t total_bytes, size_t piece_bytes, size_
   return rc;
 }
 
+int pipemax_probe_link_strided(int device, size_t row_bytes, size_t host_pitch, int rows_per_copy, int n_copies,
+                          int repeats, pipemax_link_probe_t* out) {
+  if (!out || row_bytes == 0 || host_pitch < row_bytes || rows_per_copy < 1 || n_copies < 1 || repeats < 1 ||
+      repeats > 64 || n_copies > (1 << 20))
+    PMX_FAIL(PIPEMAX_ERR_ARG, "probe link 2d: pitch >= row > 0, rows >= 1, 1 <= copies <= 1M, 1 <= repeats <= 64");
+  const size_t rows = (size_t)rows_per_copy * n_copies;
+  const size_t h_span = rows * host_pitch, d_span = rows * row_bytes;
+  if (h_span > ((size_t)24 << 30)) PMX_FAIL(PIPEMAX_ERR_ARG, "probe link 2d: more than 24 GiB of host span");
+  memset(out, 0, sizeof(*out));
+  PMX_HIP(hipSetDevice(device));
+  void *h = nullptr, *d = nullptr;
+  hipStream_t s = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = PIPEMAX_OK;
+  hipError_t err;
+  auto fail = [&](int code, const char* what, hipError_t er) {
+    if (rc == PIPEMAX_OK) {
+      rc = code;
+      set_error("probe link 2d: %s failed: %s", what, hipGetErrorString(er));
+      (void)hipGetLastError();
+    }
+  };
+  if ((err = hipHostMalloc(&h, h_span, hipHostMallocDefault)) != hipSuccess) fail(PIPEMAX_ERR_OOM_HOST, "hipHostMalloc", err);
+  if (rc == PIPEMAX_OK && (err = hipMalloc(&d, d_span)) != hipSuccess) fail(PIPEMAX_ERR_OOM_DEVICE, "hipMalloc", err);
+  if (rc == PIPEMAX_OK) memset(h, 0x5a, h_span);
+  if (rc == PIPEMAX_OK && (err = hipStreamCreateWithFlags(&s, hipStreamNonBlocking)) != hipSuccess) fail(PIPEMAX_ERR_HIP, "hipStreamCreate", err);
+  if (rc == PIPEMAX_OK && (err = hipEventCreate(&e0)) != hipSuccess) fail(PIPEMAX_ERR_HIP, "hipEventCreate", err);
+  if (rc == PIPEMAX_OK && (err = hipEventCreate(&e1)) != hipSuccess) fail(PIPEMAX_ERR_HIP, "hipEventCreate", err);
+  double best = 0.0;
+  for (int rep = 0; rep <= repeats && rc == PIPEMAX_OK; ++rep) {
+    if ((err = hipDeviceSynchronize()) != hipSuccess) fail(PIPEMAX_ERR_HIP, "hipDeviceSynchronize", err);
+    const double t0 = now_s();
+    (void)hipEventRecord(e0, s);
+    for (int c = 0; c < n_copies && rc == PIPEMAX_OK; ++c)
+      if ((err = hipMemcpy2DAsync((char*)d + (size_t)c * rows_per_copy * row_bytes, row_bytes,
+                                  (char*)h + (size_t)c * rows_per_copy * host_pitch, host_pitch, row_bytes,
+                                  (size_t)rows_per_copy, hipMemcpyHostToDevice, s)) != hipSuccess)
+        fail(PIPEMAX_ERR_HIP, "hipMemcpy2DAsync", err);
+    (void)hipEventRecord(e1, s);
+    if (rc == PIPEMAX_OK && (err = hipDeviceSynchronize()) != hipSuccess) fail(PIPEMAX_ERR_HIP, "hipDeviceSynchronize", err);
+    const double wall = now_s() - t0;
+    if (rep == 0 || rc != PIPEMAX_OK) continue;
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    if (best == 0.0 || wall < best) {
+      best = wall;
+      out->wall_s = wall;
+      out->h2d_s = ms * 1e-3;
+    }
+  }
+  out->pieces = (uint64_t)n_copies;
+  out->h2d_bytes = d_span;
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (s) (void)hipStreamDestroy(s);
+  if (h) (void)hipHostFree(h);
+  if (d) (void)hipFree(d);
+  return rc;
+}
+
 }  // extern "C"

@@ -186,6 +186,7 @@ struct pipemax_stage {
   int engine = 0;
   size_t esz = 4;
   size_t page_bytes = 0;
+  size_t layer_block_bytes = 0;     // one layer's K,V of one page
   int dev = 0;
   hipStream_t s_own = nullptr, s_h2d = nullptr, s_d2h = nullptr, s_last = nullptr;
   void* gpu_pool = nullptr;
@@ -336,7 +337,13 @@ struct pipemax_stage {
     timed.swap(keep);
   }
   char* host_page_ptr(int32_t page) const { return (char*)host_pool + (size_t)page * page_bytes; }
+  bool layer_major() const { return cfg.flags & PIPEMAX_FLAG_DEVICE_LAYER_MAJOR; }
+  // a whole page on the device: block-first pools only
   char* gpu_page_ptr(int32_t page) const { return (char*)gpu_pool + (size_t)page * page_bytes; }
+  // one layer's block of a page on the device, either pool layout
+  char* gpu_block_ptr(int32_t page, int layer) const {
+    return (char*)gpu_pool + ((size_t)page * D.page_stride + (size_t)layer * D.layer_stride) * esz;
+  }
   void wait_mb_writeback(int mb) {
     std::unique_lock<std::mutex> lk(mu);
     if (mbs[mb].wb_pending == 0) return;
@@ -578,9 +585,20 @@ void pf_worker_main(pipemax_stage* st) {
       }
       if (job.timed && !t.a && (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess)) t.a = t.b = nullptr;
       if (t.a) fail_hip(hipEventRecord(t.a, st->s_h2d), "hipEventRecord");
-      for (const CopyRun& r : job.runs)
-        fail_hip(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
-                                hipMemcpyHostToDevice, st->s_h2d), "hipMemcpyAsync");
+      if (st->layer_major()) {
+        // block-first host pages into the [layer][page] pool: per run one strided copy per layer (rows = pages,
+        // one page apart in host memory, packed on the device)
+        for (const CopyRun& r : job.runs)
+          for (int l = 0; l < st->cfg.n_layers; ++l)
+            fail_hip(hipMemcpy2DAsync(st->gpu_block_ptr(r.dst, l), st->layer_block_bytes,
+                                      st->host_page_ptr(r.src) + (size_t)l * st->layer_block_bytes, st->page_bytes,
+                                      st->layer_block_bytes, (size_t)r.count, hipMemcpyHostToDevice, st->s_h2d),
+                     "hipMemcpy2DAsync");
+      } else {
+        for (const CopyRun& r : job.runs)
+          fail_hip(hipMemcpyAsync(st->gpu_page_ptr(r.dst), st->host_page_ptr(r.src), (size_t)r.count * st->page_bytes,
+                                  hipMemcpyHostToDevice, st->s_h2d), "hipMemcpyAsync");
+      }
       if (t.a) {
         fail_hip(hipEventRecord(t.b, st->s_h2d), "hipEventRecord");
         std::lock_guard<std::mutex> lk(st->mu);
@@ -833,12 +851,23 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
   D.max_ctx_pad = D.max_pages * kPageTokens;
   D.page_elems = page_elems(c.n_layers, c.n_kv_heads, c.head_dim);
   st->page_bytes = (size_t)D.page_elems * st->esz;
+  st->layer_block_bytes = st->page_bytes / c.n_layers;
   st->engine = (mfma_shape_ok(c) && !(c.flags & PIPEMAX_FLAG_FORCE_GENERIC)) ? 1 : 0;
   const int n_gpu_pages = (int)std::min<uint64_t>(c.gpu_kv_bytes / st->page_bytes, 1u << 30);
   const int n_host_pages = (int)std::min<uint64_t>(c.host_kv_bytes / st->page_bytes, 1u << 30);
   if (n_gpu_pages < 1 || n_host_pages < 1) {
     delete st;
     PMX_FAIL(PIPEMAX_ERR_ARG, "pools must hold at least one page of %zu bytes", st->page_bytes);
+  }
+  {
+    const int64_t block = D.page_elems / c.n_layers;      // one layer's K,V of one page
+    if (c.flags & PIPEMAX_FLAG_DEVICE_LAYER_MAJOR) {
+      D.page_stride = block;
+      D.layer_stride = (int64_t)n_gpu_pages * block;
+    } else {
+      D.page_stride = D.page_elems;
+      D.layer_stride = block;
+    }
   }
 
 #define PMX_TRY(expr)           \
@@ -1227,7 +1256,7 @@ int pipemax_kv_dev_read(pipemax_stage_t* st, int mb, int seq, int layer, int tok
     const int tok = tok0 + t, pi = tok / kPageTokens;
     if (pi != cached) {
       const size_t off = (size_t)sub_block_off(Hkv, d, layer, 0, 0) * st->esz;
-      PMX_HIP(hipMemcpy(tmp.data() + off, st->gpu_page_ptr(S.gpu[pi]) + off, layer_bytes, hipMemcpyDeviceToHost));
+      PMX_HIP(hipMemcpy(tmp.data() + off, st->gpu_block_ptr(S.gpu[pi], layer), layer_bytes, hipMemcpyDeviceToHost));
       cached = pi;
     }
     if (st->esz == 4)
@@ -1279,10 +1308,11 @@ int pipemax_prefetch_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int
   M.table_dirty = true;
   PfJob job;
   job.mb = mb;
-  plan_copy_runs(src.data(), dst.data(), (int)src.size(), kMaxRunPages, job.runs);
+  // a layer-major pool takes a run as n_layers strided copies of count x 64 KiB: longer runs keep each copy large
+  plan_copy_runs(src.data(), dst.data(), (int)src.size(), st->layer_major() ? 8 * kMaxRunPages : kMaxRunPages, job.runs);
   for (const CopyRun& r : job.runs) {
     st->st.h2d_bytes += (uint64_t)r.count * st->page_bytes;
-    st->st.h2d_copies += 1;
+    st->st.h2d_copies += st->layer_major() ? st->cfg.n_layers : 1;
   }
   // the pages freed by earlier evictions may still be read by the evicted micro-batches' last steps
   job.release.swap(st->release_wait);
@@ -1903,6 +1933,8 @@ int pipemax_sync(pipemax_stage_t* st) {
 // ---- introspection ---------------------------------------------------------------------------------------
 int pipemax_stage_attach_xfer(pipemax_stage_t* st, pipemax_xfer_t* x) {
   if (!st) PMX_FAIL(PIPEMAX_ERR_ARG, "null stage");
+  if (x && st->layer_major())
+    PMX_FAIL(PIPEMAX_ERR_STATE, "a transfer orchestrator moves contiguous pieces; it cannot feed a layer-major GPU pool");
   int rc = pipemax_sync(st);
   if (rc) return rc;
   st->xfer = x;
@@ -1971,8 +2003,14 @@ int pipemax_debug_fill_free_gpu_pages(pipemax_stage_t* st, uint16_t pattern) {
     const bool fr = (p < total) && st->gpu_pages->is_free(p);
     if (fr && run0 < 0) run0 = p;
     if (!fr && run0 >= 0) {
-      PMX_HIP(hipMemsetD16Async((hipDeviceptr_t)st->gpu_page_ptr(run0), pattern,
-                                (size_t)(p - run0) * st->page_bytes / 2, st->s_own));
+      if (st->layer_major()) {
+        for (int l = 0; l < st->cfg.n_layers; ++l)
+          PMX_HIP(hipMemsetD16Async((hipDeviceptr_t)st->gpu_block_ptr(run0, l), pattern,
+                                    (size_t)(p - run0) * st->layer_block_bytes / 2, st->s_own));
+      } else {
+        PMX_HIP(hipMemsetD16Async((hipDeviceptr_t)st->gpu_page_ptr(run0), pattern,
+                                  (size_t)(p - run0) * st->page_bytes / 2, st->s_own));
+      }
       run0 = -1;
     }
   }

@@ -238,6 +238,47 @@ def test_bf16_wide_batch(rows):
     runner.stage.destroy()
 
 
+@pytest.mark.parametrize("engine", ["mfma_bf16", "generic_fp32"])
+def test_layer_major_device_pool(engine):
+    """PIPEMAX_FLAG_DEVICE_LAYER_MAJOR: the GPU pool laid out [layer][page] while the host replica and the link
+    keep block-first pages (a prefetch scatters every page run with one strided copy per layer).  Same parity
+    bars, same bit-exact bookkeeping, prefix and replica checks as the block-first pool; the outputs of the two
+    layouts are bit-identical (the layout changes where bytes live, nothing else)."""
+    torch = _torch()
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    if engine == "mfma_bf16":
+        shape, tl, td = _mid_shape(n_layers=3), 1e-2, 3e-2
+    else:
+        shape, tl, td = CONFIGS["C1"].with_(decode_steps=9, n_microbatches=3), 1e-5, 2e-4
+    outs = {}
+    for flag in (pm.FLAG_DEVICE_LAYER_MAJOR, 0):
+        syn = SynthInputs(shape, seed=2, pool_elems=1 << 23, gain_jitter=0.1)
+        ctx = _ragged_ctx(shape, syn) if engine == "mfma_bf16" else None
+        runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS | flag, ctx_lens=ctx).load()
+        assert runner.stage.get_stats()["engine"] == (1 if engine == "mfma_bf16" else 0)
+        if flag:
+            orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=tl, tol_delta=td)
+            check_tables(runner)
+            _check_replica(runner, syn, shape, orc, tol_new=tl)
+            runner.stage.debug_fill_free_gpu_pages(0x7FC0)          # the poison lands in free pages only
+            _check_replica(runner, syn, shape, orc, tol_new=tl)
+        else:
+            runner.warm_start()
+            for t in range(shape.decode_steps):
+                hin = runner.hidden_tensor(t, t % runner.n)
+                runner.step(hin, torch.empty_like(hin))
+        hin = runner.hidden_tensor(99, 0)
+        hout = torch.empty_like(hin)
+        runner.stage.prefetch_kv(0)
+        runner.stage.decode_step(0, hin.data_ptr(), hout.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        runner.stage.sync()
+        outs[flag] = hout.float().cpu().numpy()
+        runner.stage.destroy()
+    np.testing.assert_array_equal(outs[pm.FLAG_DEVICE_LAYER_MAJOR], outs[0])
+
+
 def test_bf16_generic_path_matches_oracle_and_matrix_core_path():
     """The same bf16 workload on the shape-generic kernels (fp32 activations)."""
     from paper_2605_02189_amd import binding as pm
