@@ -161,6 +161,13 @@ def run_probes(args):
         log("link piece", label, pieces[label])
     link["h2d_by_piece"] = pieces
     out["link_gbs"] = link
+    launch = {}
+    for label, graph in (("one_by_one", False), ("captured_graph", True)):
+        r = pm.probe_launch(41, graph, repeats=50)          # 41 = the launches of an 8-layer fused decode step
+        launch[label] = {"host_enqueue_us_per_kernel": round(r["host_enqueue_s"] / 41 * 1e6, 2),
+                         "gpu_us_per_kernel": round(r["gpu_s"] / 41 * 1e6, 2)}
+    out["launch_chain_of_41_dependent_one_wave_kernels"] = launch
+    log("launch:", json.dumps(launch))
     out["link_peak_nominal_gbs"] = LINK_PEAK_GBS
     out["hbm_peak_nominal_gbs"] = HBM_PEAK_GBS
     print(json.dumps(out), flush=True)

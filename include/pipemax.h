@@ -361,6 +361,16 @@ int pipemax_probe_link(int device, size_t total_bytes, size_t piece_bytes, size_
 int pipemax_probe_link_strided(int device, size_t row_bytes, size_t host_pitch, int rows_per_copy, int n_copies,
                           int repeats, pipemax_link_probe_t* out);
 
+/* Launch-overhead probe: a chain of n_kernels one-wave kernels, each depending on its predecessor, enqueued one by
+ * one (use_graph = 0) or replayed as one captured HIP graph (use_graph = 1); `repeats` passes after a warm-up, the
+ * fastest reported.  host_enqueue_s: host time to hand the chain to the runtime; gpu_s: first kernel's start to last
+ * kernel's end (HIP events around the chain).  Checks that every kernel ran.  Synchronises its own stream.       */
+typedef struct {
+  double   host_enqueue_s, gpu_s;
+  uint64_t kernels;
+} pipemax_launch_probe_t;
+int pipemax_probe_launch(int device, int n_kernels, int use_graph, int repeats, pipemax_launch_probe_t* out);
+
 /* ---- host-side planning helpers (pure host code; also used by the CPU tests) ------------- */
 
 /* Element offset, inside one KV page, of element `dd` of token slot `tok` (0..15) of head

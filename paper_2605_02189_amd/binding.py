@@ -55,7 +55,7 @@ SYMBOLS = [
     "pipemax_kv_host_write", "pipemax_kv_host_read", "pipemax_kv_dev_read", "pipemax_prefetch_kv",
     "pipemax_decode_step", "pipemax_decode_step_noalloc", "pipemax_decode_step_seqs", "pipemax_prefill", "pipemax_evict_kv", "pipemax_sync", "pipemax_get_stats",
     "pipemax_reset_stats", "pipemax_set_flags", "pipemax_probe_copy", "pipemax_probe_read", "pipemax_probe_link",
-    "pipemax_probe_link_strided", "pipemax_get_config", "pipemax_mb_size",
+    "pipemax_probe_link_strided", "pipemax_probe_launch", "pipemax_get_config", "pipemax_mb_size",
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
     "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
@@ -115,6 +115,10 @@ _vp, _i32p = C.c_void_p, C.POINTER(C.c_int32)
 class LinkProbe(C.Structure):
     _fields_ = [("h2d_s", C.c_double), ("d2h_s", C.c_double), ("wall_s", C.c_double),
                 ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64), ("pieces", C.c_uint64)]
+
+
+class LaunchProbe(C.Structure):
+    _fields_ = [("host_enqueue_s", C.c_double), ("gpu_s", C.c_double), ("kernels", C.c_uint64)]
 
 
 class XferConfig(C.Structure):
@@ -203,6 +207,7 @@ _sig = {
     "pipemax_probe_read": (C.c_int, [_vp, C.c_size_t, C.c_int, _vp, _vp]),
     "pipemax_probe_link": (C.c_int, [C.c_int, C.c_size_t, C.c_size_t, C.c_size_t, C.c_int, C.c_int,
                                      C.POINTER(LinkProbe)]),
+    "pipemax_probe_launch": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(LaunchProbe)]),
     "pipemax_probe_link_strided": (C.c_int, [C.c_int, C.c_size_t, C.c_size_t, C.c_int, C.c_int, C.c_int,
                                         C.POINTER(LinkProbe)]),
     "pipemax_get_ctx_lens": (C.c_int, [_vp, C.c_int, _i32p]),
@@ -421,6 +426,12 @@ def probe_link(total_bytes: int, piece_bytes: int, piece_stride: int | None = No
     _check(_lib.pipemax_probe_link(device, total_bytes, piece_bytes, piece_stride or piece_bytes, direction, repeats,
                                    C.byref(out)))
     return {k: getattr(out, k) for k, _ in LinkProbe._fields_}
+
+
+def probe_launch(n_kernels: int, use_graph: bool, repeats: int = 20, device: int = 0) -> dict:
+    out = LaunchProbe()
+    _check(_lib.pipemax_probe_launch(device, n_kernels, int(use_graph), repeats, C.byref(out)))
+    return {k: getattr(out, k) for k, _ in LaunchProbe._fields_}
 
 
 def probe_link_2d(row_bytes: int, host_pitch: int, rows_per_copy: int, n_copies: int, repeats: int = 3,

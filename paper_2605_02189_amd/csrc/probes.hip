@@ -46,6 +46,11 @@ __global__ __launch_bounds__(256) void k_probe_read(const uint4* __restrict__ sr
   if ((acc.x ^ acc.y) == 0x9E3779B9u && (acc.z ^ acc.w) == 0x7F4A7C15u && acc.x == 0x12345u) *sink = acc;
 }
 
+// one wave that adds 1 to a counter: the shortest kernel that still depends on its predecessor
+__global__ void k_probe_tick(unsigned* p) {
+  if (threadIdx.x == 0) *p += 1u;
+}
+
 double now_s() {
   return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
@@ -214,6 +219,78 @@ int pipemax_probe_link_strided(int device, size_t row_bytes, size_t host_pitch, 
   if (e1) (void)hipEventDestroy(e1);
   if (s) (void)hipStreamDestroy(s);
   if (h) (void)hipHostFree(h);
+  if (d) (void)hipFree(d);
+  return rc;
+}
+
+int pipemax_probe_launch(int device, int n_kernels, int use_graph, int repeats, pipemax_launch_probe_t* out) {
+  if (!out || n_kernels < 1 || n_kernels > 4096 || repeats < 1 || repeats > 1000)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "probe launch: 1 <= kernels <= 4096, 1 <= repeats <= 1000");
+  memset(out, 0, sizeof(*out));
+  PMX_HIP(hipSetDevice(device));
+  unsigned* d = nullptr;
+  hipStream_t s = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  int rc = PIPEMAX_OK;
+  auto fail = [&](const char* what, hipError_t er) {
+    if (rc == PIPEMAX_OK && er != hipSuccess) {
+      rc = PIPEMAX_ERR_HIP;
+      set_error("probe launch: %s failed: %s", what, hipGetErrorString(er));
+      (void)hipGetLastError();
+    }
+  };
+  fail("hipMalloc", hipMalloc((void**)&d, 256));
+  if (rc == PIPEMAX_OK) fail("hipMemset", hipMemset(d, 0, 256));
+  if (rc == PIPEMAX_OK) fail("hipStreamCreate", hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+  if (rc == PIPEMAX_OK) fail("hipEventCreate", hipEventCreate(&e0));
+  if (rc == PIPEMAX_OK) fail("hipEventCreate", hipEventCreate(&e1));
+  auto enqueue = [&]() {
+    for (int k = 0; k < n_kernels; ++k) hipLaunchKernelGGL(k_probe_tick, dim3(1), dim3(64), 0, s, d);
+  };
+  if (rc == PIPEMAX_OK && use_graph) {
+    fail("hipStreamBeginCapture", hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    if (rc == PIPEMAX_OK) {
+      enqueue();
+      fail("hipStreamEndCapture", hipStreamEndCapture(s, &graph));
+    }
+    if (rc == PIPEMAX_OK) fail("hipGraphInstantiate", hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+  }
+  double host_best = 0.0, gpu_best = 0.0;
+  unsigned launched = 0;
+  for (int rep = 0; rep <= repeats && rc == PIPEMAX_OK; ++rep) {      // pass 0 is a warm-up
+    fail("hipStreamSynchronize", hipStreamSynchronize(s));
+    (void)hipEventRecord(e0, s);
+    const double t0 = now_s();
+    if (use_graph) fail("hipGraphLaunch", hipGraphLaunch(exec, s));
+    else enqueue();
+    const double host = now_s() - t0;
+    (void)hipEventRecord(e1, s);
+    fail("hipStreamSynchronize", hipStreamSynchronize(s));
+    launched += (unsigned)n_kernels;
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    if (rep == 0) continue;
+    if (host_best == 0.0 || host < host_best) host_best = host;
+    if (gpu_best == 0.0 || ms * 1e-3 < gpu_best) gpu_best = ms * 1e-3;
+  }
+  if (rc == PIPEMAX_OK) {
+    unsigned got = 0;
+    fail("hipMemcpy", hipMemcpy(&got, d, sizeof(got), hipMemcpyDeviceToHost));
+    if (rc == PIPEMAX_OK && got != launched) {
+      rc = PIPEMAX_ERR_HIP;
+      set_error("probe launch: %u kernels ran, %u were launched", got, launched);
+    }
+  }
+  out->host_enqueue_s = host_best;
+  out->gpu_s = gpu_best;
+  out->kernels = (uint64_t)n_kernels;
+  if (exec) (void)hipGraphExecDestroy(exec);
+  if (graph) (void)hipGraphDestroy(graph);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (s) (void)hipStreamDestroy(s);
   if (d) (void)hipFree(d);
   return rc;
 }

@@ -1393,6 +1393,10 @@ int attention_plan(const pipemax_stage* st, int b, int max_len, int64_t sum_page
     CP = std::min(CP, (npages_max + nch_long - 1) / nch_long);
   }
   CP = std::max(8, std::min(64 * mfma::kAttnWaves, CP));
+  // Even chunks: a context one page longer than a work-group takes (4097 tokens = 257 pages against 256) must not
+  // become one full chunk and a one-page chunk -- 2048 work-groups of 256 pages run as four long rounds whose tail
+  // idles, while 4096 of 129 pages balance (measured, 256 sequences of 4097 tokens: 880 -> 765 us per launch).
+  CP = std::max(8, (npages_max + (npages_max + CP - 1) / CP - 1) / ((npages_max + CP - 1) / CP));
   if (st->attn_cp_override > 0) CP = std::max(8, std::min(64 * mfma::kAttnWaves, st->attn_cp_override));
   *cp_out = CP;
   return std::min(st->nch_alloc, (npages_max + CP - 1) / CP);

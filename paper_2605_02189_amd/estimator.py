@@ -29,10 +29,15 @@ class DecodeTimeModel:
 
 
 def fit(b, L, t) -> DecodeTimeModel:
-    """Least-squares fit of t ~ alpha*b + beta*L + delta."""
+    """Least-squares fit of t ~ alpha*b + beta*L + delta with alpha, beta, delta >= 0: each term of the model is a
+    cost (per request, per cached token, per step), and on a profiling grid where the total length grows with the
+    batch size an unconstrained fit can trade a slightly negative alpha against beta."""
+    from scipy.optimize import nnls
     b, L, t = (np.asarray(a, dtype=np.float64) for a in (b, L, t))
     A = np.stack([b, L, np.ones_like(b)], axis=1)
-    (alpha, beta, delta), *_ = np.linalg.lstsq(A, t, rcond=None)
+    scale = np.maximum(np.abs(A).max(axis=0), 1e-300)        # columns of comparable size for the solver
+    x, _ = nnls(A / scale, t)
+    alpha, beta, delta = x / scale
     return DecodeTimeModel(float(alpha), float(beta), float(delta))
 
 

@@ -1,6 +1,7 @@
 """The decode-time estimator on the GPU (Sec. 3.3.1, Eq. 2; the bar of Sec. 4.3: actual / predicted over 100
 consecutive decode steps, more than 90 % of them within 5 % and the worst below 8 %) and the prefetch budget it
-feeds (Sec. 3.3.2, Eq. 6), on a 4-layer slice of the 8B-shaped stage: the model is fitted by least squares on step
+feeds (Sec. 3.3.2, Eq. 6), on the 8B-shaped stage (8 layers: with fewer the time of a step that is enqueued and
+awaited on its own is the host's launch time, not the GPU's): the model is fitted by least squares on step
 times of six ragged profiling batches (two batch sizes x three length ranges) and then checked on 100 consecutive
 steps of a ragged batch that was not part of the fit, during which its total length grows by 6400 tokens."""
 import numpy as np
@@ -17,7 +18,7 @@ def test_fitted_model_predicts_100_consecutive_steps_of_an_unseen_batch():
     from paper_2605_02189_amd.harness import StageRunner
     from paper_2605_02189_amd.synth_inputs import CONFIGS, SynthInputs
 
-    base = CONFIGS["C2"].with_(n_layers=4)
+    base = CONFIGS["C2"]
     grid = [(b, L) for b in (16, 64) for L in ((256, 1024), (256, 4096), (1024, 4096))]
     n = len(grid) + 1
     rng = np.random.default_rng(0)

@@ -268,7 +268,9 @@ def test_layer_major_device_pool(engine):
             runner.warm_start()
             for t in range(shape.decode_steps):
                 hin = runner.hidden_tensor(t, t % runner.n)
-                runner.step(hin, torch.empty_like(hin))
+                hout = torch.empty_like(hin)
+                runner.step(hin, hout)
+                runner.stage.sync()           # a step is only enqueued: its tensors must outlive it
         hin = runner.hidden_tensor(99, 0)
         hout = torch.empty_like(hin)
         runner.stage.prefetch_kv(0)
