@@ -33,6 +33,13 @@ __device__ inline uint4 ld_stream(const uint4* p) {
 // executes as write-through stores / coherent loads, so publishing them needs only "wait until my
 // stores are acknowledged" before the arrival counter is bumped, not a write-back or invalidation
 // of the whole L2 (which is what a device-wide fence costs: ~45 us per kernel when measured here).
+// The language memory model asks for more than this relies on (a release at agent scope on the arrival and an
+// acquire at agent scope in the last arriver; measured: +3 us on every split GEMM launch, +5 % per step at 64
+// rows).  What is relied on instead is the hardware's behaviour: (1) an agent-scope atomic store is performed at
+// the level all XCDs share, not in the issuing XCD's L2; (2) s_waitcnt 0 returns only when those stores have been
+// acknowledged there; (3) an agent-scope atomic load is served from that level, never from a stale L2 line.  The
+// partial buffers are touched by nothing but these atomics while a kernel runs, so no ordinary cached copy of them
+// exists.  A run-to-run bit-exactness test of the many-chunk merges guards the contract.
 __device__ inline void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -734,3 +734,56 @@ def test_alias_microbatches_move_the_same_bytes():
                         np.testing.assert_array_equal(Vh, V0)
         st.destroy()
     assert traffic[2] == traffic[4]
+
+
+def test_split_merges_are_bit_identical_from_run_to_run():
+    """The in-kernel merges of split-K partials (GEMM splits summed by the last arriving work-group, attention chunks
+    merged by the last arriver of a (sequence, KV head)) publish their partials with agent-scope atomics and an
+    arrival counter instead of a device-wide fence.  Whatever the arrival order, the sums are taken in split order,
+    so the same inputs must give the same bits every time, also with thousands of work-groups of all XCDs in flight:
+    a stale or torn partial would show as a differing bit.  40 consecutive steps, each with 2 to 4 GEMM splits over 64 to 96 column
+    blocks and up to 24 attention chunks per sequence (one 3000-token context among short ones, 8-page chunks)."""
+    torch = _torch()
+    import os
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(n_layers=2, n_microbatches=1, seqs_per_mb=48, decode_steps=2, ctx_lo=100, ctx_hi=900,
+                       hidden=4096, n_q_heads=32, n_kv_heads=8, ffn=14336 // 2)
+    syn = SynthInputs(shape, seed=12, pool_elems=1 << 23, gain_jitter=0.1)
+    ctx = {0: syn.ctx_lens(0).copy()}
+    ctx[0][0] = 3000
+    os.environ["PIPEMAX_ATTN_CHUNK_PAGES"] = "8"
+    try:
+        runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
+                             flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
+    finally:
+        del os.environ["PIPEMAX_ATTN_CHUNK_PAGES"]
+    st = runner.stage
+    assert st.get_stats()["engine"] == 1
+    st.prefetch_kv(0)
+    cur = torch.cuda.current_stream().cuda_stream
+    hin = runner.hidden_tensor(0, 0)
+    outs = [torch.empty_like(hin) for _ in range(40)]
+    for hout in outs:                # every repetition appends a token; the twin run below repeats the same 40 steps
+        st.decode_step(0, hin.data_ptr(), hout.data_ptr(), cur)
+    st.sync()
+    a = [o.cpu().view(torch.int16).numpy().copy() for o in outs]
+    st.destroy()
+    # the twin run: same inputs, same 40 steps, a fresh stage; step r of both runs must agree bit for bit
+    os.environ["PIPEMAX_ATTN_CHUNK_PAGES"] = "8"
+    try:
+        runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
+                             flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
+    finally:
+        del os.environ["PIPEMAX_ATTN_CHUNK_PAGES"]
+    st = runner.stage
+    st.prefetch_kv(0)
+    outs = [torch.empty_like(hin) for _ in range(40)]
+    for hout in outs:
+        st.decode_step(0, hin.data_ptr(), hout.data_ptr(), cur)
+    st.sync()
+    for r, o in enumerate(outs):
+        np.testing.assert_array_equal(o.cpu().view(torch.int16).numpy(), a[r], err_msg=f"step {r} differs between two runs")
+    assert np.isfinite(np.stack([x.view(np.uint16).astype(np.uint32) << 16 for x in a]).view(np.float32)).all()
+    st.destroy()
