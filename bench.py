@@ -193,7 +193,7 @@ def run_config(name, args, *, light=False):
     kv_guess = b * (shape.ctx_lo + shape.ctx_hi) // 2 * shape.kv_bytes_per_token
     sweep_cycles = max(2, min(24, int(0.15 / ((shape.weight_bytes + kv_guess) / 5e12) / n + 0.5)))
     total_steps = ((W + K) + (0 if args.no_legs else 2 * n + 3 * Kc + 2 * n)
-                   + len(sweep_sigmas) * (1 + sweep_cycles) * n + 2 * n)
+                   + len(sweep_sigmas) * (2 + sweep_cycles) * n + 2 * n)
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
@@ -375,10 +375,18 @@ def run_config(name, args, *, light=False):
             est = max(t_c, ns * per_seq * shape.page_bytes / (link_gbs * 1e9))
             ks = n * max(2, min(sweep_cycles, int(0.15 / est / n + 0.5)))
             dts, ss = timed_steps(ks)
-            sweep.append({"sigma": sg, "feasible": True, "streamed_seqs_per_mb": ns, "steps": ks,
-                          "ms_per_step": round(dts / ks * 1e3, 3),
-                          "h2d_gb_per_step": round(ss["h2d_bytes"] / ks / 1e9, 4),
-                          "host_wait_s": round(ss["host_wait_s"], 4)})
+            row = {"sigma": sg, "feasible": True, "streamed_seqs_per_mb": ns, "steps": ks,
+                   "ms_per_step": round(dts / ks * 1e3, 3),
+                   "h2d_gb_per_step": round(ss["h2d_bytes"] / ks / 1e9, 4),
+                   "host_wait_s": round(ss["host_wait_s"], 4)}
+            # one more cycle with the attention launches and the wait for the prefetch timed (dispatch stamps and
+            # events on the compute stream): where a step that is longer than the compute-only one loses its time
+            st.set_flags(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY, 0)
+            _, sd = timed_steps(n)
+            st.set_flags(0, pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY)
+            row["attn_us_per_launch"] = round(sd["kernel_ms"]["attn"] / max(sd["kernel_launches"]["attn"], 1) * 1e3, 2)
+            row["prefetch_stall_ms_per_step"] = round(sd["prefetch_stall_ms"] / n, 4)
+            sweep.append(row)
             log("sweep:", json.dumps(sweep[-1]))
         for p in sweep:
             if not p["feasible"]:

@@ -147,6 +147,10 @@ typedef struct {
                                      of 256; every other stage runs on the generic kernels.        */
   int32_t  gpu_pages_total, gpu_pages_free, host_pages_total, host_pages_free;
   uint64_t page_bytes;
+  double   prefetch_stall_ms;     /* compute-stream time spent waiting for a step's prefetch to land: from the
+                                     moment the stream reaches the wait (the previous work has ended) to the
+                                     moment it passes it (FLAG_TIME_KERNELS, also with TIME_ATTN_ONLY)          */
+  uint64_t prefetch_stalls;       /* steps that had such a wait                                              */
 } pipemax_stats_t;
 
 /* ---- life cycle ----------------------------------------------------------------------- */

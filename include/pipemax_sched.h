@@ -114,11 +114,12 @@ int pipemax_sched_attach(pipemax_sched_t* s, pipemax_stage_t* stage);
 int pipemax_sched_plan(pipemax_sched_t* s, int64_t t, pipemax_sched_iter_t* out, int32_t* exec_ids,
                        int32_t* prefetch_ids, int32_t* evict_ids);
 
-/* The same iteration applied to the attached stage: pipemax_decode_step_seqs on D_i (rows in
- * ascending request index; hidden_in / hidden_out are device pointers with room for
- * max_seqs_per_mb rows, of which the first n_exec are used), then pipemax_evict_kv on the released
- * requests of D_k, then pipemax_prefetch_kv of P_t into D_j.  The step is enqueued before the
- * transfers so that the host-side wait of the prefetch overlaps it.  Afterwards the mirror's free
+/* The same iteration applied to the attached stage: pipemax_evict_kv on the released requests of
+ * D_k, pipemax_prefetch_kv of P_t into D_j, then pipemax_decode_step_seqs on D_i (rows in ascending
+ * request index; hidden_in / hidden_out are device pointers with room for max_seqs_per_mb rows, of
+ * which the first n_exec are used).  None of the three blocks; the transfers are arranged first so
+ * that their copies start when the previous step ends, not after this one has been enqueued.
+ * Afterwards the mirror's free
  * page count is checked against the stage's (ERR_STATE if they differ).  Other errors: those of
  * the stage calls, passed through; the mirror is then put back to its state before the call, and if the
  * failing call was not the first of the three the stage has moved on without it: attach again.     */

@@ -100,7 +100,7 @@ class Stats(C.Structure):
                 ("kernel_ms", C.c_double * N_KCLASS), ("kernel_launches", C.c_uint64 * N_KCLASS),
                 ("engine", C.c_int32), ("gpu_pages_total", C.c_int32), ("gpu_pages_free", C.c_int32),
                 ("host_pages_total", C.c_int32), ("host_pages_free", C.c_int32),
-                ("page_bytes", C.c_uint64)]
+                ("page_bytes", C.c_uint64), ("prefetch_stall_ms", C.c_double), ("prefetch_stalls", C.c_uint64)]
 
     def as_dict(self):
         d = {n: getattr(self, n) for n, _ in self._fields_ if n not in ("kernel_ms", "kernel_launches")}

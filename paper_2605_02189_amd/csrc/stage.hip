@@ -55,7 +55,7 @@ constexpr int kSlots = 4;        // depth of the write-back staging ring
 constexpr int kTableRing = 8;    // depth of the block-table upload ring
 constexpr int kMaxRunPages = 128;  // longest single prefetch copy, in pages (64 MiB at 512 KiB pages)
 enum { ST_HOST = 0, ST_INFLIGHT = 1, ST_GPU = 2 };
-enum { TC_H2D = PIPEMAX_N_KCLASS, TC_D2H = PIPEMAX_N_KCLASS + 1 };
+enum { TC_H2D = PIPEMAX_N_KCLASS, TC_D2H = PIPEMAX_N_KCLASS + 1, TC_STALL = PIPEMAX_N_KCLASS + 2 };
 
 double now_s() {
   return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
@@ -94,6 +94,14 @@ void* scratch_base(int dev) {
 __global__ void k_clear16(uint4* p, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// copies n 32-bit words from pinned host memory (device-visible) to device memory.  The block table of a step goes
+// up this way, by the compute units over the link, not as a host-to-device copy: such a copy would queue on the
+// same DMA engine as the KV prefetch and wait behind whatever part of it has been submitted, holding the step up.
+__global__ void k_upload_words(int32_t* __restrict__ dst, const int32_t* __restrict__ src, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
 // The device buffers a step works in besides its inputs, outputs, weights and KV pages (matrix-core engine).
@@ -269,7 +277,7 @@ struct pipemax_stage {
   void tbegin(int cls, hipStream_t s) {
     t_open = false;
     if (!timing()) return;
-    if ((cfg.flags & PIPEMAX_FLAG_TIME_ATTN_ONLY) && cls != PIPEMAX_K_ATTN) return;
+    if ((cfg.flags & PIPEMAX_FLAG_TIME_ATTN_ONLY) && cls != PIPEMAX_K_ATTN && cls != TC_STALL) return;
     if (timed.size() >= 4096) resolve_timers(true);
     Timed t{cls, get_event(), get_event()};
     if (!t.a || !t.b) return;
@@ -325,6 +333,9 @@ struct pipemax_stage {
         if (t.cls < PIPEMAX_N_KCLASS) {
           st.kernel_ms[t.cls] += ms;
           st.kernel_launches[t.cls] += 1;
+        } else if (t.cls == TC_STALL) {
+          st.prefetch_stall_ms += ms;
+          st.prefetch_stalls += 1;
         } else if (t.cls == TC_H2D) {
           st.h2d_ms += ms;
         } else {
@@ -1526,12 +1537,14 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
   // ---- stream dependencies -----------------------------------------------------------------------
   if (M.prefetch_pending) {
     st->wait_pf(M.pf_ticket);      // the event below exists only once the worker has issued the copies
+    st->tbegin(TC_STALL, cs);      // how long the stream stands at the wait, when timing is on
     if (st->xfer && M.prefetch_ticket) {
       rc = pipemax_xfer_stream_wait(st->xfer, M.prefetch_ticket, cs);
       if (rc) return rc;
     } else {
       PMX_HIP(hipStreamWaitEvent(cs, M.ev_prefetch, 0));
     }
+    st->tend(cs);
     M.prefetch_pending = false;
   }
   if (st->h2d_fence_pending) {
@@ -1559,8 +1572,11 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     // lengths before this step; the last kernel of a step advances the device copy
     int32_t* hl = ord + maxb;
     for (int r2 = 0; r2 < b; ++r2) hl[r2] = pos0[r2];
-    PMX_HIP(hipMemcpyAsync(M.d_table, ht, ((size_t)maxb * D.max_pages + maxb + b) * sizeof(int32_t),
-                           hipMemcpyHostToDevice, cs));
+    {
+      const size_t n_words = (size_t)maxb * D.max_pages + maxb + b;
+      hipLaunchKernelGGL(k_upload_words, dim3((unsigned)std::min<size_t>(64, (n_words + 255) / 256)), dim3(256), 0, cs,
+                         M.d_table, (const int32_t*)ht, n_words);
+    }
     PMX_HIP(hipEventRecord(st->ev_table[r], cs));
     st->table_used[r] = true;
     M.table_dirty = subset;   // after a caller-chosen row list the device copy does not describe the whole mb

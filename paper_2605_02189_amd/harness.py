@@ -153,21 +153,23 @@ class StageRunner:
 
     def step(self, hidden_in: torch.Tensor | None, hidden_out: torch.Tensor | None,
              stream: torch.cuda.Stream | None = None, transfers: bool = True, compute: bool = True):
-        """Iteration t of the cyclic schedule: execute D_i, overwrite D_k, prefetch D_j (Eq. 3).  The step is
-        enqueued first, so that the GPU already has it while the host arranges the iteration's transfers
-        (none of the three calls blocks on the GPU).
+        """Iteration t of the cyclic schedule: overwrite D_k, prefetch D_j, execute D_i (Eq. 3).  None of the
+        three calls blocks on the GPU.  The transfers are arranged first: the prefetch worker then issues the
+        copies the moment the last reader of the overwritten pages (step t-1) ends, while the host is still
+        enqueuing step t; arranged after the step they start 0.2-0.3 ms later and, where a copy takes about as
+        long as a step, no longer fit behind it.
         transfers=False keeps everything where it is (all micro-batches must be resident);
         compute=False issues only the evict / prefetch traffic of the iteration."""
         n, t = self.n, self.t
         lag = self.arenas - 1                      # the micro-batch that ran `lag` iterations ago is overwritten
         i, j, k = t % n, (t + 1) % n, (t - lag) % n
-        if compute:
-            sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
-            self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         if transfers:
             if t >= lag and self.n_stream[k] and k != i and k != j:
                 self.stage.evict_kv(k, self.stream_ids[k])
             if j != i and self.n_stream[j]:
                 self.stage.prefetch_kv(j, self.stream_ids[j])
+        if compute:
+            sp = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+            self.stage.decode_step(i, hidden_in.data_ptr(), hidden_out.data_ptr(), sp)
         self.t += 1
         return i

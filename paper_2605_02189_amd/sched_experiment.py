@@ -50,7 +50,9 @@ def main():
     ap.add_argument("--alpha-us", type=float, default=2.7)
     ap.add_argument("--beta-ns", type=float, default=6.3)
     ap.add_argument("--delta-ms", type=float, default=0.87)
-    ap.add_argument("--link-gbs", type=float, default=56.66)
+    ap.add_argument("--link-gbs", type=float, default=0.0,
+                    help="effective host-to-device bandwidth B of Eq. 6; 0 = measure it first on this workload's own "
+                         "prefetch copies (bytes / busy time of the copies of a calibration run)")
     ap.add_argument("--static", default="0.005,0.01,0.025,0.05,0.10,0.15,0.20,0.25")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
@@ -73,13 +75,13 @@ def main():
     syn = SynthInputs(shape, seed=args.seed)
     stream = torch.cuda.Stream()
     kv_tok = base.kv_bytes_per_token
-    link_tokens = args.link_gbs * 1e9 / kv_tok
     model = dict(alpha_s=args.alpha_us * 1e-6, beta_s=args.beta_ns * 1e-9, delta_s=args.delta_ms * 1e-3,
-                 link_tokens_per_s=link_tokens, n_batches=n)
+                 link_tokens_per_s=(args.link_gbs or 56.0) * 1e9 / kv_tok, n_batches=n)
 
-    def run_policy(static_tokens: int) -> dict:
+    def run_policy(static_tokens: int, time_copies: bool = False) -> dict:
         # a fresh stage per policy: every policy sees the same requests at the same lengths
-        run = StageRunner(shape, syn, sigma=0.0, steps=all_iters, ctx_lens=ctx, gpu_pages=pool_pages)
+        run = StageRunner(shape, syn, sigma=0.0, steps=all_iters, ctx_lens=ctx, gpu_pages=pool_pages,
+                          flags=(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY) if time_copies else 0)
         st = run.stage
         run.load()
         hin = run.hidden_tensor(0, 0)
@@ -128,13 +130,27 @@ def main():
                 "h2d_gb_per_iter": stats["h2d_bytes"] / args.iters / 1e9,
                 "h2d_copies_per_iter": stats["h2d_copies"] / args.iters,
                 "requests_prefetched_per_iter": npf / args.iters, "requests_released_per_iter": nev / args.iters,
+                "h2d_busy_ms_per_iter": stats["h2d_ms"] / args.iters,
+                "prefetch_stall_ms_per_iter": stats["prefetch_stall_ms"] / args.iters,
                 "host_wait_ms_per_iter": stats["host_wait_s"] / args.iters * 1e3,
                 "host_enqueue_ms_per_iter": stats["host_enqueue_s"] / args.iters * 1e3}
 
     out = {"config": base.name, "mix": args.mix, "requests": int(n * b), "mean_prefix": float(L.mean()),
            "median_prefix": float(np.median(L)), "total_tokens": int(L.sum()), "pool_frac": args.pool_frac,
            "pool_tokens": pool_pages * 16, "iters": args.iters, "warmup_iters": args.warmup_iters, "model": model, "policies": {}}
-    run_policy(0)          # discarded: the first stage of a process runs about 0.2 ms per iteration slower
+    # The first stage of a process runs about 0.2 ms per iteration slower, so the first run is not a result; it
+    # serves as the calibration of B: the prefetch copies of this workload are per request, a few MB each and
+    # scattered over the GPU pool, and the rate they reach -- bytes over the time the copies of an iteration take
+    # from the first one's start to the last one's end -- is what Eq. 6 calls the effective bandwidth.
+    cal = run_policy(int(0.02 * pool_pages * 16), time_copies=True)
+    b_eff = cal["h2d_gb_per_iter"] / max(cal["h2d_busy_ms_per_iter"], 1e-9) * 1e3
+    out["calibration"] = {"static_budget_frac": 0.02, "h2d_gb_per_iter": cal["h2d_gb_per_iter"],
+                          "h2d_busy_ms_per_iter": cal["h2d_busy_ms_per_iter"], "effective_link_gbs": b_eff,
+                          "ms_per_iter": cal["ms_per_iter"],
+                          "prefetch_stall_ms_per_iter": cal["prefetch_stall_ms_per_iter"]}
+    if not args.link_gbs:
+        model["link_tokens_per_s"] = b_eff * 1e9 / kv_tok
+    out["model"] = model
     res = run_policy(0)
     out["policies"]["scheduler"] = res
     if args.verbose:
@@ -144,8 +160,9 @@ def main():
         out["policies"][f"static_{f:g}"] = res
         if args.verbose:
             print(f"static {f:g}", res, file=sys.stderr, flush=True)
-    best_static = max(v["tokens_per_s"] for k, v in out["policies"].items() if k != "scheduler")
-    out["scheduler_vs_best_static"] = out["policies"]["scheduler"]["tokens_per_s"] / best_static
+    statics = [v["tokens_per_s"] for k, v in out["policies"].items() if k != "scheduler"]
+    if statics:
+        out["scheduler_vs_best_static"] = out["policies"]["scheduler"]["tokens_per_s"] / max(statics)
     print(json.dumps(out))
 
 

@@ -24,7 +24,7 @@ def test_struct_sizes_match_the_header(lib):
     # pipemax_config_t: 6 int32, 2 float, 5 int32, (pad) 2 uint64, int32, uint32, 2 int32
     assert C.sizeof(lib.Config) == 88
     assert lib.Config.gpu_kv_bytes.offset == 56
-    assert C.sizeof(lib.Stats) == 8 * 8 + 4 * 8 + lib.N_KCLASS * 16 + 5 * 4 + 4 + 8
+    assert C.sizeof(lib.Stats) == 8 * 8 + 4 * 8 + lib.N_KCLASS * 16 + 5 * 4 + 4 + 8 + 8 + 8
 
 
 def test_stage_create_fails_loudly_without_a_gpu_or_with_bad_shapes(lib):
