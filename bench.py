@@ -193,7 +193,7 @@ def run_config(name, args, *, light=False):
     kv_guess = b * (shape.ctx_lo + shape.ctx_hi) // 2 * shape.kv_bytes_per_token
     sweep_cycles = max(2, min(24, int(0.15 / ((shape.weight_bytes + kv_guess) / 5e12) / n + 0.5)))
     total_steps = ((W + K) + (0 if args.no_legs else 2 * n + 3 * Kc + 2 * n)
-                   + len(sweep_sigmas) * (2 + sweep_cycles) * n + 2 * n)
+                   + (len(sweep_sigmas) + 1) * (3 + sweep_cycles) * n + 2 * n)
 
     t_setup = time.perf_counter()
     syn = SynthInputs(shape, seed=args.seed)
@@ -360,9 +360,20 @@ def run_config(name, args, *, light=False):
         per_seq = pages_for(int(max(int(c.max()) for c in run.ctx0.values()))) + grow
         sweep = [{"sigma": args.sigma, "ms_per_step": round(res["ms_per_step"], 3),
                   "h2d_gb_per_step": round(s3["h2d_bytes"] / K / 1e9, 4), "feasible": True}]
+        full = {mb: [pages_for(int(l)) + grow for l in run.ctx0[mb]] for mb in range(n)}
+
+        def pages_needed(ns):
+            return (sum(sum(full[mb][: b - ns]) for mb in range(n))
+                    + sum(sorted((sum(full[mb][b - ns:]) for mb in range(n)), reverse=True)[: run.arenas]) + 8)
+        # where the HBM cannot hold every point of the list, the smallest streamed fraction it can hold joins it
+        if pages_needed(0) > pool_pages:
+            ns_min = next(k for k in range(b + 1) if pages_needed(k) <= pool_pages)
+            sg_min = ns_min / b
+            if ns_min < b and all(abs(sg_min - x) > 1e-9 for x in sweep_sigmas):
+                sweep_sigmas = sorted(sweep_sigmas + [sg_min], reverse=True)
         for sg in sweep_sigmas:
             ns = int(round(sg * b))
-            need = n * (b - ns) * per_seq + run.arenas * ns * per_seq + 8
+            need = pages_needed(ns)
             if need > pool_pages:
                 sweep.append({"sigma": sg, "feasible": False,
                               "why": f"resident parts + two streamed arenas need {need} GPU pages, the HBM holds {pool_pages}"})
@@ -382,26 +393,31 @@ def run_config(name, args, *, light=False):
             # one more cycle with the attention launches and the wait for the prefetch timed (dispatch stamps and
             # events on the compute stream): where a step that is longer than the compute-only one loses its time
             st.set_flags(pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY, 0)
-            _, sd = timed_steps(n)
+            _, sd = timed_steps(2 * n)
             st.set_flags(0, pm.FLAG_TIME_KERNELS | pm.FLAG_TIME_ATTN_ONLY)
             row["attn_us_per_launch"] = round(sd["kernel_ms"]["attn"] / max(sd["kernel_launches"]["attn"], 1) * 1e3, 2)
-            row["prefetch_stall_ms_per_step"] = round(sd["prefetch_stall_ms"] / n, 4)
+            row["prefetch_stall_ms_per_step"] = round(sd["prefetch_stall_ms"] / (2 * n), 4)
             sweep.append(row)
             log("sweep:", json.dumps(sweep[-1]))
+        # the compute-only reference of the sweep is its own sigma = 0 point (same driver loop, same timing) where
+        # the pool can hold it, else the compute-only leg
+        zero = [p for p in sweep if p["feasible"] and p["sigma"] == 0.0]
+        t_ref = zero[0]["ms_per_step"] * 1e-3 if zero else t_c
         for p in sweep:
             if not p["feasible"]:
                 continue
             tx = p["h2d_gb_per_step"] / link_gbs        # what the step's prefetch takes on the link alone (s)
             p["t_transfer_ms_at_measured_link"] = round(tx * 1e3, 3)
-            p["bound"] = "link" if tx > t_c else "hbm"
-            p["hidden"] = bool(p["ms_per_step"] * 1e-3 <= 1.05 * max(t_c, tx))
-            p["vs_compute_only"] = round(p["ms_per_step"] * 1e-3 / t_c, 3)
-        sigma_star = t_c * link_gbs * 1e9 / kv_mb
+            p["bound"] = "link" if tx > t_ref else "hbm"
+            p["hidden"] = bool(p["ms_per_step"] * 1e-3 <= 1.05 * max(t_ref, tx))
+            p["vs_compute_only"] = round(p["ms_per_step"] * 1e-3 / t_ref, 3)
+        sigma_star = t_ref * link_gbs * 1e9 / kv_mb
         hbm_side = [p for p in sweep if p["feasible"] and p["bound"] == "hbm" and p["sigma"] > 0]
         link_side = [p for p in sweep if p["feasible"] and p["bound"] == "link"]
         res["crossover"] = {
             "sigma_star_predicted": round(sigma_star, 4),
             "formula": "sigma* = T_compute_only * link rate / KV bytes of one micro-batch",
+            "t_compute_only_ms_used": round(t_ref * 1e3, 4),
             "smallest_link_bound_sigma_measured": min((p["sigma"] for p in link_side), default=None),
             "largest_hbm_bound_sigma_measured": max((p["sigma"] for p in hbm_side), default=None),
             "hidden_at_largest_hbm_bound_sigma": (max(hbm_side, key=lambda p: p["sigma"])["hidden"] if hbm_side else None),
