@@ -59,7 +59,7 @@ SYMBOLS = [
     "pipemax_get_ctx_lens", "pipemax_get_residency", "pipemax_get_block_table",
     "pipemax_get_layer_outputs", "pipemax_debug_fill_free_gpu_pages", "pipemax_debug_set_delays",
     "pipemax_last_error", "pipemax_version", "pipemax_page_elem_offset",
-    "pipemax_plan_copy_runs", "pipemax_plan_gemm_splits", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
+    "pipemax_plan_copy_runs", "pipemax_plan_gemm_splits", "pipemax_plan_attention_chunks", "pipemax_pool_create", "pipemax_pool_destroy", "pipemax_pool_alloc",
     "pipemax_pool_free", "pipemax_pool_free_count",
 ]
 # every symbol include/pipemax_xfer.h declares
@@ -221,6 +221,7 @@ _sig = {
     "pipemax_page_elem_offset": (C.c_int64, [C.c_int] * 8),
     "pipemax_plan_copy_runs": (C.c_int, [_i32p, _i32p, C.c_int, C.c_int, _i32p]),
     "pipemax_plan_gemm_splits": (C.c_int, [C.c_int, C.c_int, C.c_int, _i32p, _i32p, _i32p]),
+    "pipemax_plan_attention_chunks": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int64, _i32p, _i32p]),
     "pipemax_pool_create": (C.c_int, [C.c_int, C.POINTER(_vp)]),
     "pipemax_pool_destroy": (C.c_int, [_vp]),
     "pipemax_pool_alloc": (C.c_int, [_vp, C.c_int, _i32p]),
@@ -455,6 +456,13 @@ def plan_copy_runs(src_pages, dst_pages, max_run_pages: int):
     if n < 0:
         raise PipemaxError(n, last_error())
     return runs[: 3 * n].reshape(n, 3)
+
+
+def plan_attention_chunks(n_seqs: int, n_kv_heads: int, max_ctx_tokens: int, sum_pages: int):
+    """(pages per work-group, chunks of the longest sequence) the stage plans for such a step."""
+    cp, nch = C.c_int32(0), C.c_int32(0)
+    _check(_lib.pipemax_plan_attention_chunks(n_seqs, n_kv_heads, max_ctx_tokens, sum_pages, C.byref(cp), C.byref(nch)))
+    return int(cp.value), int(nch.value)
 
 
 def plan_gemm_splits(rows: int, n_cols: int, k: int):

@@ -1468,6 +1468,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
                 const void* hidden_in, void* hidden_out, void* hip_stream, bool one_seq_chunk = false,
                 bool static_scratch = false) {
   const double t_enter = now_s();
+  const double wait_enter = st->st.host_wait_s;
   int rc;
   if (!hidden_in || !hidden_out) PMX_FAIL(PIPEMAX_ERR_ARG, "null hidden pointer");
   MicroBatch& M = st->mbs[mb];
@@ -1829,7 +1830,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
   st->step_no += 1;
   st->st.steps += 1;
   st->st.tokens += (uint64_t)b;
-  st->st.host_enqueue_s += now_s() - t_enter;
+  st->st.host_enqueue_s += (now_s() - t_enter) - (st->st.host_wait_s - wait_enter);     // without the waits above
   return PIPEMAX_OK;
 }
 }  // namespace
@@ -2125,6 +2126,19 @@ int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, 
   *plan_splits = p.split;
   *launch_splits = pmx::mfma::large_gemm_splits(k / 16, p.split, &ksp);
   *k_steps_per_split = ksp;
+  return PIPEMAX_OK;
+}
+
+int pipemax_plan_attention_chunks(int n_seqs, int n_kv_heads, int max_ctx_tokens, int64_t sum_pages,
+                                  int32_t* chunk_pages, int32_t* n_chunks) {
+  if (!chunk_pages || !n_chunks || n_seqs < 1 || n_kv_heads < 1 || max_ctx_tokens < 1 || sum_pages < 1)
+    PMX_FAIL(PIPEMAX_ERR_ARG, "plan_attention_chunks: positive counts");
+  pipemax_stage tmp;
+  tmp.D.Hkv = n_kv_heads;
+  tmp.nch_alloc = (((max_ctx_tokens + kPageTokens - 1) / kPageTokens) + 7) / 8;
+  int cp = 0;
+  *n_chunks = attention_plan(&tmp, n_seqs, max_ctx_tokens - 1, sum_pages, &cp);
+  *chunk_pages = cp;
   return PIPEMAX_OK;
 }
 

@@ -161,3 +161,32 @@ def test_gemm_split_plan_and_launch_geometry_agree(lib):
     assert lib.plan_gemm_splits(1024, 4096, 4096)[0] * 4 * (4096 // 256) == 256
     with pytest.raises(lib.PipemaxError):
         lib.plan_gemm_splits(256, 300, 4096)
+
+
+def test_attention_chunk_plan_covers_the_context_with_even_chunks(lib):
+    """The decode attention's chunking: every plan covers the longest context (chunks x pages per chunk >= its
+    pages), a work-group never gets more than 256 pages, chunks are even (no chunk is more than one page short of
+    the others), and the cases the benchmark configurations hit come out as measured best: one chunk for 256
+    sequences of 2049 tokens, two halves (129 + 128 pages) for 4097 tokens -- not a full work-group and a
+    one-page rest."""
+    def pages(tokens):
+        return -(-tokens // 16)
+    for n_seqs, hkv, tokens in ((256, 8, 2049), (256, 8, 4097), (64, 8, 1025), (1, 1, 1), (1, 8, 40000), (3, 1, 3000),
+                                (128, 8, 4100), (256, 8, 4096), (2, 2, 4113), (7, 4, 257 * 16), (5, 8, 8193)):
+        total = n_seqs * pages(tokens)
+        cp, nch = lib.plan_attention_chunks(n_seqs, hkv, tokens, total)
+        npg = pages(tokens)
+        assert 8 <= cp <= 256 and nch >= 1, (n_seqs, hkv, tokens, cp, nch)
+        assert cp * nch >= npg, (n_seqs, hkv, tokens, cp, nch)
+        assert nch == -(-npg // cp)
+        last = npg - (nch - 1) * cp                     # pages of the last chunk
+        assert last >= 1 and (cp - last <= nch or cp == 8), (n_seqs, hkv, tokens, cp, nch, last)
+    assert lib.plan_attention_chunks(256, 8, 2049, 256 * 129) == (129, 1)
+    assert lib.plan_attention_chunks(256, 8, 4097, 256 * 257) == (129, 2)
+    assert lib.plan_attention_chunks(64, 8, 1025, 64 * 65) == (65, 1)
+    # a ragged batch whose longest sequence would outlast everything else is cut into several chunks
+    cp, nch = lib.plan_attention_chunks(3, 1, 3000, pages(3000) + pages(41) + pages(1026))
+    assert nch > 1
+    import pytest
+    with pytest.raises(lib.PipemaxError):
+        lib.plan_attention_chunks(0, 8, 100, 7)
