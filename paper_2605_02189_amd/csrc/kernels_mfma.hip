@@ -944,15 +944,13 @@ __device__ inline void chunk_range(int n_tok, int CP, int chunk, int& nch, int& 
 
 constexpr int kORow = 132;   // padded LDS row of the cross-wave merge
 
+// Three waves per SIMD: the body needs 145 registers, and left to itself the compiler takes 181.
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint16_t* __restrict__ q,
-                                                  const uint16_t* __restrict__ pool,
-                                                  const int* __restrict__ table,
-                                                  const int* __restrict__ ctx, float* __restrict__ part_o,
-                                                  float* __restrict__ part_ml, int CP, int NCH,
-                                                  int* __restrict__ counters,
-                                                  uint16_t* __restrict__ out_t,
-                                                  const int* __restrict__ order) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_attn(
+    Dims D, int layer, const uint16_t* __restrict__ q, const uint16_t* __restrict__ pool,
+    const int* __restrict__ table, const int* __restrict__ ctx, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int CP, int NCH, int* __restrict__ counters, uint16_t* __restrict__ out_t,
+    const int* __restrict__ order) {
   extern __shared__ float so[];                 // [NW][G][kORow], later [G][kORow] merged
   __shared__ float sm[NW][16], sl[NW][16];
   __shared__ int s_last;
@@ -998,15 +996,17 @@ __global__ __launch_bounds__(NW * 64) void k_attn(Dims D, int layer, const uint1
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // two register buffers: the next page is requested before the current one is consumed
+  // two register buffers: the next page is requested before the current one is consumed.  Every K / V line is used
+  // exactly once per launch, so the loads are marked non-temporal: as ordinary loads, which claim an L2 line each,
+  // the same kernel streamed 10 % slower (256 sequences x 2048 tokens, 8 KV heads: 386 -> 349 us per launch).
   uint4 kf[2][4], vf[2][4];
   auto load_page = [&](int t, uint4* kd, uint4* vd) {
     const int phys = __builtin_amdgcn_readfirstlane(__shfl(my_page, t));
     const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_stride + sub_off) + lane;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) kd[kk] = base[kk * 64];
+    for (int kk = 0; kk < 4; ++kk) kd[kk] = ld_stream(base + kk * 64);
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) vd[jj] = base[256 + jj * 64];
+    for (int jj = 0; jj < 4; ++jj) vd[jj] = ld_stream(base + 256 + jj * 64);
   };
   if (npw > 0) load_page(0, kf[0], vf[0]);
   for (int t0 = 0; t0 < npw; t0 += 2) {
