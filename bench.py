@@ -168,6 +168,26 @@ def run_probes(args):
                          "gpu_us_per_kernel": round(r["gpu_s"] / 41 * 1e6, 2)}
     out["launch_chain_of_41_dependent_one_wave_kernels"] = launch
     log("launch:", json.dumps(launch))
+    # Reference only, not part of the path: the vendor library's plain bf16 GEMM (torch.matmul) on the shapes of the
+    # stage's four projections, four weight matrices taken in turn so that they stream from HBM; the time includes
+    # the gap between launches, as a step's kernels do.
+    lib = {}
+    for label, rows, h, nqkv, f in (("8B-shaped stage, 64 rows", 64, 4096, 6144, 14336),
+                                    ("70B-shaped stage, 256 rows", 256, 8192, 10240, 28672),
+                                    ("70B-shaped stage, 1024 rows", 1024, 8192, 10240, 28672)):
+        per = {}
+        for gname, k, n_cols in (("qkv", h, nqkv), ("o", h, h), ("gate_up", h, 2 * f), ("down", f, h)):
+            a = torch.randn(rows, k, device="cuda", dtype=torch.bfloat16)
+            ws = [torch.randn(k, n_cols, device="cuda", dtype=torch.bfloat16) * 0.02 for _ in range(4)]
+            reps = 40
+            t = timed(lambda: [torch.matmul(a, ws[r % 4]) for r in range(reps)], reps=2) / reps
+            per[gname] = {"us": round(t * 1e6, 1), "tflops": round(2 * rows * k * n_cols / t / 1e12, 1),
+                          "weight_gbs": round(k * n_cols * 2 / t / 1e9, 1)}
+            del a, ws
+        per["layer_us"] = round(sum(v["us"] for v in per.values()), 1)
+        lib[label] = per
+        log("library gemm", label, json.dumps(per))
+    out["library_gemm_reference"] = lib
     out["link_peak_nominal_gbs"] = LINK_PEAK_GBS
     out["hbm_peak_nominal_gbs"] = HBM_PEAK_GBS
     print(json.dumps(out), flush=True)
@@ -331,6 +351,8 @@ def run_config(name, args, *, light=False):
             "ms_per_step_with_event_brackets": round(t_timed / Kc * 1e3, 4),
             "hbm_bytes_per_step": int(hbm_bytes_step),
             "frac_of_hbm_roofline": round(hbm_bytes_step / t_c / 1e9 / HBM_PEAK_GBS, 4),
+            # attention: the dispatch's own start and stop; the other classes: between two stream events, which
+            # includes the gap to the next launch (about 3 us); exact durations: profiles/bench_<config>_kernel_trace.txt
             "kernel_us_per_launch": {k: round(kms[k] / max(kl[k], 1) * 1e3, 2) for k in kms if kl[k]},
             "kernel_ms_per_step": {k: round(kms[k] / Kc, 4) for k in kms if kl[k]},
             "gemm_tflops": round(2 * (shape.weight_bytes / shape.elem_bytes) * b / (gemm_ms * 1e-3) / 1e12, 1),
