@@ -389,13 +389,16 @@ int64_t pipemax_page_elem_offset(int n_layers, int n_kv_heads, int head_dim,
 int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, int32_t* launch_splits,
                              int32_t* k_steps_per_split);
 
-/* Chunking of the decode attention for a step of n_seqs sequences whose longest context is max_ctx_tokens tokens
- * (the new token included) and whose contexts cover sum_pages pages in all: pages per work-group (*chunk_pages, at
- * most 256) and the number of chunks the longest sequence is cut into (*n_chunks).  Chunks are even: a context one
- * page longer than a work-group takes becomes two halves, not a full chunk and a one-page chunk.  Pure host arithmetic
- * (the stage's own planner, without the PIPEMAX_ATTN_CHUNK_PAGES override).  Errors: ERR_ARG.                       */
+/* Plan of the decode attention for a step of n_seqs sequences whose longest context is max_ctx_tokens tokens (the new
+ * token included) and whose contexts cover sum_pages pages in all, on a GPU of compute_units compute units.  The
+ * attention's items are (chunk of the context, KV head, sequence).  *wave_per_item = 1: every item is streamed by one
+ * wave (chosen when n_seqs * n_kv_heads >= 4 * compute_units); 0: by a work-group of four waves that share its pages
+ * (then *chunk_pages <= 256).  *chunk_pages = pages per item, *n_chunks = chunks the longest sequence is cut into.
+ * Chunks are even: a context one page longer than an item takes becomes two halves, not a full chunk and a one-page
+ * chunk.  Pure host arithmetic (the stage's own planner, without the PIPEMAX_ATTN_CHUNK_PAGES / PIPEMAX_ATTN_KERNEL
+ * overrides).  Errors: ERR_ARG.                                                                                     */
 int pipemax_plan_attention_chunks(int n_seqs, int n_kv_heads, int max_ctx_tokens, int64_t sum_pages,
-                                  int32_t* chunk_pages, int32_t* n_chunks);
+                                  int compute_units, int32_t* chunk_pages, int32_t* n_chunks, int32_t* wave_per_item);
 
 /* Merges n (src_page, dst_page) pairs, in the given order, into runs of consecutive pages,
  * each at most max_run_pages long.  Writes (src_first, dst_first, count) triples to runs

@@ -221,7 +221,7 @@ _sig = {
     "pipemax_page_elem_offset": (C.c_int64, [C.c_int] * 8),
     "pipemax_plan_copy_runs": (C.c_int, [_i32p, _i32p, C.c_int, C.c_int, _i32p]),
     "pipemax_plan_gemm_splits": (C.c_int, [C.c_int, C.c_int, C.c_int, _i32p, _i32p, _i32p]),
-    "pipemax_plan_attention_chunks": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int64, _i32p, _i32p]),
+    "pipemax_plan_attention_chunks": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int, _i32p, _i32p, _i32p]),
     "pipemax_pool_create": (C.c_int, [C.c_int, C.POINTER(_vp)]),
     "pipemax_pool_destroy": (C.c_int, [_vp]),
     "pipemax_pool_alloc": (C.c_int, [_vp, C.c_int, _i32p]),
@@ -458,11 +458,13 @@ def plan_copy_runs(src_pages, dst_pages, max_run_pages: int):
     return runs[: 3 * n].reshape(n, 3)
 
 
-def plan_attention_chunks(n_seqs: int, n_kv_heads: int, max_ctx_tokens: int, sum_pages: int):
-    """(pages per work-group, chunks of the longest sequence) the stage plans for such a step."""
-    cp, nch = C.c_int32(0), C.c_int32(0)
-    _check(_lib.pipemax_plan_attention_chunks(n_seqs, n_kv_heads, max_ctx_tokens, sum_pages, C.byref(cp), C.byref(nch)))
-    return int(cp.value), int(nch.value)
+def plan_attention_chunks(n_seqs: int, n_kv_heads: int, max_ctx_tokens: int, sum_pages: int, compute_units: int = 256):
+    """(pages per item, chunks of the longest sequence, whether a wave (True) or a work-group streams an item) the
+    stage plans for such a step on a GPU of that many compute units."""
+    cp, nch, pw = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(_lib.pipemax_plan_attention_chunks(n_seqs, n_kv_heads, max_ctx_tokens, sum_pages, compute_units,
+                                              C.byref(cp), C.byref(nch), C.byref(pw)))
+    return int(cp.value), int(nch.value), bool(pw.value)
 
 
 def plan_gemm_splits(rows: int, n_cols: int, k: int):

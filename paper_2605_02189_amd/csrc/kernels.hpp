@@ -77,21 +77,23 @@ void rope_append(hipStream_t s, const Dims& D, int layer, int b, const float* pa
                  uint16_t* pool, uint16_t* staging, uint16_t* q_out);
 
 constexpr int kAttnWaves = 4;   // waves per attention work-group
+int compute_units();            // of the current device (cached per device)
 // Causal attention of a prefill chunk: `rows` consecutive new tokens of one sequence starting at position
 // pos0, K,V already appended; table = the sequence's page ids.  (pos0 + rows) tokens must fit 64 * kAttnWaves
 // pages.  Output rows are written A-tiled like the decode kernel's.
 void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int pos0, const uint16_t* q,
                        const uint16_t* pool, const int* table, uint16_t* out_t);
-// Split-K paged GQA decode attention.  chunk_pages = target pages per work-group (<= 64 * kAttnWaves), max_chunks = grid
-// extent along the context axis (>= ceil(max pages / chunk_pages)).  The wave that finishes a
-// (sequence, kv head) last merges the chunk partials (counters: b * Hkv ints, zero, self-resetting)
-// and writes the A-tiled bf16 input of the output projection.  order[z] = sequence handled by grid
-// slice z (a permutation of 0..b-1, longest context first).  ev_start / ev_stop (both or neither): events that
-// receive the start and stop time of this dispatch (for timing the kernel alone).
+// Split-K paged GQA decode attention over the items (chunk, KV head, sequence): chunk_pages = pages per item,
+// max_chunks = chunks of the longest context (>= ceil(max pages / chunk_pages)).  per_wave = false: a work-group of
+// kAttnWaves waves per item (chunk_pages <= 64 * kAttnWaves), whose waves share the item's pages and merge through LDS;
+// true: a wave per item (any chunk_pages).  Whoever finishes a (sequence, kv head) last merges the chunk partials
+// (counters: b * Hkv ints, zero, self-resetting) and writes the A-tiled bf16 input of the output projection.
+// order[z] = sequence handled by slice z of the items (a permutation of 0..b-1, longest context first).  ev_start /
+// ev_stop (both or neither): events that receive the start and stop time of this dispatch (for timing the kernel alone).
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q,
                const uint16_t* pool, const int* table, const int* ctx, float* part_o, float* part_ml,
                int chunk_pages, int max_chunks, int* counters, uint16_t* out_t, const int* order,
-               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, bool per_wave = false);
 
 // ---- fused pipeline for b <= 64 rows -----------------------------------------------------------------
 // x = hidden_in; ssq_out[i][0] = sum of squares of row i (other nb-1 entries 0); xg_t = x * gain as

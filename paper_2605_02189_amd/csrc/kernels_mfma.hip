@@ -1148,6 +1148,195 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3)))
   }
 }
 
+// The same attention with a wave, not a work-group, as the worker: wave (blockIdx.x * NW + w) takes item (chunk, KV
+// head, sequence) of that number and streams all of the chunk's pages (up to 256: four registers of page ids) by
+// itself; the NW waves of a work-group share nothing and never meet at a barrier.  In k_attn the waves of an item
+// drift apart while they stream and the faster ones wait at the merge for the slowest: a copy of k_attn without
+// its merge ran 332 us where k_attn runs 348 (256 sequences x 2048 tokens, 8 KV heads), and the loss grows as the
+// items shrink (66 / 33 pages per item: +48 / +100 us with the merge, +3 / +7 us without).  A chunk that is the whole
+// context is normalised and written by its wave; several chunks are merged by the wave that arrives last at the
+// (sequence, KV head) counter, as in k_attn.  For launches with enough items to fill the chip (the host decides).
+template <int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_attn_w(
+    Dims D, int layer, const uint16_t* __restrict__ q, const uint16_t* __restrict__ pool,
+    const int* __restrict__ table, const int* __restrict__ ctx, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int CP, int NCH, int* __restrict__ counters, uint16_t* __restrict__ out_t,
+    const int* __restrict__ order, int n_items) {
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
+  const int G = D.G, Hkv = D.Hkv;
+  const int j = blockIdx.x * NW + w;
+  if (j >= n_items) return;
+  // item j of a (chunks, heads, sequences) grid; the head is rotated by the sequence as in k_attn
+  const int chunk = j % NCH, yz = j / NCH, y = yz % Hkv, z = yz / Hkv;
+  const int c = (y + z) % Hkv, i = order[z];
+  // length, the first 256 page ids (lane l holds pages p0 + l, + 64, + 128, + 192 of the chunk) and Q are requested
+  // together
+  int mp[4];
+  auto load_ids = [&](int first) {                // page ids of the chunk's pages first .. first + 255
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int off = first + lane + 64 * r, pidx = chunk * CP + off;
+      mp[r] = (off < CP && pidx < D.max_pages) ? table[(int64_t)i * D.max_pages + pidx] : 0;
+    }
+  };
+  load_ids(0);
+  const int n_tok = ctx[i] + 1;
+  int nch, p0, p1;
+  chunk_range(n_tok, CP, chunk, nch, p0, p1);
+  if (chunk >= nch) return;                       // a sequence shorter than the longest has fewer chunks
+  const int np = p1 - p0;                         // >= 1
+
+  bf16x8 qf[4];                                   // B operand, lane (n, g) holds Q[head n][kk*32 + 8g .. +8]
+  {
+    const uint16_t* qrow = q + ((int64_t)i * D.Hq + c * G + (n < G ? n : 0)) * 128 + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 v = (n < G) ? *(const uint4*)(qrow + kk * 32) : make_uint4(0, 0, 0, 0);
+      qf[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  const int64_t sub_off = (int64_t)layer * D.layer_stride + sub_block_off(Hkv, 128, 0, c, 0);
+  const float scale_log2 = 1.4426950408889634f / sqrtf(128.0f);
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 oacc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 kf[2][4], vf[2][4];
+  auto load_page = [&](int t, uint4* kd, uint4* vd) {
+    const int r = t >> 6;
+    const int ids = r == 0 ? mp[0] : r == 1 ? mp[1] : r == 2 ? mp[2] : mp[3];
+    const int phys = __builtin_amdgcn_readfirstlane(__shfl(ids, t & 63));
+    const uint4* base = (const uint4*)(pool + (int64_t)phys * D.page_stride + sub_off) + lane;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kd[kk] = ld_stream(base + kk * 64);      // used once: see k_attn
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) vd[jj] = ld_stream(base + 256 + jj * 64);
+  };
+  auto consume_page = [&](int t, const uint4* kq, const uint4* vq) {
+    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[kk]), qf[kk], sacc, 0, 0, 0);
+    const int tok0 = ((p0 + t) << 4) + 4 * g;
+    float s[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] = (tok0 + e < n_tok) ? sacc[e] * scale_log2 : -INFINITY;
+    float mloc = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+    const float m_new = fmaxf(m_run, mloc);
+    const float alpha = exp2f(m_run - m_new);
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = exp2f(s[e] - m_new);
+    float lsum = (p[0] + p[1]) + (p[2] + p[3]);
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    l_run = l_run * alpha + lsum;
+    m_run = m_new;
+    const uint2 pp = make_uint2(pack2(p[0], p[1]), pack2(p[2], p[3]));
+    const s16x4 pf = __builtin_bit_cast(s16x4, pp);
+    // the V operand of the last (partial) page is masked: see k_attn
+    uint32_t vm0 = 0xffffffffu, vm1 = 0xffffffffu;
+    if (tok0 + 3 >= n_tok) {
+      const int valid = n_tok - tok0;
+      vm0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+      vm1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+    }
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const s16x4 v0 = __builtin_bit_cast(s16x4, make_uint2(vq[jj].x & vm0, vq[jj].y & vm1));
+      const s16x4 v1 = __builtin_bit_cast(s16x4, make_uint2(vq[jj].z & vm0, vq[jj].w & vm1));
+      oacc[2 * jj] = oacc[2 * jj] * alpha;
+      oacc[2 * jj + 1] = oacc[2 * jj + 1] * alpha;
+      oacc[2 * jj] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pf, oacc[2 * jj], 0, 0, 0);
+      oacc[2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pf, oacc[2 * jj + 1], 0, 0, 0);
+    }
+  };
+  // two buffers, one page requested ahead; no branch between a request and the wait for the older page in the
+  // steady part (the compiler would otherwise wait for both).  The page ids in registers reach 256 pages; a longer
+  // chunk goes window by window (one exposed load of ids and one of a first page per 256 pages).
+  for (int first = 0; first < np; first += 256) {
+    if (first) load_ids(first);
+    const int nw = min(256, np - first);
+    load_page(0, kf[0], vf[0]);
+    int t = 0;
+    for (; t + 2 < nw; t += 2) {
+      load_page(t + 1, kf[1], vf[1]);
+      consume_page(first + t, kf[0], vf[0]);
+      load_page(t + 2, kf[0], vf[0]);
+      consume_page(first + t + 1, kf[1], vf[1]);
+    }
+    if (t + 1 < nw) {
+      load_page(t + 1, kf[1], vf[1]);
+      consume_page(first + t, kf[0], vf[0]);
+      consume_page(first + t + 1, kf[1], vf[1]);
+    } else {
+      consume_page(first + t, kf[0], vf[0]);
+    }
+  }
+
+  // lane (n, g) holds, of query head n, output dimensions 16 dt + 4 g .. + 3 (dt = 0..7) and the head's (m, l)
+  const int KTo = D.Hq * 128 / 16;
+  const int head = c * G + n;
+  if (nch == 1) {
+    if (n < G) {
+      const float inv = 1.0f / l_run;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const f32x4 v = oacc[dt] * inv;
+        *(uint2*)(out_t + a_tiled_idx(KTo, i, head * 128 + dt * 16 + 4 * g)) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+      }
+    }
+    return;
+  }
+  // several chunks: publish (m, l, o); the wave that arrives last merges them in chunk order
+  if (n < G) {
+    float* dst = part_o + (((int64_t)i * D.Hq + head) * NCH + chunk) * 128 + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      st_agent2(dst + dt * 16, oacc[dt][0], oacc[dt][1]);
+      st_agent2(dst + dt * 16 + 2, oacc[dt][2], oacc[dt][3]);
+    }
+    if (g == 0) st_agent2(part_ml + (((int64_t)i * D.Hq + head) * NCH + chunk) * 2, m_run, l_run);
+  }
+  publish_stores();
+  int old = 0;
+  if (lane == 0) old = arrive(&counters[i * Hkv + c]);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != nch - 1) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  if (lane == 0) counters[i * Hkv + c] = 0;
+  if (n < G) {
+    const float* ml = part_ml + ((int64_t)i * D.Hq + head) * NCH * 2;
+    const float* po = part_o + ((int64_t)i * D.Hq + head) * NCH * 128 + 4 * g;
+    float m_tot = -INFINITY;
+    for (int jc = 0; jc < nch; ++jc) m_tot = fmaxf(m_tot, ld_agent(ml + 2 * jc));
+    float l = 0.f;
+    f32x4 o[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int jc = 0; jc < nch; ++jc) {
+      f32x4 v[8];
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[dt][e] = ld_agent(po + (int64_t)jc * 128 + dt * 16 + e);
+      const float fj = exp2f(ld_agent(ml + 2 * jc) - m_tot);
+      l += ld_agent(ml + 2 * jc + 1) * fj;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) o[dt] += v[dt] * fj;
+    }
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      const f32x4 v = o[dt] * inv;
+      *(uint2*)(out_t + a_tiled_idx(KTo, i, head * 128 + dt * 16 + 4 * g)) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+    }
+  }
+}
+
 // =================================================================================================
 // Causal attention of a prefill chunk: R rows = R consecutive new tokens of ONE sequence, row r at
 // position pos0 + r, whose K,V are already in the sequence's pages.
@@ -1474,9 +1663,20 @@ void attention_prefill(hipStream_t s, const Dims& D, int layer, int rows, int po
 void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q, const uint16_t* pool,
                const int* table, const int* ctx, float* part_o, float* part_ml, int chunk_pages,
                int max_chunks, int* counters, uint16_t* out_t, const int* order, hipEvent_t ev_start,
-               hipEvent_t ev_stop) {
+               hipEvent_t ev_stop, bool per_wave) {
   constexpr int NW = kAttnWaves;
   const size_t lds = (size_t)NW * D.G * kORow * sizeof(float);
+  const int n_items = max_chunks * D.Hkv * b;
+  if (per_wave) {
+    const unsigned grid = (unsigned)((n_items + NW - 1) / NW);
+    if (ev_start && ev_stop)
+      hipExtLaunchKernelGGL((k_attn_w<NW>), dim3(grid), dim3(NW * 64), 0u, s, ev_start, ev_stop, 0u, D, layer, q, pool,
+                            table, ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t, order, n_items);
+    else
+      hipLaunchKernelGGL((k_attn_w<NW>), dim3(grid), dim3(NW * 64), 0, s, D, layer, q, pool, table, ctx, part_o,
+                         part_ml, chunk_pages, max_chunks, counters, out_t, order, n_items);
+    return;
+  }
   if (ev_start && ev_stop)      // the events take the start and stop times of this dispatch itself
     hipExtLaunchKernelGGL((k_attn<NW>), dim3(max_chunks, D.Hkv, b), dim3(NW * 64), (uint32_t)lds, s, ev_start, ev_stop,
                           0u, D, layer, q, pool, table, ctx, part_o, part_ml, chunk_pages, max_chunks, counters, out_t,
@@ -1492,7 +1692,7 @@ void first(hipStream_t s, int b, int h, const uint16_t* hin, float* x, const uin
                      (double)rope_base);
 }
 
-static int compute_units() {      // of the current device (cached per device)
+int compute_units() {      // of the current device (cached per device)
   static std::atomic<int> cus[64];
   int dev = 0;
   (void)hipGetDevice(&dev);

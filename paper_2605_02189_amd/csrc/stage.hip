@@ -215,6 +215,7 @@ struct pipemax_stage {
   // up to 64 rows: consumers fused into the GEMM epilogues (plans f_*); more: large-tile GEMMs with
   // separate element-wise kernels, planned per call from the row count
   int attn_cp_override = 0;   // PIPEMAX_ATTN_CHUNK_PAGES: tuning override of the attention chunk size
+  int attn_worker = 0;        // PIPEMAX_ATTN_KERNEL=wave|group: tuning override of the attention kernel choice
   GemmPlan f_qkv, f_o, f_gu, f_d;
   int nch_alloc = 1;
   float* layer_out = nullptr;
@@ -1056,6 +1057,7 @@ int pipemax_stage_create(const pipemax_config_t* cfg, pipemax_stage_t** out) {
 #undef PMX_TRY_HIP
 
   if (const char* e = getenv("PIPEMAX_ATTN_CHUNK_PAGES")) st->attn_cp_override = atoi(e);
+  if (const char* e = getenv("PIPEMAX_ATTN_KERNEL")) st->attn_worker = e[0] == 'w' ? 1 : (e[0] == 'g' ? 2 : 0);
   st->dma = dma_copy_create(st->d_stage[0], st->h_stage[0]);
   st->worker = std::thread(worker_main, st);
   st->pf_worker = std::thread(pf_worker_main, st);
@@ -1382,9 +1384,31 @@ int pipemax_evict_kv(pipemax_stage_t* st, int mb, const int32_t* seq_ids, int n)
 // ---- the decode step ----------------------------------------------------------------------------------
 namespace {
 // Chunking of the decode attention for a step of b rows whose longest context is max_len cached tokens and that
-// reads sum_pages pages per KV head and layer: pages per work-group (*cp_out) and the number of chunks (returned).
-int attention_plan(const pipemax_stage* st, int b, int max_len, int64_t sum_pages, int* cp_out) {
+// reads sum_pages pages per KV head and layer, on a chip of `cus` compute units: which kernel (*per_wave: a wave per
+// (chunk, KV head, sequence) item, else a work-group per item), pages per item (*cp_out) and the number of chunks
+// (returned).
+int attention_plan(const pipemax_stage* st, int b, int max_len, int64_t sum_pages, int cus, int* cp_out,
+                   bool* per_wave) {
   const Dims& D = st->D;
+  *per_wave = false;
+  // A wave per item when the (sequence, KV head) pairs alone give every compute unit four waves: the waves then
+  // share nothing and never wait for each other (256 x 8 pairs of 129 pages: 334 against 348 us per launch; 128 x 8
+  // ragged pairs: 213 against 217; 64 x 8 pairs of 65 pages, where the work-group kernel's four waves per pair are
+  // what fills the chip: 55.8 against 52.4).  A wave streams a page in about 1 us at best (2.6 us when 2048 of them
+  // share the chip); a context that would take one wave longer than all pages take the chip (6.5 TB/s, 8 KiB per page
+  // and head) is split evenly -- and with it every sequence longer than the resulting chunk (128 ragged sequences of
+  // 512..4096 tokens: chunks of 129 pages 213 us, of 86 pages 221 us).
+  if (st->attn_worker == 1 || (st->attn_worker == 0 && b * D.Hkv >= 4 * cus)) {
+    const int npages = (max_len + 1 + kPageTokens - 1) / kPageTokens;
+    const double t_all_us = (double)D.Hkv * (double)sum_pages * 8192.0 / 6.5e6;
+    int CP = std::min(npages, std::max(16, (int)(t_all_us / 1.0)));
+    const int n = (npages + CP - 1) / CP;
+    CP = std::max(8, (npages + n - 1) / n);
+    if (st->attn_cp_override > 0) CP = std::max(8, st->attn_cp_override);
+    *per_wave = true;
+    *cp_out = CP;
+    return std::min(st->nch_alloc, (npages + CP - 1) / CP);
+  }
   // attention split: about one wave per SIMD (1024 on the chip); a work-group of kAttnWaves waves
   // covers up to 64 pages per wave, so most contexts are a single chunk
   const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
@@ -1504,7 +1528,9 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     int cp = 0;
     Work probe;
     size_t clear_bytes = 0;
-    const size_t need_bytes = carve_work(st, b, attention_plan(st, b, max_len, sum_pages, &cp), &probe, &clear_bytes);
+    bool pw = false;
+    const size_t need_bytes = carve_work(st, b, attention_plan(st, b, max_len, sum_pages, mfma::compute_units(), &cp, &pw), &probe,
+                                         &clear_bytes);
     if (need_bytes > kScratchBytes)
       PMX_FAIL(PIPEMAX_ERR_ARG, "a step of %d rows on this stage needs %zu bytes of working buffers; the static scratch "
                "of the entry point that allocates nothing holds %zu", b, need_bytes, kScratchBytes);
@@ -1684,7 +1710,8 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
     const int nq = D.Hq * D.d;
     const int npages_max = (max_len + 1 + kPageTokens - 1) / kPageTokens;
     int CP = 0;
-    const int nch = attention_plan(st, b, max_len, sum_pages, &CP);
+    bool per_wave = false;
+    const int nch = attention_plan(st, b, max_len, sum_pages, mfma::compute_units(), &CP, &per_wave);
     Work W;     // the buffers the step works in: the stage's own, or carved from the static per-GPU scratch
     if (!static_scratch) {
       W.x = st->x; W.rope_cs = st->rope_cs; W.m_xn_t = st->m_xn_t; W.m_q = st->m_q; W.m_attn_t = st->m_attn_t;
@@ -1716,7 +1743,7 @@ int decode_rows(pipemax_stage_t* st, int mb, const std::vector<int>& sel, const 
         mfma::attention(cs, D, l, b, W.m_q, (const uint16_t*)st->gpu_pool, M.d_table, M.d_ctx, W.m_part_o,
                         W.m_part_ml, CP, nch, W.m_cnt_attn, W.m_attn_t,
                         M.d_table + (size_t)st->cfg.max_seqs_per_mb * D.max_pages, tp ? tp->a : nullptr,
-                        tp ? tp->b : nullptr);
+                        tp ? tp->b : nullptr, per_wave);
       }
     };
     if (b <= kFusedRows) {
@@ -2130,15 +2157,18 @@ int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, 
 }
 
 int pipemax_plan_attention_chunks(int n_seqs, int n_kv_heads, int max_ctx_tokens, int64_t sum_pages,
-                                  int32_t* chunk_pages, int32_t* n_chunks) {
-  if (!chunk_pages || !n_chunks || n_seqs < 1 || n_kv_heads < 1 || max_ctx_tokens < 1 || sum_pages < 1)
+                                  int compute_units, int32_t* chunk_pages, int32_t* n_chunks, int32_t* wave_per_item) {
+  if (!chunk_pages || !n_chunks || !wave_per_item || n_seqs < 1 || n_kv_heads < 1 || max_ctx_tokens < 1 ||
+      sum_pages < 1 || compute_units < 1)
     PMX_FAIL(PIPEMAX_ERR_ARG, "plan_attention_chunks: positive counts");
   pipemax_stage tmp;
   tmp.D.Hkv = n_kv_heads;
   tmp.nch_alloc = (((max_ctx_tokens + kPageTokens - 1) / kPageTokens) + 7) / 8;
   int cp = 0;
-  *n_chunks = attention_plan(&tmp, n_seqs, max_ctx_tokens - 1, sum_pages, &cp);
+  bool pw = false;
+  *n_chunks = attention_plan(&tmp, n_seqs, max_ctx_tokens - 1, sum_pages, compute_units, &cp, &pw);
   *chunk_pages = cp;
+  *wave_per_item = pw ? 1 : 0;
   return PIPEMAX_OK;
 }
 

@@ -174,19 +174,26 @@ def test_attention_chunk_plan_covers_the_context_with_even_chunks(lib):
     for n_seqs, hkv, tokens in ((256, 8, 2049), (256, 8, 4097), (64, 8, 1025), (1, 1, 1), (1, 8, 40000), (3, 1, 3000),
                                 (128, 8, 4100), (256, 8, 4096), (2, 2, 4113), (7, 4, 257 * 16), (5, 8, 8193)):
         total = n_seqs * pages(tokens)
-        cp, nch = lib.plan_attention_chunks(n_seqs, hkv, tokens, total)
+        cp, nch, per_wave = lib.plan_attention_chunks(n_seqs, hkv, tokens, total)
         npg = pages(tokens)
-        assert 8 <= cp <= 256 and nch >= 1, (n_seqs, hkv, tokens, cp, nch)
+        assert per_wave == (n_seqs * hkv >= 4 * 256)
+        assert 8 <= cp and (per_wave or cp <= 256) and nch >= 1, (n_seqs, hkv, tokens, cp, nch)
         assert cp * nch >= npg, (n_seqs, hkv, tokens, cp, nch)
         assert nch == -(-npg // cp)
         last = npg - (nch - 1) * cp                     # pages of the last chunk
         assert last >= 1 and (cp - last <= nch or cp == 8), (n_seqs, hkv, tokens, cp, nch, last)
-    assert lib.plan_attention_chunks(256, 8, 2049, 256 * 129) == (129, 1)
-    assert lib.plan_attention_chunks(256, 8, 4097, 256 * 257) == (129, 2)
-    assert lib.plan_attention_chunks(64, 8, 1025, 64 * 65) == (65, 1)
+    # uniform batches with enough (sequence, head) pairs: a wave per pair, the whole context in one chunk
+    assert lib.plan_attention_chunks(256, 8, 2049, 256 * 129) == (129, 1, True)
+    assert lib.plan_attention_chunks(256, 8, 4097, 256 * 257) == (257, 1, True)
+    # on a chip with more compute units the same step goes to work-groups of four waves, at most 256 pages each
+    assert lib.plan_attention_chunks(256, 8, 2049, 256 * 129, 1024) == (129, 1, False)
+    assert lib.plan_attention_chunks(256, 8, 4097, 256 * 257, 1024) == (129, 2, False)
+    assert lib.plan_attention_chunks(64, 8, 1025, 64 * 65) == (65, 1, False)
     # a ragged batch whose longest sequence would outlast everything else is cut into several chunks
-    cp, nch = lib.plan_attention_chunks(3, 1, 3000, pages(3000) + pages(41) + pages(1026))
+    cp, nch, _ = lib.plan_attention_chunks(3, 1, 3000, pages(3000) + pages(41) + pages(1026))
     assert nch > 1
+    cp, nch, per_wave = lib.plan_attention_chunks(128, 8, 4097, 127 * pages(1600) + 257)
+    assert per_wave and nch > 1 and cp * nch >= 257
     import pytest
     with pytest.raises(lib.PipemaxError):
         lib.plan_attention_chunks(0, 8, 100, 7)

@@ -197,22 +197,47 @@ def _mid_shape(**kw):
     return StageShape(**base)
 
 
+class _attn_kernel:
+    """Selects the decode attention kernel of stages created inside the block (the library reads the variable when a
+    stage is created): "wave" = a wave per (chunk, KV head, sequence) item, "group" = a work-group per item, None =
+    the library's own choice by launch size."""
+    def __init__(self, which):
+        self.which = which
+
+    def __enter__(self):
+        import os
+        self.old = os.environ.get("PIPEMAX_ATTN_KERNEL")
+        if self.which is None:
+            os.environ.pop("PIPEMAX_ATTN_KERNEL", None)
+        else:
+            os.environ["PIPEMAX_ATTN_KERNEL"] = self.which
+
+    def __exit__(self, *a):
+        import os
+        if self.old is None:
+            os.environ.pop("PIPEMAX_ATTN_KERNEL", None)
+        else:
+            os.environ["PIPEMAX_ATTN_KERNEL"] = self.old
+
+
 def _ragged_ctx(shape, syn):
     ctx = {mb: syn.ctx_lens(mb).copy() for mb in range(shape.n_microbatches)}
     ctx[0][:6] = [0, 1, 15, 16, 17, 300]         # empty prompt, page-boundary cases, the longest
     return ctx
 
 
-def test_bf16_matrix_core_path_ragged():
+@pytest.mark.parametrize("attn", ["group", "wave"])
+def test_bf16_matrix_core_path_ragged(attn):
     """bf16 stage on the matrix-core kernels: ragged batch (20 rows: one partial 32-row tile), ragged
     contexts including an empty prompt and page-boundary lengths, several GEMM tiles and attention
-    chunks, 3 micro-batches streamed through 2 arenas."""
+    chunks, 3 micro-batches streamed through 2 arenas; with either attention kernel."""
     from paper_2605_02189_amd import binding as pm
     shape = _mid_shape()
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
     syn = SynthInputs(shape, seed=2, pool_elems=1 << 23, gain_jitter=0.1)
-    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=_ragged_ctx(shape, syn)).load()
+    with _attn_kernel(attn):
+        runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=_ragged_ctx(shape, syn)).load()
     assert runner.stage.get_stats()["engine"] == 1
     orc = _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-2, tol_delta=3e-2)
     check_tables(runner)
@@ -294,8 +319,10 @@ def test_bf16_generic_path_matches_oracle_and_matrix_core_path():
     runner.stage.destroy()
 
 
-def test_long_context_many_chunks_and_wide_group():
-    """One long sequence next to short ones (split-K load balance), G = 8 query heads per KV head."""
+@pytest.mark.parametrize("attn", ["group", "wave"])
+def test_long_context_many_chunks_and_wide_group(attn):
+    """One long sequence next to short ones (split-K load balance), G = 8 query heads per KV head; with either
+    attention kernel (the wave-per-item kernel merges the chunks of the 188-page context through its partials)."""
     from paper_2605_02189_amd import binding as pm
     from paper_2605_02189_amd.synth_inputs import SynthInputs
     from paper_2605_02189_amd.harness import StageRunner
@@ -303,7 +330,8 @@ def test_long_context_many_chunks_and_wide_group():
                        seqs_per_mb=3, decode_steps=3, ctx_hi=3000)
     syn = SynthInputs(shape, seed=4, pool_elems=1 << 23, gain_jitter=0.1)
     ctx = {0: np.array([2999, 40, 1025], dtype=np.int32)}
-    runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx).load()
+    with _attn_kernel(attn):
+        runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx).load()
     assert runner.stage.get_stats()["engine"] == 1
     _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-2, tol_delta=3e-2)
     runner.stage.destroy()
@@ -736,13 +764,15 @@ def test_alias_microbatches_move_the_same_bytes():
     assert traffic[2] == traffic[4]
 
 
-def test_split_merges_are_bit_identical_from_run_to_run():
+@pytest.mark.parametrize("attn", ["group", "wave"])
+def test_split_merges_are_bit_identical_from_run_to_run(attn):
     """The in-kernel merges of split-K partials (GEMM splits summed by the last arriving work-group, attention chunks
     merged by the last arriver of a (sequence, KV head)) publish their partials with agent-scope atomics and an
     arrival counter instead of a device-wide fence.  Whatever the arrival order, the sums are taken in split order,
     so the same inputs must give the same bits every time, also with thousands of work-groups of all XCDs in flight:
     a stale or torn partial would show as a differing bit.  40 consecutive steps, each with 2 to 4 GEMM splits over 64 to 96 column
-    blocks and up to 24 attention chunks per sequence (one 3000-token context among short ones, 8-page chunks)."""
+    blocks and up to 24 attention chunks per sequence (one 3000-token context among short ones, 8-page chunks), merged
+    by the last work-group ("group") or the last wave ("wave") to arrive."""
     torch = _torch()
     import os
     from paper_2605_02189_amd import binding as pm
@@ -755,8 +785,9 @@ def test_split_merges_are_bit_identical_from_run_to_run():
     ctx[0][0] = 3000
     os.environ["PIPEMAX_ATTN_CHUNK_PAGES"] = "8"
     try:
-        runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
-                             flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
+        with _attn_kernel(attn):
+            runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
+                                 flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
     finally:
         del os.environ["PIPEMAX_ATTN_CHUNK_PAGES"]
     st = runner.stage
@@ -773,8 +804,9 @@ def test_split_merges_are_bit_identical_from_run_to_run():
     # the twin run: same inputs, same 40 steps, a fresh stage; step r of both runs must agree bit for bit
     os.environ["PIPEMAX_ATTN_CHUNK_PAGES"] = "8"
     try:
-        runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
-                             flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
+        with _attn_kernel(attn):
+            runner = StageRunner(shape, syn, sigma=0.0, ctx_lens=ctx, gpu_pool_all_resident=True,
+                                 flags=pm.FLAG_NO_WRITEBACK, steps=64).load()
     finally:
         del os.environ["PIPEMAX_ATTN_CHUNK_PAGES"]
     st = runner.stage
