@@ -337,7 +337,13 @@ def run_config(name, args, *, light=False):
         s_plain = st.get_stats()
         kms, kl = s1["kernel_ms"], s1["kernel_launches"]
         achieved = bytes_attn / max(attn_launches, 1) / (attn_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_attn (GQA paged decode attention, split-K pass)",
+        lens_now = st.get_ctx_lens(0)
+        _cp, _nch, per_wave = pm.plan_attention_chunks(
+            b, shape.n_kv_heads, int(lens_now.max()) + 1, int(((lens_now + 1 + 15) // 16).sum()),
+            torch.cuda.get_device_properties(0).multi_processor_count)
+        roofline = {"bound": "hbm",
+                    "kernel": ("k_attn_w (GQA paged decode attention, a wave per (chunk, KV head, sequence) item)" if per_wave
+                               else "k_attn (GQA paged decode attention, a work-group per (chunk, KV head, sequence) item)"),
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(name),
                     "traffic_measured_on_algorithmic_bytes": measured_traffic(name, "algorithmic_bytes_per_launch"),
