@@ -373,7 +373,7 @@ __global__ __launch_bounds__(256) void k_gemm_l(const uint4* __restrict__ Xt, co
 //   k ranges of an even number of k-steps; the X operand is readable up to the end of the last row block, whose
 //   rows >= M are computed and not stored.
 // =================================================================================================
-template <int R, int RH>
+template <int R, int RH, bool WNT>
 __global__ __launch_bounds__(256 * RH, 3 - RH) void k_gemm_l5(const uint4* __restrict__ Xt, const uint4* __restrict__ Wt,
                                                          float* __restrict__ part, int M, int N, int KT, int ksp,
                                                          int64_t split_stride, uint16_t* __restrict__ act_t, int n_z,
@@ -431,8 +431,14 @@ __global__ __launch_bounds__(256 * RH, 3 - RH) void k_gemm_l5(const uint4* __res
       src = wp + ((int64_t)tile * KT + 2 * s + kk) * 64;
       dst += kXs + g * 64;
     }
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                     (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+    // WNT: the launch has one row block, so every weight line is used once: requested non-temporal (cache policy
+    // bit 1), it does not claim an L2 line; the activations, which every column block re-reads, stay ordinary loads
+    if (WNT && i >= 2)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)dst, 16, 0, 2);
+    else
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
   };
   // Every step issues exactly LPS loads, so "at most LPS (R - 2) outstanding" always means that the next
   // step's slot has landed; past the end of the k range the loads re-fetch the last step into a slot that is
@@ -1568,7 +1574,7 @@ static void gemm_wn(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, float
 
 // 0 = not asked yet, 1 = granted, 2 = refused: more than 64 KiB of dynamic LDS must be allowed once per device
 // and kernel
-template <int R, int RH>
+template <int R, int RH, bool WNT>
 static bool ring_allowed(int lds) {
   static std::atomic<int> state[64];
   int dev = 0;
@@ -1576,7 +1582,7 @@ static bool ring_allowed(int lds) {
   dev = std::min(std::max(dev, 0), 63);
   int st = state[dev].load(std::memory_order_acquire);
   if (st == 0) {
-    st = hipFuncSetAttribute((const void*)k_gemm_l5<R, RH>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) ==
+    st = hipFuncSetAttribute((const void*)k_gemm_l5<R, RH, WNT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) ==
                  hipSuccess ? 1 : 2;
     if (st == 2) (void)hipGetLastError();
     state[dev].store(st, std::memory_order_release);
@@ -1598,7 +1604,13 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
   const bool even = KT % 2 == 0 && (S == 1 || ksp % 2 == 0);
   constexpr int R2 = 4, kLds2 = R2 * 2048 * 16;       // 256-row blocks: 4 slots of 32 KiB
   constexpr int R1 = 3, kLds1 = R1 * 1536 * 16;       // 128-row block: 3 slots of 24 KiB, two work-groups per CU
-  if (even && !four_waves && ring_allowed<R2, 2>(kLds2) && ring_allowed<R1, 1>(kLds1)) {
+  // One row block: every weight line is used once, and the large matrices are requested non-temporal (256 rows of the
+  // 70B shape: gate/up 235 -> 226 us, down unchanged; QKV and O, whose 134-168 MB were 2-3 % slower that way, are
+  // not; on a box whose GEMMs ran 20 % slower than usual the gain was 13 % on gate/up and 23 % on down).
+  static const bool no_wnt_env = getenv("PIPEMAX_GEMM_NO_WNT") != nullptr;
+  const bool no_wnt = no_wnt_env || (int64_t)K * N * 2 < ((int64_t)256 << 20);
+  if (even && !four_waves && ring_allowed<R2, 2, false>(kLds2) && ring_allowed<R1, 1, false>(kLds1) &&
+      ring_allowed<R2, 2, true>(kLds2) && ring_allowed<R1, 1, true>(kLds1)) {
     // blocks of 256 rows along grid.z; a last block of at most 128 rows takes the 128-row tile
     const int rem = M % 256;
     const int tall = (rem == 0 || rem > 128) ? (M + 255) / 256 : M / 256;
@@ -1607,18 +1619,25 @@ static void gemm_large(hipStream_t s, const uint16_t* Xt, const uint16_t* Wt, fl
       int G = 1;
       for (int c = 8; c >= 1; --c)
         if ((n_x / 8) % c == 0) { G = c; break; }
-      hipLaunchKernelGGL((k_gemm_l5<R2, 2>), dim3(n_x * tall, S, 1), dim3(512), kLds2, s, (const uint4*)Xt,
+      hipLaunchKernelGGL((k_gemm_l5<R2, 2, false>), dim3(n_x * tall, S, 1), dim3(512), kLds2, s, (const uint4*)Xt,
                          (const uint4*)Wt, part, M, N, KT, ksp, stride, act_t, tall, G);
-    } else if (tall)
-      hipLaunchKernelGGL((k_gemm_l5<R2, 2>), dim3(n_x, S, tall), dim3(512), kLds2, s, (const uint4*)Xt,
+    } else if (tall == 1 && !no_wnt)      // one row block: the weights are read once
+      hipLaunchKernelGGL((k_gemm_l5<R2, 2, true>), dim3(n_x, S, 1), dim3(512), kLds2, s, (const uint4*)Xt,
+                         (const uint4*)Wt, part, M, N, KT, ksp, stride, act_t, 0, 0);
+    else if (tall)
+      hipLaunchKernelGGL((k_gemm_l5<R2, 2, false>), dim3(n_x, S, tall), dim3(512), kLds2, s, (const uint4*)Xt,
                          (const uint4*)Wt, part, M, N, KT, ksp, stride, act_t, 0, 0);
     if (tall * 256 < M) {
       const uint4* Xr = (const uint4*)Xt + (int64_t)tall * 8 * KT * 64;
       float* pr = part + (int64_t)tall * 256 * N;
       // the A-tiled output of these rows starts at row tile tall * 8 of the next GEMM's operand
       uint16_t* ar = act_t ? act_t + (int64_t)tall * 8 * (N >> 5) * 512 : nullptr;
-      hipLaunchKernelGGL((k_gemm_l5<R1, 1>), dim3(N / 256, S, 1), dim3(256), kLds1, s, Xr, (const uint4*)Wt, pr,
-                         M - tall * 256, N, KT, ksp, stride, ar, 0, 0);
+      if (tall == 0 && !no_wnt)
+        hipLaunchKernelGGL((k_gemm_l5<R1, 1, true>), dim3(N / 256, S, 1), dim3(256), kLds1, s, Xr, (const uint4*)Wt, pr,
+                           M - tall * 256, N, KT, ksp, stride, ar, 0, 0);
+      else
+        hipLaunchKernelGGL((k_gemm_l5<R1, 1, false>), dim3(N / 256, S, 1), dim3(256), kLds1, s, Xr, (const uint4*)Wt, pr,
+                           M - tall * 256, N, KT, ksp, stride, ar, 0, 0);
     }
     return;
   }
