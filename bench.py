@@ -342,7 +342,9 @@ def run_config(name, args, *, light=False):
             b, shape.n_kv_heads, int(lens_now.max()) + 1, int(((lens_now + 1 + 15) // 16).sum()),
             torch.cuda.get_device_properties(0).multi_processor_count)
         roofline = {"bound": "hbm",
-                    "kernel": ("k_attn_w (GQA paged decode attention, a wave per (chunk, KV head, sequence) item)" if per_wave
+                    "kernel": ("k_attention (shape-generic paged decode attention, one work-group per query head)"
+                               if st.get_stats()["engine"] == 0 else
+                               "k_attn_w (GQA paged decode attention, a wave per (chunk, KV head, sequence) item)" if per_wave
                                else "k_attn (GQA paged decode attention, a work-group per (chunk, KV head, sequence) item)"),
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(name),
