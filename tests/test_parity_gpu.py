@@ -337,6 +337,29 @@ def test_long_context_many_chunks_and_wide_group(attn):
     runner.stage.destroy()
 
 
+def test_one_wave_streams_a_context_of_several_windows():
+    """The wave-per-item attention keeps the page ids of 256 pages in registers and goes through a longer item window
+    by window: contexts of 9000 and 5000 tokens as single items (563 and 313 pages: three and two windows, the last
+    ones partial) next to a short one."""
+    import os
+    from paper_2605_02189_amd import binding as pm
+    from paper_2605_02189_amd.synth_inputs import SynthInputs
+    from paper_2605_02189_amd.harness import StageRunner
+    shape = _mid_shape(n_layers=1, n_q_heads=8, n_kv_heads=1, hidden=512, ffn=1024, n_microbatches=1,
+                       seqs_per_mb=3, decode_steps=3, ctx_hi=9100)
+    syn = SynthInputs(shape, seed=5, pool_elems=1 << 23, gain_jitter=0.1)
+    ctx = {0: np.array([9000, 40, 5000], dtype=np.int32)}
+    os.environ["PIPEMAX_ATTN_CHUNK_PAGES"] = "1024"
+    try:
+        with _attn_kernel("wave"):
+            runner = StageRunner(shape, syn, flags=pm.FLAG_CAPTURE_LAYERS, ctx_lens=ctx).load()
+    finally:
+        del os.environ["PIPEMAX_ATTN_CHUNK_PAGES"]
+    assert runner.stage.get_stats()["engine"] == 1
+    _run_cyclic_and_compare(runner, syn, shape, shape.decode_steps, tol_layer=1e-2, tol_delta=3e-2)
+    runner.stage.destroy()
+
+
 def test_offload_then_prefetch_is_a_bit_identical_round_trip():
     """Bytes written to the host replica come back from the GPU pages unchanged, wherever the pages
     land; evicting and prefetching again (into other physical pages) changes nothing."""
