@@ -1686,6 +1686,7 @@ void attention(hipStream_t s, const Dims& D, int layer, int b, const uint16_t* q
   constexpr int NW = kAttnWaves;
   const size_t lds = (size_t)NW * D.G * kORow * sizeof(float);
   const int n_items = max_chunks * D.Hkv * b;
+  if (chunk_pages > 64 * NW) per_wave = true;      // beyond the reach of a work-group's page ids: the wave kernel takes any length
   if (per_wave) {
     const unsigned grid = (unsigned)((n_items + NW - 1) / NW);
     if (ev_start && ev_stop)
