@@ -236,6 +236,10 @@ def run_config(name, args, *, light=False):
                       flags=(pm.FLAG_NO_WRITEBACK if args.no_writeback else 0)
                       | (pm.FLAG_DEVICE_LAYER_MAJOR if args.device_layout == "layer" else 0))
     st = run.stage
+    xfer = None
+    if args.orchestrated:      # the prefetch goes through the transfer orchestrator in chunks of that many MiB
+        xfer = pm.Xfer(device=0, max_inflight_bulk=2, chunk_bytes=int(args.orchestrated) << 20)
+        st.attach_xfer(xfer)
     run.load()
     hin = [run.hidden_tensor(mb, mb) for mb in range(n)]
     hout = [torch.empty_like(h) for h in hin]
@@ -454,6 +458,9 @@ def run_config(name, args, *, light=False):
             "reachable": bool(hbm_side),
         }
     res.update(legs=legs, roofline=roofline, sweep=sweep, syn=syn, ctx0=run.ctx0[0])
+    if xfer is not None:
+        st.attach_xfer(None)
+        xfer.destroy()
     st.destroy()
     del run
     torch.cuda.empty_cache()
@@ -475,6 +482,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the sweep over the streamed fraction")
     ap.add_argument("--no-also", action="store_true", help="default run: skip the compact C4 run")
     ap.add_argument("--no-writeback", action="store_true", help="diagnostic: skip the KV write-back (invalid as a result)")
+    ap.add_argument("--orchestrated", type=int, default=0, metavar="MiB",
+                    help="route the KV prefetch through the transfer orchestrator in chunks of this many MiB (block-first pool only)")
     ap.add_argument("--arenas", type=int, default=2,
                     help="GPU room for this many streamed parts: 2 = Eq. 3 (the prefetch overwrites D_i-1), 3 = it "
                          "overwrites D_i-2 and never waits for the compute stream")
@@ -516,7 +525,9 @@ def main():
                    "sigma": args.sigma, "schedule": "cyclic (execute D_i, overwrite D_i-1, prefetch D_i+1)",
                    "inactive_kv": "pinned host memory", "page_tokens": 16, "gpu_arenas_for_streamed_kv": args.arenas,
                    "gpu_pool_layout": "[layer][page]" if args.device_layout == "layer" else "block-first pages",
-                   "prefetch_issue": "stage's prefetch worker, whole page runs on the prefetch stream"},
+                   "prefetch_issue": (f"transfer orchestrator, chunks of {args.orchestrated} MiB, two in flight"
+                                      if args.orchestrated else
+                                      "stage's prefetch worker, whole page runs on the prefetch stream")},
         "roofline": r["roofline"], "legs": r["legs"],
     }
     if r["sweep"] is not None:
