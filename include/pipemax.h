@@ -392,7 +392,7 @@ int pipemax_plan_gemm_splits(int rows, int n_cols, int k, int32_t* plan_splits, 
 /* Plan of the decode attention for a step of n_seqs sequences whose longest context is max_ctx_tokens tokens (the new
  * token included) and whose contexts cover sum_pages pages in all, on a GPU of compute_units compute units.  The
  * attention's items are (chunk of the context, KV head, sequence).  *wave_per_item = 1: every item is streamed by one
- * wave (chosen when n_seqs * n_kv_heads >= 4 * compute_units); 0: by a work-group of four waves that share its pages
+ * wave (chosen when n_seqs * n_kv_heads >= 2 * compute_units); 0: by a work-group of four waves that share its pages
  * (then *chunk_pages <= 256).  *chunk_pages = pages per item, *n_chunks = chunks the longest sequence is cut into.
  * Chunks are even: a context one page longer than an item takes becomes two halves, not a full chunk and a one-page
  * chunk.  Pure host arithmetic (the stage's own planner, without the PIPEMAX_ATTN_CHUNK_PAGES / PIPEMAX_ATTN_KERNEL

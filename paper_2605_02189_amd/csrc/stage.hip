@@ -1391,14 +1391,14 @@ int attention_plan(const pipemax_stage* st, int b, int max_len, int64_t sum_page
                    bool* per_wave) {
   const Dims& D = st->D;
   *per_wave = false;
-  // A wave per item when the (sequence, KV head) pairs alone give every compute unit four waves: the waves then
+  // A wave per item when the (sequence, KV head) pairs alone give every compute unit two waves: the waves then
   // share nothing and never wait for each other (256 x 8 pairs of 129 pages: 334 against 348 us per launch; 128 x 8
-  // ragged pairs: 213 against 217; 64 x 8 pairs of 65 pages, where the work-group kernel's four waves per pair are
-  // what fills the chip: 55.8 against 52.4).  A wave streams a page in about 1 us at best (2.6 us when 2048 of them
-  // share the chip); a context that would take one wave longer than all pages take the chip (6.5 TB/s, 8 KiB per page
-  // and head) is split evenly -- and with it every sequence longer than the resulting chunk (128 ragged sequences of
-  // 512..4096 tokens: chunks of 129 pages 213 us, of 86 pages 221 us).
-  if (st->attn_worker == 1 || (st->attn_worker == 0 && b * D.Hkv >= 4 * cus)) {
+  // ragged pairs: 213 against 217; 64 x 8 pairs of 65-82 pages, in two chunks each: 51.7 against 53.6).  A wave streams
+  // a page in about 1 us at best (2.6 us when 2048 of them share the chip); a context that would take one wave longer
+  // than all pages take the chip (6.5 TB/s, 8 KiB per page and head) is split evenly -- and with it every sequence
+  // longer than the resulting chunk (128 ragged sequences of 512..4096 tokens: chunks of 129 pages 213 us, of 86
+  // pages 221 us; the 64 x 8 pairs in one / two / three chunks: 55.0 / 51.7 / 57-61 us).
+  if (st->attn_worker == 1 || (st->attn_worker == 0 && b * D.Hkv >= 2 * cus)) {
     const int npages = (max_len + 1 + kPageTokens - 1) / kPageTokens;
     const double t_all_us = (double)D.Hkv * (double)sum_pages * 8192.0 / 6.5e6;
     int CP = std::min(npages, std::max(16, (int)(t_all_us / 1.0)));
