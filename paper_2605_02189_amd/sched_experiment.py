@@ -108,6 +108,7 @@ def main():
             if t == args.warmup_iters:
                 st.sync()
                 st.reset_stats()
+                lens0 = np.concatenate([st.get_ctx_lens(k) for k in range(n)])
                 t0 = time.perf_counter()
             d = sched.iterate(st, t, hin.data_ptr(), hout.data_ptr(), stream.cuda_stream)
             if t < args.warmup_iters:
@@ -122,10 +123,14 @@ def main():
         st.sync()
         dt = time.perf_counter() - t0
         stats = st.get_stats()
+        # tokens every request decoded in the timed iterations: a request that stays on the host never executes
+        progress = np.concatenate([st.get_ctx_lens(k) for k in range(n)]) - lens0
         sched.destroy()
         st.destroy()
         return {"tokens_per_s": tok / dt, "ms_per_iter": dt / args.iters * 1e3, "mean_batch": float(np.mean(bsz)),
-                "min_batch": int(min(bsz)), "prefetch_tokens_per_iter": pf / args.iters,
+                "min_batch": int(min(bsz)), "requests_never_executed": int((progress == 0).sum()),
+                "min_tokens_per_request": int(progress.min()), "median_tokens_per_request": float(np.median(progress)),
+                "prefetch_tokens_per_iter": pf / args.iters,
                 "budget_tokens_per_iter": bud / args.iters, "steady_frac": steady / args.iters,
                 "h2d_gb_per_iter": stats["h2d_bytes"] / args.iters / 1e9,
                 "h2d_copies_per_iter": stats["h2d_copies"] / args.iters,
